@@ -1,0 +1,110 @@
+"""Pins for the fp64 SpMM oracle: nothing here is derived from the oracle itself."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import literal
+from _util import csr_from_rows, random_csr, f16
+
+
+def test_f16_decode_matches_numpy_for_every_bit_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    mine = np.array([oracle._load().orc_f16_to_f64(int(b)) for b in bits[::3]])
+    lit = np.array([literal.f16_bits_to_float(int(b)) for b in bits[::3]])
+    np.testing.assert_array_equal(mine, ref[::3])
+    np.testing.assert_array_equal(lit, ref[::3])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_matches_dense_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    M, K, N = rng.integers(1, 64, 3)
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.2)
+    B = f16(rng.standard_normal((K, N)))
+    C, bound = oracle.spmm(rowptr, colidx, vals, B)
+    Cd, bd = literal.spmm_dense(M, K, rowptr, colidx, vals, B)
+    np.testing.assert_allclose(C, Cd, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(bound, bd, rtol=0, atol=1e-12)
+
+
+def test_matches_numpy_matmul_on_transposed_operand_shapes():
+    # non-square, asymmetric: a transposed operand or swapped index would not survive this
+    rng = np.random.default_rng(42)
+    M, K, N = 7, 13, 5
+    A = np.zeros((M, K), np.float16)
+    mask = rng.random((M, K)) < 0.4
+    A[mask] = rng.uniform(-2, 2, mask.sum()).astype(np.float16)
+    rows = [np.nonzero(mask[i])[0].tolist() for i in range(M)]
+    rowptr, colidx, vals = csr_from_rows(rows, A[mask])
+    Bf = rng.uniform(-1, 1, (K, N)).astype(np.float16)
+    C, bound = oracle.spmm(rowptr, colidx, vals, Bf.view(np.uint16))
+    np.testing.assert_allclose(C, A.astype(np.float64) @ Bf.astype(np.float64), atol=1e-13)
+    np.testing.assert_allclose(bound, np.abs(A).astype(np.float64) @ np.abs(Bf).astype(np.float64), atol=1e-13)
+
+
+def test_identity_gives_B_exactly():
+    rng = np.random.default_rng(1)
+    n, N = 50, 8
+    rowptr, colidx, vals = csr_from_rows([[i] for i in range(n)], np.ones(n))
+    B = f16(rng.standard_normal((n, N)))
+    C, _ = oracle.spmm(rowptr, colidx, vals, B)
+    np.testing.assert_array_equal(C, B.view(np.float16).astype(np.float64))
+
+
+def test_permutation_matrix_permutes_rows_of_B():
+    rng = np.random.default_rng(2)
+    n, N = 40, 6
+    p = rng.permutation(n)
+    rowptr, colidx, vals = csr_from_rows([[int(p[i])] for i in range(n)], np.ones(n))
+    B = f16(rng.standard_normal((n, N)))
+    C, _ = oracle.spmm(rowptr, colidx, vals, B)
+    np.testing.assert_array_equal(C, B.view(np.float16).astype(np.float64)[p])
+
+
+def test_all_ones_counts_row_lengths():
+    rng = np.random.default_rng(3)
+    rowptr, colidx, _ = random_csr(rng, 30, 40, 0.3)
+    vals = f16(np.ones(len(colidx)))
+    B = f16(np.ones((40, 4)))
+    C, bound = oracle.spmm(rowptr, colidx, vals, B)
+    expect = np.repeat(np.diff(rowptr)[:, None], 4, 1).astype(np.float64)
+    np.testing.assert_array_equal(C, expect)
+    np.testing.assert_array_equal(bound, expect)
+
+
+def test_linearity_in_B_exact_on_small_integers():
+    rng = np.random.default_rng(4)
+    rowptr, colidx, _ = random_csr(rng, 20, 25, 0.3)
+    vals = f16(rng.integers(-4, 5, len(colidx)))
+    B1 = rng.integers(-8, 9, (25, 6)).astype(np.float64)
+    B2 = rng.integers(-8, 9, (25, 6)).astype(np.float64)
+    alpha = 4.0
+    C1, _ = oracle.spmm(rowptr, colidx, vals, f16(B1))
+    C2, _ = oracle.spmm(rowptr, colidx, vals, f16(B2))
+    C12, _ = oracle.spmm(rowptr, colidx, vals, f16(alpha * B1 + B2))
+    np.testing.assert_array_equal(C12, alpha * C1 + C2)
+
+
+def test_row_subset_and_empty_rows():
+    rng = np.random.default_rng(5)
+    rowptr, colidx, vals = random_csr(rng, 30, 30, 0.2, empty_row_frac=0.3)
+    B = f16(rng.standard_normal((30, 5)))
+    C, bound = oracle.spmm(rowptr, colidx, vals, B)
+    rows = np.array([29, 0, 7, 7, 13])
+    Cs, bs = oracle.spmm(rowptr, colidx, vals, B, rows=rows)
+    np.testing.assert_array_equal(Cs, C[rows])
+    np.testing.assert_array_equal(bs, bound[rows])
+    empty = np.nonzero(np.diff(rowptr) == 0)[0]
+    assert len(empty) and not C[empty].any() and not bound[empty].any()
+
+
+def test_within_bound_accepts_and_rejects():
+    C_ref = np.array([[1.0, -2.0]])
+    bound = np.array([[1.0, 2.0]])
+    ok, _ = oracle.within_bound(np.array([[1.0 + 2e-3, -2.0]], np.float32), C_ref, bound)
+    assert ok
+    ok, ratio = oracle.within_bound(np.array([[1.0 + 3e-3, -2.0]], np.float32), C_ref, bound)
+    assert not ok and ratio > 1
+    ok, _ = oracle.within_bound(np.array([[np.nan, -2.0]], np.float32), C_ref, bound)
+    assert not ok

@@ -1,0 +1,217 @@
+/*
+ * acc_spmm.h -- C ABI of the MI355X (gfx950) SpMM library.
+ *
+ * Computes C = A.B with A sparse M x K (given once as CSR with fp16 values), B dense
+ * K x N fp16 and C dense M x N fp32 (problem statement: Acc-SpMM paper, Section 5, first
+ * sentence; CSR input: Section 2.2).  The work is split as the paper's overview
+ * (Section 3.1) splits it: an offline stage that reorders rows, translates A into the
+ * bitmap tile format and balances the load (acc_spmm_plan), and one runtime kernel
+ * (acc_spmm_execute).
+ *
+ * Conventions for every entry point:
+ *  - plain C types only; "HOST" / "DEVICE" says where a pointer must live;
+ *  - fp16 data is passed as IEEE binary16 bit patterns (uint16_t on the host);
+ *  - no entry point throws or aborts: failures return NULL or a negative acc_spmm_status,
+ *    and acc_spmm_last_error() gives the message of the calling thread's last failure;
+ *  - the library needs a gfx950 device; there is no CPU fallback.
+ */
+#ifndef ACC_SPMM_H
+#define ACC_SPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#define ACC_SPMM_API __attribute__((visibility("default")))
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ACC_SPMM_OK = 0,
+    ACC_SPMM_ERR_INVALID_ARG = -1, /* null pointer, negative size, bad option value     */
+    ACC_SPMM_ERR_INVALID_CSR = -2, /* rowptr not monotone / rowptr[M] != nnz / column   */
+                                   /* out of range / duplicate column inside a row      */
+    ACC_SPMM_ERR_UNSUPPORTED = -3, /* N or tile geometry the kernels do not cover       */
+    ACC_SPMM_ERR_OOM = -4,         /* host or device allocation failed                  */
+    ACC_SPMM_ERR_HIP = -5          /* a HIP runtime call failed (message has the name)  */
+} acc_spmm_status;
+
+/* Opaque plan handle, owned by the library; release with acc_spmm_destroy. */
+typedef struct acc_spmm_plan_s acc_spmm_plan_t;
+
+/* Values for acc_spmm_options.reorder and .load_balance */
+enum { ACC_SPMM_OFF = 0, ACC_SPMM_ON = 1, ACC_SPMM_AUTO = 2 };
+
+/*
+ * Plan options.  Zero-initialise, set struct_size = sizeof(acc_spmm_options), then
+ * change what you need; a field left 0 takes its default where "0 = default" is stated.
+ */
+typedef struct {
+    int32_t struct_size;
+    /* Row reordering (Section 3.2, Algorithm 1).  OFF: identity.  ON: always apply.
+     * AUTO (default when struct is NULL): compute it, keep it only if it lowers the number
+     * of tiles (the paper notes in Section 4.3.5 that reordering can lose).
+     * Requires M == K; for M != K the dendrogram step is skipped and the order is the
+     * identity. */
+    int32_t reorder;
+    /* Load balancing (Section 3.5).  OFF: one work item per row window.  ON: always split
+     * heavy windows / pack light ones.  AUTO: apply iff IBD (Eq. 3) > ibd_threshold. */
+    int32_t load_balance;
+    /* Most tiles one work item may hold; heavier windows are split (Section 3.5 uses 32
+     * for 8x8x16 tiles on NVIDIA parts).  0 = default (see acc_spmm_stats.max_tiles_per_item). */
+    int32_t max_tiles_per_item;
+    /* Tile geometry: rows per row window and condensed columns per tile.  0 = default
+     * (16,16), the geometry the execute kernel runs.  (8,8), the paper's geometry
+     * (Section 3.3), is accepted for building and exporting the format only:
+     * acc_spmm_execute returns ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
+    int32_t window_height;
+    int32_t tile_width;
+    /* Leaves per segment in the ordering step's candidate search.  0 = default 1024. */
+    int32_t segment_length;
+    /* IBD threshold for load_balance == AUTO.  0 = default 8 (Section 3.5). */
+    float ibd_threshold;
+    /* Keep a device copy of the input CSR so that acc_spmm_execute_csr_naive works. */
+    int32_t keep_csr;
+    /* Ablation switch: 0 = default (software-pipelined loads, Section 3.4), 1 = issue each
+     * tile's loads only when the tile is computed. */
+    int32_t no_prefetch;
+    /* Ablation switch: 0 = default (streaming stores for C, the counterpart of the
+     * write-through policy of Section 3.4), 1 = plain stores. */
+    int32_t plain_stores;
+} acc_spmm_options;
+
+/* What a plan holds; filled by acc_spmm_plan_stats. */
+typedef struct {
+    int64_t M, K, nnz;
+    int32_t window_height, tile_width;
+    int64_t num_windows;        /* W = ceil(M / window_height)                               */
+    int64_t num_tiles;          /* T = NumTcBlock                                            */
+    int64_t sum_distinct_cols;  /* sum over windows of distinct column indices (B rows read) */
+    int64_t num_tiles_identity; /* T with the identity order (== num_tiles if reorder off)   */
+    int64_t num_items;          /* work items (one wavefront each) in the schedule           */
+    int64_t num_split_windows;  /* windows whose tiles are spread over several items         */
+    int64_t num_partial_slots;  /* partial C tiles (window_height x N fp32) in the workspace */
+    int32_t max_tiles_per_item;
+    int32_t reorder_applied, load_balance_applied;
+    double ibd;                 /* Eq. 3 on the final tile counts                            */
+    double mean_nnz_per_tile;   /* MeanNNZTC (Section 4.3.1) = nnz / T                       */
+    int64_t index_bytes;        /* RowWindowOffset + TCOffset + SparseAToB + TCLocalBit      */
+    int64_t schedule_bytes;     /* work items + permutation                                  */
+    double t_validate_s, t_reorder_s, t_encode_s, t_schedule_s, t_total_s;
+} acc_spmm_stats;
+
+/* Arrays acc_spmm_plan_export can copy out (element type, element count). */
+typedef enum {
+    ACC_SPMM_ARR_PERM = 0,              /* int32  M          new row -> input row           */
+    ACC_SPMM_ARR_IPERM = 1,             /* int32  M          input row -> new row           */
+    ACC_SPMM_ARR_ROW_WINDOW_OFFSET = 2, /* int32  W+1                                       */
+    ACC_SPMM_ARR_TC_OFFSET = 3,         /* int32  T+1                                       */
+    ACC_SPMM_ARR_SPARSE_A_TO_B = 4,     /* int32  T*tile_width                              */
+    ACC_SPMM_ARR_TC_LOCAL_BIT = 5,      /* uint64 T*ceil(window_height*tile_width/64)       */
+    ACC_SPMM_ARR_VALUES = 6,            /* uint16 nnz        fp16 bits in tile order        */
+    ACC_SPMM_ARR_WORK_ITEMS = 7,        /* int32  4*num_items, see acc_spmm_plan_export     */
+    ACC_SPMM_ARR_DENDROGRAM_PARENT = 8  /* int32  M          -1 for roots; empty if reorder */
+                                        /*                   was off                        */
+} acc_spmm_array;
+
+/*
+ * Build a plan with default options (reorder AUTO, load balance AUTO, 16x16 tiles).
+ *   M, K, nnz    shape of A and number of stored entries; 0 <= M, K < 2^31, 0 <= nnz < 2^31
+ *   csr_rowptr   HOST int32[M+1], rowptr[0] == 0, non-decreasing, rowptr[M] == nnz
+ *   csr_colidx   HOST int32[nnz], each in [0,K); order inside a row is free, duplicates
+ *                inside a row are an error
+ *   csr_vals     HOST uint16[nnz], fp16 bit patterns (a stored 0.0 stays a stored entry)
+ * The arrays are only read during the call.  Returns NULL on failure.
+ * The plan lives on the HIP device that is current when this is called.
+ */
+ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                               const int32_t* csr_colidx, const uint16_t* csr_vals);
+
+/* Same, with options (NULL = defaults). */
+ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                                  const int32_t* csr_colidx, const uint16_t* csr_vals,
+                                  const acc_spmm_options* options);
+
+/*
+ * Enqueue C = A.B on `stream` (Algorithm 2's runtime kernel; Section 3.5's split row
+ * windows are combined by a second small kernel on the same stream).
+ *   B       DEVICE fp16, row-major K x N, leading dimension N, 16-byte aligned
+ *   N       16, 32, 64, 128, or a multiple of 128 up to 512
+ *   C       DEVICE fp32, row-major M x N, leading dimension N, 16-byte aligned; every
+ *           element is overwritten (rows without entries become 0); rows are in the
+ *           caller's original order whatever the plan's internal reordering
+ *   stream  hipStream_t, NULL = the default stream
+ * Returns without waiting for the GPU.  Calls on one plan must not overlap in time on
+ * different streams when the plan has split windows (they share one partial-sum
+ * workspace, which the first call with a larger N (re)allocates).
+ */
+ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
+
+/*
+ * acc_spmm_execute with per-kernel timing, for benchmarks: records HIP events on `stream`
+ * around the tile kernel and around the split-window combine kernel, waits for them, and
+ * returns the two durations in milliseconds (combine_ms = 0 when the plan has no split
+ * windows).  Same contract as acc_spmm_execute otherwise, but it blocks the calling thread.
+ */
+ACC_SPMM_API int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C,
+                                        void* stream, float* tiles_ms, float* combine_ms);
+
+/*
+ * Baseline for comparisons: one wavefront per CSR row, fp32 FMA, no tiles, no matrix
+ * cores.  Needs a plan built with keep_csr = 1.  Same B / N / C / stream contract, any N >= 1.
+ */
+ACC_SPMM_API int acc_spmm_execute_csr_naive(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
+
+ACC_SPMM_API void acc_spmm_destroy(acc_spmm_plan_t* plan);
+
+/* Message of the calling thread's last failure; returns its status code (0 if none).
+ * buf may be NULL. */
+ACC_SPMM_API int acc_spmm_last_error(char* buf, size_t len);
+
+ACC_SPMM_API int acc_spmm_plan_stats(const acc_spmm_plan_t* plan, acc_spmm_stats* out);
+
+/*
+ * Bytes the method must move for one execute at width N, counted from the plan
+ * (A values once, A indices once, each window's distinct B rows once, C once), and the
+ * dense flops the matrix cores are issued.  Any output pointer may be NULL.
+ */
+ACC_SPMM_API int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, int64_t* a_bytes, int64_t* b_bytes,
+                          int64_t* c_bytes, int64_t* mfma_flops);
+
+/*
+ * Copy one of the plan's arrays to HOST memory.  Pass host_dst == NULL to get the size in
+ * bytes through *bytes; otherwise *bytes must be at least that size.
+ * Work items are 4 x int32 {w_begin, w_end, t_begin, t_end}:
+ *   w_end >  w_begin : the item owns windows [w_begin, w_end) completely
+ *                      (t_begin, t_end are their first and one-past-last tile);
+ *   w_end <  0       : the item owns tiles [t_begin, t_end) of window w_begin and writes
+ *                      partial slot (-w_end - 1).
+ */
+ACC_SPMM_API int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst, size_t* bytes);
+
+/*
+ * The two host-side stages of acc_spmm_plan, callable on their own (no GPU needed).
+ *
+ * acc_spmm_reorder_host: the row reordering of Section 3.2 (Algorithm 1) for a square
+ * M x M pattern.  csr_rowptr / csr_colidx as for acc_spmm_plan (HOST).  segment_length
+ * 0 = default.  Outputs, HOST int32[M] each: perm (new -> input row), iperm (its inverse),
+ * parent (dendrogram: community each vertex was merged into, -1 for roots; may be NULL).
+ *
+ * acc_spmm_schedule_host: Section 3.5 for 16x16 tiles.  row_window_offset is HOST
+ * int32[W+1].  load_balance / max_tiles_per_item / ibd_threshold as in acc_spmm_options.
+ * *ibd_out receives Eq. 3 (may be NULL).  Work items (4 x int32 each, encoding as for
+ * acc_spmm_plan_export) are written to `items` if it is not NULL; items_capacity is its
+ * capacity in items.  Returns the number of work items, or a negative acc_spmm_status.
+ */
+ACC_SPMM_API int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
+                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent);
+
+ACC_SPMM_API int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,
+                               int32_t max_tiles_per_item, float ibd_threshold, double* ibd_out,
+                               int32_t* items, int64_t items_capacity, int64_t* num_partial_slots);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ACC_SPMM_H */

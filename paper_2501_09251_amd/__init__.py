@@ -1,0 +1,241 @@
+"""Python binding of libaccspmm.so (see include/acc_spmm.h for the contract of each call).
+
+Argument marshalling only: every step of the SpMM path runs in the library's HIP
+kernels and host code.  The functions keep the C names.  Device buffers are passed either
+as torch tensors (their data pointers are taken) or as integer device addresses; torch is
+used by callers for device memory and streams, never for arithmetic.
+
+There is no fallback: if the shared library is missing, ``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaccspmm.so")
+_lib = None
+
+ACC_SPMM_OFF, ACC_SPMM_ON, ACC_SPMM_AUTO = 0, 1, 2
+
+(ACC_SPMM_ARR_PERM, ACC_SPMM_ARR_IPERM, ACC_SPMM_ARR_ROW_WINDOW_OFFSET, ACC_SPMM_ARR_TC_OFFSET,
+ ACC_SPMM_ARR_SPARSE_A_TO_B, ACC_SPMM_ARR_TC_LOCAL_BIT, ACC_SPMM_ARR_VALUES, ACC_SPMM_ARR_WORK_ITEMS,
+ ACC_SPMM_ARR_DENDROGRAM_PARENT) = range(9)
+
+_ARRAY_DTYPES = {
+    ACC_SPMM_ARR_PERM: np.int32, ACC_SPMM_ARR_IPERM: np.int32, ACC_SPMM_ARR_ROW_WINDOW_OFFSET: np.int32,
+    ACC_SPMM_ARR_TC_OFFSET: np.int32, ACC_SPMM_ARR_SPARSE_A_TO_B: np.int32, ACC_SPMM_ARR_TC_LOCAL_BIT: np.uint64,
+    ACC_SPMM_ARR_VALUES: np.uint16, ACC_SPMM_ARR_WORK_ITEMS: np.int32, ACC_SPMM_ARR_DENDROGRAM_PARENT: np.int32,
+}
+
+EXPORTED_SYMBOLS = [
+    "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
+    "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
+    "acc_spmm_reorder_host", "acc_spmm_schedule_host",
+]
+
+
+class acc_spmm_options(ctypes.Structure):
+    _fields_ = [
+        ("struct_size", ctypes.c_int32), ("reorder", ctypes.c_int32), ("load_balance", ctypes.c_int32),
+        ("max_tiles_per_item", ctypes.c_int32), ("window_height", ctypes.c_int32), ("tile_width", ctypes.c_int32),
+        ("segment_length", ctypes.c_int32), ("ibd_threshold", ctypes.c_float), ("keep_csr", ctypes.c_int32),
+        ("no_prefetch", ctypes.c_int32), ("plain_stores", ctypes.c_int32),
+    ]
+
+
+class acc_spmm_stats(ctypes.Structure):
+    _fields_ = [
+        ("M", ctypes.c_int64), ("K", ctypes.c_int64), ("nnz", ctypes.c_int64),
+        ("window_height", ctypes.c_int32), ("tile_width", ctypes.c_int32),
+        ("num_windows", ctypes.c_int64), ("num_tiles", ctypes.c_int64), ("sum_distinct_cols", ctypes.c_int64),
+        ("num_tiles_identity", ctypes.c_int64), ("num_items", ctypes.c_int64),
+        ("num_split_windows", ctypes.c_int64), ("num_partial_slots", ctypes.c_int64),
+        ("max_tiles_per_item", ctypes.c_int32), ("reorder_applied", ctypes.c_int32),
+        ("load_balance_applied", ctypes.c_int32),
+        ("ibd", ctypes.c_double), ("mean_nnz_per_tile", ctypes.c_double),
+        ("index_bytes", ctypes.c_int64), ("schedule_bytes", ctypes.c_int64),
+        ("t_validate_s", ctypes.c_double), ("t_reorder_s", ctypes.c_double), ("t_encode_s", ctypes.c_double),
+        ("t_schedule_s", ctypes.c_double), ("t_total_s", ctypes.c_double),
+    ]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class AccSpmmError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"acc_spmm error {code}: {msg}")
+        self.code = code
+
+
+def load():
+    """Load the shared library.  Raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_09251_amd.build` "
+                          "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+    L.acc_spmm_plan.restype = vp
+    L.acc_spmm_plan.argtypes = [i64, i64, i64, vp, vp, vp]
+    L.acc_spmm_plan_ex.restype = vp
+    L.acc_spmm_plan_ex.argtypes = [i64, i64, i64, vp, vp, vp, ctypes.POINTER(acc_spmm_options)]
+    L.acc_spmm_execute.restype = ctypes.c_int
+    L.acc_spmm_execute.argtypes = [vp, vp, i32, vp, vp]
+    L.acc_spmm_execute_timed.restype = ctypes.c_int
+    L.acc_spmm_execute_timed.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+    L.acc_spmm_execute_csr_naive.restype = ctypes.c_int
+    L.acc_spmm_execute_csr_naive.argtypes = [vp, vp, i32, vp, vp]
+    L.acc_spmm_destroy.restype = None
+    L.acc_spmm_destroy.argtypes = [vp]
+    L.acc_spmm_last_error.restype = ctypes.c_int
+    L.acc_spmm_last_error.argtypes = [ctypes.c_char_p, ctypes.c_size_t]
+    L.acc_spmm_plan_stats.restype = ctypes.c_int
+    L.acc_spmm_plan_stats.argtypes = [vp, ctypes.POINTER(acc_spmm_stats)]
+    L.acc_spmm_plan_traffic.restype = ctypes.c_int
+    L.acc_spmm_plan_traffic.argtypes = [vp, i32] + [ctypes.POINTER(ctypes.c_int64)] * 4
+    L.acc_spmm_plan_export.restype = ctypes.c_int
+    L.acc_spmm_plan_export.argtypes = [vp, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_size_t)]
+    L.acc_spmm_reorder_host.restype = ctypes.c_int
+    L.acc_spmm_reorder_host.argtypes = [i64, i64, vp, vp, i32, vp, vp, vp]
+    L.acc_spmm_schedule_host.restype = i64
+    L.acc_spmm_schedule_host.argtypes = [i64, vp, i32, i32, ctypes.c_float, ctypes.POINTER(ctypes.c_double), vp, i64,
+                                         ctypes.POINTER(ctypes.c_int64)]
+    _lib = L
+    return L
+
+
+def acc_spmm_last_error():
+    buf = ctypes.create_string_buffer(1024)
+    code = load().acc_spmm_last_error(buf, len(buf))
+    return code, buf.value.decode(errors="replace")
+
+
+def _raise():
+    raise AccSpmmError(*acc_spmm_last_error())
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data
+
+
+def _dev_ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()  # torch tensor
+
+
+def make_options(**kw) -> acc_spmm_options:
+    o = acc_spmm_options()
+    o.struct_size = ctypes.sizeof(acc_spmm_options)
+    o.reorder = ACC_SPMM_AUTO
+    o.load_balance = ACC_SPMM_AUTO
+    for k, v in kw.items():
+        if not hasattr(o, k):
+            raise TypeError(f"unknown option {k}")
+        setattr(o, k, v)
+    return o
+
+
+def acc_spmm_plan(M, K, nnz, csr_rowptr, csr_colidx, csr_vals):
+    """Build a plan with default options; returns the opaque handle (an int)."""
+    return acc_spmm_plan_ex(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, None)
+
+
+def acc_spmm_plan_ex(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, options):
+    rp, rp_p = _host(csr_rowptr, np.int32)
+    ci, ci_p = _host(csr_colidx, np.int32)
+    va, va_p = _host(csr_vals, np.uint16)
+    if len(rp) != M + 1 or len(ci) < nnz or len(va) < nnz:
+        raise ValueError("CSR array lengths do not match M / nnz")
+    h = load().acc_spmm_plan_ex(M, K, nnz, rp_p, ci_p, va_p, ctypes.byref(options) if options is not None else None)
+    if not h:
+        _raise()
+    return h
+
+
+def acc_spmm_execute(plan, B, N, C, stream=None):
+    """Enqueue C = A.B.  B, C: torch CUDA tensors or device addresses; stream: hipStream_t as int."""
+    if load().acc_spmm_execute(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
+        _raise()
+
+
+def acc_spmm_execute_timed(plan, B, N, C, stream=None):
+    """Blocking execute; returns (tile kernel ms, combine kernel ms) from HIP events on `stream`."""
+    t, c = ctypes.c_float(), ctypes.c_float()
+    if load().acc_spmm_execute_timed(plan, _dev_ptr(B), N, _dev_ptr(C), stream, ctypes.byref(t), ctypes.byref(c)) != 0:
+        _raise()
+    return t.value, c.value
+
+
+def acc_spmm_execute_csr_naive(plan, B, N, C, stream=None):
+    if load().acc_spmm_execute_csr_naive(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
+        _raise()
+
+
+def acc_spmm_destroy(plan):
+    if plan:
+        load().acc_spmm_destroy(plan)
+
+
+def acc_spmm_plan_stats(plan) -> dict:
+    st = acc_spmm_stats()
+    if load().acc_spmm_plan_stats(plan, ctypes.byref(st)) != 0:
+        _raise()
+    return st.as_dict()
+
+
+def acc_spmm_plan_traffic(plan, N) -> dict:
+    a, b, c, f = (ctypes.c_int64() for _ in range(4))
+    if load().acc_spmm_plan_traffic(plan, N, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(f)) != 0:
+        _raise()
+    return dict(a_bytes=a.value, b_bytes=b.value, c_bytes=c.value, mfma_flops=f.value)
+
+
+def acc_spmm_plan_export(plan, which) -> np.ndarray:
+    n = ctypes.c_size_t(0)
+    L = load()
+    if L.acc_spmm_plan_export(plan, which, None, ctypes.byref(n)) != 0:
+        _raise()
+    dt = np.dtype(_ARRAY_DTYPES[which])
+    out = np.empty(n.value // dt.itemsize, dt)
+    if n.value and L.acc_spmm_plan_export(plan, which, out.ctypes.data, ctypes.byref(n)) != 0:
+        _raise()
+    return out
+
+
+def acc_spmm_reorder_host(M, nnz, csr_rowptr, csr_colidx, segment_length=0):
+    """Host stage of the plan: returns (perm, iperm, parent) as int32 arrays."""
+    rp, rp_p = _host(csr_rowptr, np.int32)
+    ci, ci_p = _host(csr_colidx, np.int32)
+    perm, iperm, parent = (np.empty(M, np.int32) for _ in range(3))
+    if load().acc_spmm_reorder_host(M, nnz, rp_p, ci_p, segment_length, perm.ctypes.data, iperm.ctypes.data,
+                                    parent.ctypes.data) != 0:
+        _raise()
+    return perm, iperm, parent
+
+
+def acc_spmm_schedule_host(row_window_offset, load_balance=ACC_SPMM_AUTO, max_tiles_per_item=0, ibd_threshold=0.0):
+    """Host stage of the plan: returns (items[n,4] int32, ibd, num_partial_slots)."""
+    rwo, rwo_p = _host(row_window_offset, np.int32)
+    W = len(rwo) - 1
+    ibd, slots = ctypes.c_double(), ctypes.c_int64()
+    L = load()
+    n = L.acc_spmm_schedule_host(W, rwo_p, load_balance, max_tiles_per_item, ibd_threshold, ctypes.byref(ibd), None, 0,
+                                 ctypes.byref(slots))
+    if n < 0:
+        _raise()
+    items = np.empty((n, 4), np.int32)
+    n2 = L.acc_spmm_schedule_host(W, rwo_p, load_balance, max_tiles_per_item, ibd_threshold, None, items.ctypes.data, n,
+                                  None)
+    if n2 != n:
+        _raise()
+    return items, ibd.value, slots.value

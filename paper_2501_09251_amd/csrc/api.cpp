@@ -1,0 +1,363 @@
+// C ABI of the library (see include/acc_spmm.h): argument checks, plan orchestration,
+// statistics and array export.  No exception leaves this file.
+#include <algorithm>
+#include <chrono>
+#include <cstring>
+#include <new>
+
+#include "internal.h"
+
+namespace accspmm {
+
+namespace {
+thread_local int g_err_code = 0;
+thread_local std::string g_err_msg;
+
+double now_s() {
+    using namespace std::chrono;
+    return duration<double>(steady_clock::now().time_since_epoch()).count();
+}
+
+constexpr int32_t kDefaultCap = 64;
+constexpr int32_t kDefaultSegLen = 1024;
+constexpr float kDefaultIbdThreshold = 8.0f;
+}  // namespace
+
+void set_error(int code, const std::string& msg) {
+    g_err_code = code;
+    g_err_msg = msg;
+}
+
+void fail(int code, const std::string& msg) { throw Failure{code, msg}; }
+
+namespace {
+
+// Checks the CSR (monotone row pointers, columns in range, no duplicate column in a row).
+// Rows whose columns are not ascending are sorted into `fixed_*`; returns true if that
+// copy must be used.
+bool validate_csr(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
+                  const uint16_t* vals, std::vector<int32_t>& fixed_col, std::vector<uint16_t>& fixed_val) {
+    if (rowptr[0] != 0) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr[0] must be 0");
+    for (int64_t i = 0; i < M; ++i)
+        if (rowptr[i + 1] < rowptr[i]) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr decreases at row " + std::to_string(i));
+    if (rowptr[M] != nnz) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr[M] != nnz");
+    bool unsorted = false;
+    for (int64_t p = 0; p < nnz; ++p)
+        if (colidx[p] < 0 || colidx[p] >= K)
+            fail(ACC_SPMM_ERR_INVALID_CSR, "column index out of range at entry " + std::to_string(p));
+    for (int64_t i = 0; i < M && !unsorted; ++i)
+        for (int64_t p = rowptr[i] + 1; p < rowptr[i + 1]; ++p)
+            if (colidx[p] <= colidx[p - 1]) { unsorted = true; break; }
+    if (unsorted) {
+        fixed_col.assign(colidx, colidx + nnz);
+        fixed_val.assign(vals, vals + nnz);
+        std::vector<std::pair<int32_t, uint16_t>> row;
+        for (int64_t i = 0; i < M; ++i) {
+            const int64_t b = rowptr[i], e = rowptr[i + 1];
+            if (std::is_sorted(colidx + b, colidx + e)) continue;
+            row.clear();
+            for (int64_t p = b; p < e; ++p) row.push_back({colidx[p], vals[p]});
+            std::stable_sort(row.begin(), row.end(), [](auto& x, auto& y) { return x.first < y.first; });
+            for (int64_t p = b; p < e; ++p) { fixed_col[p] = row[p - b].first; fixed_val[p] = row[p - b].second; }
+        }
+        colidx = fixed_col.data();
+    }
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t p = rowptr[i] + 1; p < rowptr[i + 1]; ++p)
+            if (colidx[p] == colidx[p - 1])
+                fail(ACC_SPMM_ERR_INVALID_CSR, "duplicate column " + std::to_string(colidx[p]) + " in row " + std::to_string(i));
+    return unsorted;
+}
+
+acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
+                            const uint16_t* vals, const acc_spmm_options* user) {
+    const double t0 = now_s();
+    if (M < 0 || K < 0 || nnz < 0 || M >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || nnz >= ((int64_t)1 << 31))
+        fail(ACC_SPMM_ERR_INVALID_ARG, "M, K and nnz must be in [0, 2^31)");
+    if (!rowptr || (nnz > 0 && (!colidx || !vals))) fail(ACC_SPMM_ERR_INVALID_ARG, "null CSR pointer");
+    acc_spmm_options opt{};
+    opt.reorder = ACC_SPMM_AUTO;
+    opt.load_balance = ACC_SPMM_AUTO;
+    if (user) {
+        if (user->struct_size != (int32_t)sizeof(acc_spmm_options))
+            fail(ACC_SPMM_ERR_INVALID_ARG, "options.struct_size does not match this library");
+        opt = *user;
+    }
+    if (opt.reorder < 0 || opt.reorder > 2 || opt.load_balance < 0 || opt.load_balance > 2)
+        fail(ACC_SPMM_ERR_INVALID_ARG, "reorder / load_balance must be OFF, ON or AUTO");
+    if (opt.window_height == 0) opt.window_height = 16;
+    if (opt.tile_width == 0) opt.tile_width = 16;
+    if (!((opt.window_height == 16 && opt.tile_width == 16) || (opt.window_height == 8 && opt.tile_width == 8)))
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "tile geometry must be 16x16 or 8x8");
+    if (opt.max_tiles_per_item == 0) opt.max_tiles_per_item = kDefaultCap;
+    if (opt.max_tiles_per_item < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "max_tiles_per_item must be positive");
+    if (opt.segment_length == 0) opt.segment_length = kDefaultSegLen;
+    if (opt.segment_length < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "segment_length must be positive");
+    if (opt.ibd_threshold == 0.f) opt.ibd_threshold = kDefaultIbdThreshold;
+
+    std::vector<int32_t> fixed_col;
+    std::vector<uint16_t> fixed_val;
+    if (validate_csr(M, K, nnz, rowptr, colidx, vals, fixed_col, fixed_val)) {
+        colidx = fixed_col.data();
+        vals = fixed_val.data();
+    }
+
+    int dev_count = 0;
+    if (hipGetDeviceCount(&dev_count) != hipSuccess || dev_count == 0)
+        fail(ACC_SPMM_ERR_HIP, "no HIP device: this library only runs on a gfx950 GPU (there is no CPU path)");
+    const double t1 = now_s();
+
+    acc_spmm_plan_t* handle = new acc_spmm_plan_t;
+    Plan& P = handle->plan;
+    try {
+        ACC_HIP(hipGetDevice(&P.device));
+        P.opt = opt;
+        const int32_t WH = opt.window_height, TW = opt.tile_width;
+
+        // device copy of the CSR
+        P.d_rowptr.upload(rowptr, M + 1);
+        P.d_colidx.upload(colidx, nnz);
+        P.d_vals.upload(vals, nnz);
+
+        // ---- row order ----
+        std::vector<int32_t> identity(M);
+        for (int64_t i = 0; i < M; ++i) identity[i] = (int32_t)i;
+        DevBuf<int32_t> d_perm;
+        d_perm.upload(identity.data(), M);
+        bool use_reorder = false;
+        int64_t tiles_identity = -1;
+        double t_reorder = 0.0;
+        if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
+            const double r0 = now_s();
+            reorder_rows(M, rowptr, colidx, opt.segment_length, P.perm, P.iperm, P.parent);
+            DeviceFormat probe;
+            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
+            tiles_identity = probe.T;
+            DevBuf<int32_t> d_new;
+            d_new.upload(P.perm.data(), M);
+            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
+            use_reorder = opt.reorder == ACC_SPMM_ON || probe.T < tiles_identity;
+            if (use_reorder) d_perm.upload(P.perm.data(), M);
+            t_reorder = now_s() - r0;
+        }
+        if (!use_reorder) {
+            P.perm = identity;
+            P.iperm = identity;
+        }
+        std::vector<int32_t>().swap(identity);
+
+        // ---- format ----
+        const double e0 = now_s();
+        encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, P.fmt, false);
+        const double t_encode = now_s() - e0;
+        if (!opt.keep_csr) {
+            P.d_rowptr.release();
+            P.d_colidx.release();
+            P.d_vals.release();
+        }
+
+        // ---- schedule ----
+        const double s0 = now_s();
+        const int64_t W = P.fmt.W;
+        std::vector<int32_t> rwo(W + 1, 0);
+        P.fmt.row_window_offset.download(rwo.data());
+        const double ibd = imbalance_degree(rwo);
+        const bool balance = opt.load_balance == ACC_SPMM_ON || (opt.load_balance == ACC_SPMM_AUTO && ibd > opt.ibd_threshold);
+        build_schedule(rwo, balance, opt.max_tiles_per_item, WH, TW, P.items, P.splits, P.n_slots);
+        P.d_items.upload(P.items.data(), P.items.size());
+        P.d_splits.upload(P.splits.data(), P.splits.size());
+        std::vector<int32_t> pad((size_t)W * WH, -1);
+        std::copy(P.perm.begin(), P.perm.end(), pad.begin());
+        P.d_perm_pad.upload(pad.data(), pad.size());
+        const double t_schedule = now_s() - s0;
+
+        // ---- statistics ----
+        acc_spmm_stats& st = P.stats;
+        st.M = M; st.K = K; st.nnz = nnz;
+        st.window_height = WH; st.tile_width = TW;
+        st.num_windows = W;
+        st.num_tiles = P.fmt.T;
+        st.sum_distinct_cols = P.fmt.sum_dw;
+        st.num_tiles_identity = tiles_identity >= 0 ? tiles_identity : P.fmt.T;
+        st.num_items = (int64_t)P.items.size();
+        st.num_split_windows = (int64_t)P.splits.size();
+        st.num_partial_slots = P.n_slots;
+        st.max_tiles_per_item = opt.max_tiles_per_item;
+        st.reorder_applied = use_reorder;
+        st.load_balance_applied = balance;
+        st.ibd = ibd;
+        st.mean_nnz_per_tile = P.fmt.T ? (double)nnz / (double)P.fmt.T : 0.0;
+        st.index_bytes = 4 * (W + 1) + 4 * (P.fmt.T + 1) + 4 * P.fmt.T * TW + 8 * P.fmt.T * P.fmt.NW;
+        st.schedule_bytes = (int64_t)(sizeof(WorkItem) * P.items.size() + sizeof(SplitWindow) * P.splits.size()) + 4 * W * WH;
+        st.t_validate_s = t1 - t0;
+        st.t_reorder_s = t_reorder;
+        st.t_encode_s = t_encode;
+        st.t_schedule_s = t_schedule;
+        st.t_total_s = now_s() - t0;
+    } catch (...) {
+        delete handle;
+        throw;
+    }
+    return handle;
+}
+
+template <class F>
+int guarded(F&& fn) {
+    try {
+        fn();
+        return ACC_SPMM_OK;
+    } catch (const Failure& f) {
+        set_error(f.code, f.msg);
+        return f.code;
+    } catch (const std::bad_alloc&) {
+        set_error(ACC_SPMM_ERR_OOM, "host allocation failed");
+        return ACC_SPMM_ERR_OOM;
+    } catch (const std::exception& e) {
+        set_error(ACC_SPMM_ERR_INVALID_ARG, e.what());
+        return ACC_SPMM_ERR_INVALID_ARG;
+    }
+}
+
+}  // namespace
+}  // namespace accspmm
+
+using namespace accspmm;
+
+extern "C" {
+
+acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                                  const int32_t* csr_colidx, const uint16_t* csr_vals,
+                                  const acc_spmm_options* options) {
+    acc_spmm_plan_t* out = nullptr;
+    guarded([&] { out = build_plan(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, options); });
+    return out;
+}
+
+acc_spmm_plan_t* acc_spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                               const int32_t* csr_colidx, const uint16_t* csr_vals) {
+    return acc_spmm_plan_ex(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, nullptr);
+}
+
+int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream) {
+    return guarded([&] {
+        if (!plan || !C || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream));
+    });
+}
+
+int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream,
+                           float* tiles_ms, float* combine_ms) {
+    return guarded([&] {
+        if (!plan || !C || !tiles_ms || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), tiles_ms, combine_ms);
+    });
+}
+
+int acc_spmm_execute_csr_naive(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream) {
+    return guarded([&] {
+        if (!plan || !C || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_csr_naive(plan->plan, B, N, C, static_cast<hipStream_t>(stream));
+    });
+}
+
+void acc_spmm_destroy(acc_spmm_plan_t* plan) { delete plan; }
+
+int acc_spmm_last_error(char* buf, size_t len) {
+    if (buf && len) {
+        std::strncpy(buf, g_err_msg.c_str(), len - 1);
+        buf[len - 1] = 0;
+    }
+    return g_err_code;
+}
+
+int acc_spmm_plan_stats(const acc_spmm_plan_t* plan, acc_spmm_stats* out) {
+    return guarded([&] {
+        if (!plan || !out) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        *out = plan->plan.stats;
+    });
+}
+
+int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, int64_t* a_bytes, int64_t* b_bytes,
+                          int64_t* c_bytes, int64_t* mfma_flops) {
+    return guarded([&] {
+        if (!plan || N <= 0) fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
+        const acc_spmm_stats& st = plan->plan.stats;
+        if (a_bytes) *a_bytes = 2 * st.nnz + st.index_bytes + st.schedule_bytes;
+        if (b_bytes) *b_bytes = st.sum_distinct_cols * (int64_t)N * 2;
+        if (c_bytes) *c_bytes = st.M * (int64_t)N * 4;
+        if (mfma_flops) *mfma_flops = 2 * st.num_tiles * st.window_height * st.tile_width * (int64_t)N;
+    });
+}
+
+int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
+                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent) {
+    return guarded([&] {
+        if (M < 0 || nnz < 0 || !csr_rowptr || (nnz > 0 && !csr_colidx) || !perm || !iperm)
+            fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
+        std::vector<int32_t> fixed_col;
+        std::vector<uint16_t> fixed_val, dummy((size_t)nnz, 0);
+        if (validate_csr(M, M, nnz, csr_rowptr, csr_colidx, dummy.data(), fixed_col, fixed_val)) csr_colidx = fixed_col.data();
+        std::vector<int32_t> p, ip, par;
+        reorder_rows(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, p, ip, par);
+        std::copy(p.begin(), p.end(), perm);
+        std::copy(ip.begin(), ip.end(), iperm);
+        if (parent) std::copy(par.begin(), par.end(), parent);
+    });
+}
+
+int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,
+                               int32_t max_tiles_per_item, float ibd_threshold, double* ibd_out,
+                               int32_t* items, int64_t items_capacity, int64_t* num_partial_slots) {
+    int64_t n = -1;
+    int rc = guarded([&] {
+        if (W < 0 || !row_window_offset || load_balance < 0 || load_balance > 2)
+            fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
+        std::vector<int32_t> rwo(row_window_offset, row_window_offset + W + 1);
+        const double ibd = imbalance_degree(rwo);
+        if (ibd_out) *ibd_out = ibd;
+        const float thr = ibd_threshold > 0.f ? ibd_threshold : kDefaultIbdThreshold;
+        const bool balance = load_balance == ACC_SPMM_ON || (load_balance == ACC_SPMM_AUTO && ibd > thr);
+        std::vector<WorkItem> it;
+        std::vector<SplitWindow> sp;
+        int64_t slots = 0;
+        build_schedule(rwo, balance, max_tiles_per_item > 0 ? max_tiles_per_item : kDefaultCap, 16, 16, it, sp, slots);
+        if (num_partial_slots) *num_partial_slots = slots;
+        if (items) {
+            if ((int64_t)it.size() > items_capacity) fail(ACC_SPMM_ERR_INVALID_ARG, "items_capacity too small");
+            std::memcpy(items, it.data(), it.size() * sizeof(WorkItem));
+        }
+        n = (int64_t)it.size();
+    });
+    return rc == ACC_SPMM_OK ? n : rc;
+}
+
+int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst, size_t* bytes) {
+    return guarded([&] {
+        if (!plan || !bytes) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        const Plan& P = plan->plan;
+        const DeviceFormat& f = P.fmt;
+        const void* dev = nullptr;
+        const void* host = nullptr;
+        size_t need = 0;
+        switch (which) {
+            case ACC_SPMM_ARR_PERM: host = P.perm.data(); need = P.perm.size() * 4; break;
+            case ACC_SPMM_ARR_IPERM: host = P.iperm.data(); need = P.iperm.size() * 4; break;
+            case ACC_SPMM_ARR_DENDROGRAM_PARENT: host = P.parent.data(); need = P.parent.size() * 4; break;
+            case ACC_SPMM_ARR_WORK_ITEMS: host = P.items.data(); need = P.items.size() * sizeof(WorkItem); break;
+            case ACC_SPMM_ARR_ROW_WINDOW_OFFSET: dev = f.row_window_offset.p; need = (size_t)(f.W + 1) * 4; break;
+            case ACC_SPMM_ARR_TC_OFFSET: dev = f.tc_offset.p; need = (size_t)(f.T + 1) * 4; break;
+            case ACC_SPMM_ARR_SPARSE_A_TO_B: dev = f.sparse_a_to_b.p; need = (size_t)f.T * f.TW * 4; break;
+            case ACC_SPMM_ARR_TC_LOCAL_BIT: dev = f.tc_local_bit.p; need = (size_t)f.T * f.NW * 8; break;
+            case ACC_SPMM_ARR_VALUES: dev = f.vals.p; need = (size_t)f.nnz * 2; break;
+            default: fail(ACC_SPMM_ERR_INVALID_ARG, "unknown array id");
+        }
+        if (!host_dst) { *bytes = need; return; }
+        if (*bytes < need) fail(ACC_SPMM_ERR_INVALID_ARG, "destination too small");
+        *bytes = need;
+        if (!need) return;
+        if (host) std::memcpy(host_dst, host, need);
+        else ACC_HIP(hipMemcpy(host_dst, dev, need, hipMemcpyDeviceToHost));
+    });
+}
+
+}  // extern "C"

@@ -1,0 +1,406 @@
+// Runtime kernels: C = A.B from the bitmap tile format (paper Section 3.4, Algorithm 2,
+// re-designed for gfx950).
+//
+// One wavefront owns one work item: a run of whole row windows, or a slice of the tiles of
+// one heavy window (Section 3.5).  For every 16x16 tile the wavefront
+//   - reads the tile's 16 SparseAToB entries and gathers those 16 rows of B straight into
+//     registers (as in the paper's Fig. 5, B goes global -> registers): each 16-lane group
+//     reads four whole rows with 16-byte loads per lane,
+//   - decodes its own four positions of the tile from the bitmap (popcount of the lower
+//     bits gives the value offset, Section 3.3) and reads up to four packed values,
+//   - issues v_mfma_f32_16x16x16_f16 with the sparse tile as the 16x16 left operand and
+//     sixteen feature columns of the gathered rows as the right operand.
+// Lane c of a group owns features [FPL*c, FPL*c+FPL) of a 16*FPL-wide slab, so a feature's
+// position inside an MFMA is a free choice and no transpose through LDS is needed: the
+// four k-values of one feature come from four registers and are packed with v_perm_b32.
+//
+// Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
+// values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
+// words of tile t+DEPTH+1 are requested one step before they are needed for addresses.
+#include "internal.h"
+
+namespace accspmm {
+namespace {
+
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef int32_t intx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWavesPerBlock = 4;
+
+struct ExecParams {
+    const int32_t* __restrict__ rwo;
+    const int32_t* __restrict__ tco;
+    const int32_t* __restrict__ a2b;
+    const uint64_t* __restrict__ bits;
+    const uint16_t* __restrict__ vals;
+    const int32_t* __restrict__ perm_pad;
+    const WorkItem* __restrict__ items;
+    const uint16_t* __restrict__ B;
+    float* __restrict__ C;
+    float* __restrict__ ws;
+    int64_t W;
+    int32_t n_items;
+    int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
+    int32_t N;
+};
+
+template <int FPL>
+struct Chunk {  // FPL consecutive fp16 features of one B row, as dwords
+    static constexpr int DW = (FPL + 1) / 2;
+    uint32_t d[DW];
+};
+
+template <int FPL>
+__device__ __forceinline__ void load_chunk(const uint16_t* p, Chunk<FPL>& c) {
+    if constexpr (FPL == 8) {
+        uintx4 v = *reinterpret_cast<const uintx4*>(p);
+        c.d[0] = v.x; c.d[1] = v.y; c.d[2] = v.z; c.d[3] = v.w;
+    } else if constexpr (FPL == 4) {
+        uintx2 v = *reinterpret_cast<const uintx2*>(p);
+        c.d[0] = v.x; c.d[1] = v.y;
+    } else if constexpr (FPL == 2) {
+        c.d[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else {
+        c.d[0] = *p;
+    }
+}
+
+struct TileMeta {       // index words of one tile
+    intx4 cols;         // this lane group's four SparseAToB entries
+    uint64_t bm[4];     // TCLocalBit (wave-uniform)
+    int32_t tco;        // TCOffset (wave-uniform)
+};
+
+template <int FPL, int NS>
+struct TileData {       // what the multiply needs
+    Chunk<FPL> b[NS][4];
+    uint32_t h[4];      // up to four packed values (fp16 bits)
+    uint32_t nib;       // this lane's four bitmap bits
+};
+
+template <int FPL, int NS, int DEPTH, bool NT>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecParams p, int slab0) {
+    constexpr int R = DEPTH + 1;
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, c = lane & 15;
+    // Consecutive blocks go to different XCDs (round-robin over 8); give each XCD one
+    // contiguous eighth of the items so that neighbouring windows share an L2.
+    const int per_xcd = (p.n_blocks + 7) >> 3;
+    const int lblock = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (lblock >= p.n_blocks) return;
+    const int item_id = __builtin_amdgcn_readfirstlane(lblock * kWavesPerBlock + (int)(threadIdx.x >> 6));
+    if (item_id >= p.n_items) return;
+    const WorkItem it = p.items[item_id];
+    const int w_begin = __builtin_amdgcn_readfirstlane(it.w_begin);
+    const int w_end_raw = __builtin_amdgcn_readfirstlane(it.w_end);
+    const int tb = __builtin_amdgcn_readfirstlane(it.t_begin);
+    const int te = __builtin_amdgcn_readfirstlane(it.t_end);
+    const bool partial = w_end_raw < 0;
+    const int w_end = partial ? w_begin + 1 : w_end_raw;
+    const int N = p.N;
+    const int slab_base = (slab0 + blockIdx.y * NS) * 128;  // first feature of this launch's slabs (NS>1 or grid.y>1 only when FPL==8)
+    const int f0 = slab_base + c * FPL;
+
+    // lane constants of the bitmap decode: bit index of (row c, k 4g) is c*16 + 4g
+    const int wq = c >> 2;
+    const int sh = ((c & 3) << 4) | (g << 2);
+    const uint64_t below_mask = (1ull << sh) - 1ull;
+
+    floatx4 acc[NS][FPL];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    auto flush = [&](int w) {
+        float* base;
+        intx4 rows;
+        if (partial) {
+            const int slot = -w_end_raw - 1;
+            base = p.ws + (size_t)slot * 16 * (size_t)N;
+            rows = intx4{4 * g, 4 * g + 1, 4 * g + 2, 4 * g + 3};
+        } else {
+            base = p.C;
+            rows = *reinterpret_cast<const intx4*>(p.perm_pad + (size_t)w * 16 + 4 * g);
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = rows[r];
+            if (row >= 0) {
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    float* dst = base + (size_t)row * (size_t)N + f0 + s * 128;
+                    if constexpr (FPL >= 4) {
+#pragma unroll
+                        for (int m = 0; m < FPL; m += 4) {
+                            floatx4 v{acc[s][m][r], acc[s][m + 1][r], acc[s][m + 2][r], acc[s][m + 3][r]};
+                            if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(dst + m));
+                            else *reinterpret_cast<floatx4*>(dst + m) = v;
+                        }
+                    } else {
+#pragma unroll
+                        for (int m = 0; m < FPL; ++m) {
+                            if constexpr (NT) __builtin_nontemporal_store(acc[s][m][r], dst + m);
+                            else dst[m] = acc[s][m][r];
+                        }
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+    };
+
+    auto load_meta = [&](int t, TileMeta& m) {
+        t = t < te ? t : te - 1;  // past the end: re-read the last tile (always in bounds)
+        m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 16 + 4 * g);
+        const uint64_t* bm = p.bits + (size_t)t * 4;
+        m.bm[0] = bm[0]; m.bm[1] = bm[1]; m.bm[2] = bm[2]; m.bm[3] = bm[3];
+        m.tco = p.tco[t];
+    };
+
+    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint16_t* row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) load_chunk<FPL>(row + s * 128, d.b[s][q]);
+        }
+        const int p0 = __builtin_popcountll(m.bm[0]);
+        const int p1 = p0 + __builtin_popcountll(m.bm[1]);
+        const int p2 = p1 + __builtin_popcountll(m.bm[2]);
+        const uint64_t word = wq == 0 ? m.bm[0] : wq == 1 ? m.bm[1] : wq == 2 ? m.bm[2] : m.bm[3];
+        const int pre = wq == 0 ? 0 : wq == 1 ? p0 : wq == 2 ? p1 : p2;
+        const uint32_t nib = (uint32_t)(word >> sh) & 15u;
+        const uint32_t i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
+        const uint32_t i1 = i0 + (nib & 1u);
+        const uint32_t i2 = i1 + ((nib >> 1) & 1u);
+        const uint32_t i3 = i2 + ((nib >> 2) & 1u);
+        d.h[0] = p.vals[i0]; d.h[1] = p.vals[i1]; d.h[2] = p.vals[i2]; d.h[3] = p.vals[i3];
+        d.nib = nib;
+    };
+
+    auto multiply = [&](const TileData<FPL, NS>& d) {
+        const uint32_t a0 = (d.nib & 1u) ? d.h[0] : 0u;
+        const uint32_t a1 = (d.nib & 2u) ? d.h[1] : 0u;
+        const uint32_t a2 = (d.nib & 4u) ? d.h[2] : 0u;
+        const uint32_t a3 = (d.nib & 8u) ? d.h[3] : 0u;
+        const uintx2 au{a0 | (a1 << 16), a2 | (a3 << 16)};
+        const half4 a = __builtin_bit_cast(half4, au);
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int m = 0; m < FPL; ++m) {
+                const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
+                const uintx2 bu{__builtin_amdgcn_perm(d.b[s][1].d[m >> 1], d.b[s][0].d[m >> 1], sel),
+                                __builtin_amdgcn_perm(d.b[s][3].d[m >> 1], d.b[s][2].d[m >> 1], sel)};
+                acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(a, __builtin_bit_cast(half4, bu), acc[s][m], 0, 0, 0);
+            }
+    };
+
+    // window bookkeeping (all wave-uniform)
+    int w = w_begin;
+    int wend = partial ? te : p.rwo[w + 1];
+    // leading empty windows
+    while (!partial && wend == tb && w < w_end) {
+        flush(w);
+        ++w;
+        if (w < w_end) wend = p.rwo[w + 1];
+    }
+    if (tb >= te) return;
+
+    auto after_tile = [&](int tt) {  // tile tt has been multiplied: close the window(s) ending there
+        if (tt + 1 != wend) return;
+        flush(w);
+        ++w;
+        if (partial) return;
+        if (w < w_end) wend = p.rwo[w + 1];
+        while (w < w_end && wend == tt + 1) {  // empty windows inside the run
+            flush(w);
+            ++w;
+            if (w < w_end) wend = p.rwo[w + 1];
+        }
+    };
+
+    if constexpr (DEPTH == 0) {
+        // ablation: every tile's loads are issued only when the tile is computed
+        for (int tt = tb; tt < te; ++tt) {
+            TileMeta m;
+            TileData<FPL, NS> d;
+            load_meta(tt, m);
+            issue(m, d);
+            multiply(d);
+            after_tile(tt);
+        }
+    } else {
+        // Ring of R = DEPTH+1 buffers; tile x uses slot (x - tb) % R.  vmcnt retires loads in
+        // issue order, so the index words of tile tt+DEPTH+1 are requested *before* the data
+        // of tile tt+DEPTH: waiting for index words then never drains the data behind them,
+        // and DEPTH tiles of B rows stay in flight while tile tt is multiplied.
+        TileMeta meta[R];
+        TileData<FPL, NS> data[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_meta(tb + r, meta[r]);
+#pragma unroll
+        for (int r = 0; r < DEPTH; ++r) issue(meta[r], data[r]);
+        for (int t = tb; t < te; t += R) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int tt = t + r;
+                if (tt >= te) break;
+                TileMeta next_meta;
+                load_meta(tt + DEPTH + 1, next_meta);                     // slot r, free since tile tt was issued
+                issue(meta[(r + DEPTH) % R], data[(r + DEPTH) % R]);     // tile tt+DEPTH
+                meta[r] = next_meta;
+                multiply(data[r]);
+                after_tile(tt);
+            }
+        }
+    }
+}
+
+// Sum the partial tiles of each split window and write the rows of C (Section 3.5: the
+// write-back of a window shared by several work items).  One block per split window.
+__global__ __launch_bounds__(256) void combine_split_kernel(const SplitWindow* __restrict__ splits,
+                                                            const float* __restrict__ ws,
+                                                            const int32_t* __restrict__ perm_pad,
+                                                            float* __restrict__ C, int32_t N) {
+    const SplitWindow sw = splits[blockIdx.x];
+    const int n4 = N >> 2;
+    for (int e = threadIdx.x; e < 16 * n4; e += blockDim.x) {
+        const int r = e / n4, j = (e - r * n4) << 2;
+        const int row = perm_pad[(size_t)sw.window * 16 + r];
+        if (row < 0) continue;
+        floatx4 s{0.f, 0.f, 0.f, 0.f};
+        for (int slot = sw.slot_begin; slot < sw.slot_end; ++slot)
+            s += *reinterpret_cast<const floatx4*>(ws + ((size_t)slot * 16 + r) * (size_t)N + j);
+        __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(C + (size_t)row * (size_t)N + j));
+    }
+}
+
+// Baseline: one wavefront per CSR row, lanes over the N features, serial loop over the
+// row's entries, fp32 FMA.
+__global__ __launch_bounds__(256) void csr_row_per_wave_kernel(int64_t M, const int32_t* __restrict__ rowptr,
+                                                               const int32_t* __restrict__ colidx,
+                                                               const uint16_t* __restrict__ vals,
+                                                               const uint16_t* __restrict__ B,
+                                                               float* __restrict__ C, int32_t N) {
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= M) return;
+    const int lane = threadIdx.x & 63;
+    const int pb = rowptr[row], pe = rowptr[row + 1];
+    for (int j0 = 0; j0 < N; j0 += 64) {
+        const int j = j0 + lane;
+        float acc = 0.f;
+        if (j < N)
+            for (int q = pb; q < pe; ++q) {
+                const float a = (float)__builtin_bit_cast(_Float16, vals[q]);
+                const float b = (float)__builtin_bit_cast(_Float16, B[(size_t)colidx[q] * (size_t)N + j]);
+                acc = __builtin_fmaf(a, b, acc);
+            }
+        if (j < N) C[(size_t)row * (size_t)N + j] = acc;
+    }
+}
+
+template <int FPL, int NS>
+void launch_variant(const ExecParams& p, int n_slab_launches, bool no_prefetch, bool plain_stores,
+                    hipStream_t stream) {
+    const int blocks = ((p.n_blocks + 7) / 8) * 8;
+    dim3 grid(blocks, n_slab_launches), block(kWavesPerBlock * 64);
+    if (no_prefetch) {
+        if (plain_stores) hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 0, false>), grid, block, 0, stream, p, 0);
+        else hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 0, true>), grid, block, 0, stream, p, 0);
+    } else {
+        if (plain_stores) hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 2, false>), grid, block, 0, stream, p, 0);
+        else hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 2, true>), grid, block, 0, stream, p, 0);
+    }
+}
+
+}  // namespace
+
+void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream, float* tiles_ms,
+                    float* combine_ms) {
+    const bool timed = tiles_ms != nullptr;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    if (timed) {
+        *tiles_ms = 0.f;
+        if (combine_ms) *combine_ms = 0.f;
+        for (auto& e : ev) ACC_HIP(hipEventCreate(&e));
+    }
+    struct EventGuard {
+        hipEvent_t* ev;
+        ~EventGuard() { for (int i = 0; i < 3; ++i) if (ev[i]) (void)hipEventDestroy(ev[i]); }
+    } guard{ev};
+    const DeviceFormat& f = plan.fmt;
+    if (f.WH != 16 || f.TW != 16)
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "execute needs a plan with 16x16 tiles");
+    const bool small = (N == 16 || N == 32 || N == 64 || N == 128);
+    if (!(small || (N > 0 && N <= 512 && N % 128 == 0)))
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "N must be 16, 32, 64, 128, 256, 384 or 512");
+    if ((reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
+        fail(ACC_SPMM_ERR_INVALID_ARG, "B and C must be 16-byte aligned");
+    if (f.M == 0) return;
+    if (plan.n_slots > 0 && plan.workspace_N < N) {
+        plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
+        plan.workspace_N = N;
+    }
+    ExecParams p;
+    p.rwo = f.row_window_offset.p;
+    p.tco = f.tc_offset.p;
+    p.a2b = f.sparse_a_to_b.p;
+    p.bits = f.tc_local_bit.p;
+    p.vals = f.vals.p;
+    p.perm_pad = plan.d_perm_pad.p;
+    p.items = plan.d_items.p;
+    p.B = static_cast<const uint16_t*>(B);
+    p.C = static_cast<float*>(C);
+    p.ws = plan.workspace.p;
+    p.W = f.W;
+    p.n_items = (int32_t)plan.items.size();
+    p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    p.N = N;
+    const bool np = plan.opt.no_prefetch != 0, ps = plan.opt.plain_stores != 0;
+    if (timed) ACC_HIP(hipEventRecord(ev[0], stream));
+    if (p.n_items > 0) {
+        switch (N) {
+            case 16: launch_variant<1, 1>(p, 1, np, ps, stream); break;
+            case 32: launch_variant<2, 1>(p, 1, np, ps, stream); break;
+            case 64: launch_variant<4, 1>(p, 1, np, ps, stream); break;
+            case 128: launch_variant<8, 1>(p, 1, np, ps, stream); break;
+            case 256: launch_variant<8, 2>(p, 1, np, ps, stream); break;
+            case 384: launch_variant<8, 1>(p, 3, np, ps, stream); break;
+            case 512: launch_variant<8, 2>(p, 2, np, ps, stream); break;
+        }
+        ACC_HIP(hipGetLastError());
+    }
+    if (timed) ACC_HIP(hipEventRecord(ev[1], stream));
+    if (!plan.splits.empty()) {
+        hipLaunchKernelGGL(combine_split_kernel, dim3((unsigned)plan.splits.size()), dim3(256), 0, stream,
+                           plan.d_splits.p, plan.workspace.p, plan.d_perm_pad.p, static_cast<float*>(C), N);
+        ACC_HIP(hipGetLastError());
+    }
+    if (timed) {
+        ACC_HIP(hipEventRecord(ev[2], stream));
+        ACC_HIP(hipEventSynchronize(ev[2]));
+        ACC_HIP(hipEventElapsedTime(tiles_ms, ev[0], ev[1]));
+        if (combine_ms && !plan.splits.empty()) ACC_HIP(hipEventElapsedTime(combine_ms, ev[1], ev[2]));
+    }
+}
+
+void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream) {
+    if (!plan.d_rowptr.p) fail(ACC_SPMM_ERR_INVALID_ARG, "plan was built without keep_csr");
+    if (N <= 0) fail(ACC_SPMM_ERR_INVALID_ARG, "N must be positive");
+    const int64_t M = plan.fmt.M;
+    if (M == 0) return;
+    hipLaunchKernelGGL(csr_row_per_wave_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, stream, M,
+                       plan.d_rowptr.p, plan.d_colidx.p, plan.d_vals.p, static_cast<const uint16_t*>(B),
+                       static_cast<float*>(C), N);
+    ACC_HIP(hipGetLastError());
+}
+
+}  // namespace accspmm

@@ -1,0 +1,120 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "acc_spmm.h"
+
+namespace accspmm {
+
+// ---- error plumbing -------------------------------------------------------------------
+void set_error(int code, const std::string& msg);
+struct Failure {
+    int code;
+    std::string msg;
+};
+[[noreturn]] void fail(int code, const std::string& msg);  // throws Failure; caught at the ABI
+
+#define ACC_HIP(expr)                                                                       \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            ::accspmm::fail(e_ == hipErrorOutOfMemory ? ACC_SPMM_ERR_OOM : ACC_SPMM_ERR_HIP, \
+                            std::string(#expr) + ": " + hipGetErrorString(e_));             \
+    } while (0)
+
+// ---- device buffer --------------------------------------------------------------------
+template <class T>
+struct DevBuf {
+    T* p = nullptr;
+    size_t n = 0;
+    DevBuf() = default;
+    DevBuf(const DevBuf&) = delete;
+    DevBuf& operator=(const DevBuf&) = delete;
+    ~DevBuf() { release(); }
+    void alloc(size_t count) {
+        release();
+        n = count;
+        if (count) ACC_HIP(hipMalloc((void**)&p, count * sizeof(T)));
+    }
+    void release() {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        n = 0;
+    }
+    void upload(const T* host, size_t count) {
+        alloc(count);
+        if (count) ACC_HIP(hipMemcpy(p, host, count * sizeof(T), hipMemcpyHostToDevice));
+    }
+    void download(T* host) const {
+        if (n) ACC_HIP(hipMemcpy(host, p, n * sizeof(T), hipMemcpyDeviceToHost));
+    }
+};
+
+// One unit of runtime work = one wavefront (see acc_spmm_plan_export for the encoding).
+struct WorkItem {
+    int32_t w_begin, w_end, t_begin, t_end;
+};
+struct SplitWindow {
+    int32_t window, slot_begin, slot_end, pad;
+};
+
+// The tile format on the device (paper Section 3.3), for WH x TW tiles.
+struct DeviceFormat {
+    int32_t WH = 16, TW = 16, NW = 4;  // NW = 64-bit words per tile bitmap
+    int64_t M = 0, W = 0, T = 0, nnz = 0, sum_dw = 0;
+    DevBuf<int32_t> row_window_offset;  // W+1
+    DevBuf<int32_t> tc_offset;          // T+1
+    DevBuf<int32_t> sparse_a_to_b;      // T*TW
+    DevBuf<uint64_t> tc_local_bit;      // T*NW
+    DevBuf<uint16_t> vals;              // nnz (+ padding so that 4 halves past the end are readable)
+};
+
+// encode.hip: CSR (device) + perm (device, new->old, M entries) -> DeviceFormat.
+void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,
+                      const uint16_t* d_vals, const int32_t* d_perm, int32_t WH, int32_t TW, DeviceFormat& out,
+                      bool tiles_only);
+
+// reorder.cpp: Algorithm 1 on the host.  perm/iperm/parent get M entries.
+void reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
+                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent);
+
+// schedule.cpp: Section 3.5.
+double imbalance_degree(const std::vector<int32_t>& rwo);
+void build_schedule(const std::vector<int32_t>& rwo, bool balance, int32_t cap, int32_t WH, int32_t TW,
+                    std::vector<WorkItem>& items, std::vector<SplitWindow>& splits, int64_t& n_slots);
+
+struct Plan {
+    int device = 0;
+    acc_spmm_options opt{};
+    acc_spmm_stats stats{};
+    DeviceFormat fmt;
+    std::vector<int32_t> perm, iperm, parent;  // host copies (perm: new->old)
+    DevBuf<int32_t> d_perm_pad;                // W*WH entries, -1 past M
+    std::vector<WorkItem> items;
+    std::vector<SplitWindow> splits;
+    DevBuf<WorkItem> d_items;
+    DevBuf<SplitWindow> d_splits;
+    int64_t n_slots = 0;
+    // partial-sum workspace, grown on demand by execute
+    mutable DevBuf<float> workspace;
+    mutable int32_t workspace_N = 0;
+    // optional CSR copy for the naive baseline
+    DevBuf<int32_t> d_rowptr, d_colidx;
+    DevBuf<uint16_t> d_vals;
+};
+
+// execute.hip
+// tiles_ms / combine_ms non-null: time the two kernels with events and wait for them
+void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream,
+                    float* tiles_ms = nullptr, float* combine_ms = nullptr);
+void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
+
+}  // namespace accspmm
+
+struct acc_spmm_plan_s {
+    accspmm::Plan plan;
+};

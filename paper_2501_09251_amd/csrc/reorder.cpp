@@ -1,0 +1,262 @@
+// Data-affinity-based row reordering (paper Section 3.2, Algorithm 1), host side.
+//
+// Step I (dendrogram construction) is sequential by definition: vertices are visited in
+// ascending degree and every decision depends on the merges made before it, so it runs on
+// one host thread over flat arrays.  Step II (ordering generation) is independent per
+// segment of the dendrogram's leaf sequence and runs on all host threads.
+//
+// Readings of what the paper leaves open (Eq. 1 is printed as the modularity itself, the
+// tie-breaks and the search scope of Step II are not stated):
+//  - graph: vertex per row/column index, undirected unit edge {i,j}, i != j, iff A_ij or
+//    A_ji is stored;
+//  - visiting order: ascending degree, ties by lower id;
+//  - gain of joining communities u and v: 2*(w_uv/(2m) - d_u*d_v/(2m)^2), compared exactly
+//    as s = w_uv*2m - d_u*d_v in 64-bit integers; ties go to the lower community id; merge
+//    only when s > 0;
+//  - leaf sequence: roots by ascending id, a root first and then its children's subtrees
+//    in merge order; every tree's sequence is cut into segments of at most seg_len leaves;
+//  - chaining inside a segment: next is the unvisited leaf sharing the most column indices
+//    with the current row (at least one), ties to the earliest leaf of the sequence.
+#include <algorithm>
+#include <atomic>
+#include <thread>
+
+#include "internal.h"
+
+namespace accspmm {
+namespace {
+
+template <class F>
+void parallel_chunks(int64_t n, int64_t grain, F&& fn) {
+    unsigned hw = std::thread::hardware_concurrency();
+    int nt = (int)std::min<int64_t>(hw ? hw : 4, std::max<int64_t>(1, (n + grain - 1) / grain));
+    nt = std::min(nt, 32);
+    if (nt <= 1) {
+        fn((int64_t)0, n);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    std::vector<std::thread> th;
+    auto body = [&]() {
+        for (;;) {
+            int64_t b = next.fetch_add(grain);
+            if (b >= n) break;
+            fn(b, std::min(n, b + grain));
+        }
+    };
+    for (int t = 1; t < nt; ++t) th.emplace_back(body);
+    body();
+    for (auto& t : th) t.join();
+}
+
+// Symmetric adjacency (pattern of A + A^T, no diagonal) as CSR with ascending neighbours.
+void build_graph(int64_t M, const int32_t* rowptr, const int32_t* colidx, std::vector<int64_t>& gptr,
+                 std::vector<int32_t>& gadj) {
+    // transpose pattern by counting sort
+    std::vector<std::atomic<int32_t>> cnt(M);
+    for (auto& c : cnt) c.store(0, std::memory_order_relaxed);
+    parallel_chunks(M, 1 << 14, [&](int64_t b, int64_t e) {
+        for (int64_t i = b; i < e; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
+                if (colidx[p] != i) cnt[colidx[p]].fetch_add(1, std::memory_order_relaxed);
+    });
+    std::vector<int64_t> tptr(M + 1, 0);
+    for (int64_t i = 0; i < M; ++i) tptr[i + 1] = tptr[i] + cnt[i].load(std::memory_order_relaxed);
+    std::vector<int32_t> tadj(tptr[M]);
+    for (auto& c : cnt) c.store(0, std::memory_order_relaxed);
+    parallel_chunks(M, 1 << 14, [&](int64_t b, int64_t e) {
+        for (int64_t i = b; i < e; ++i)
+            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+                int32_t j = colidx[p];
+                if (j != i) tadj[tptr[j] + cnt[j].fetch_add(1, std::memory_order_relaxed)] = (int32_t)i;
+            }
+    });
+    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
+        for (int64_t j = b; j < e; ++j) std::sort(tadj.begin() + tptr[j], tadj.begin() + tptr[j + 1]);
+    });
+    // union of row i of A (ascending) and row i of A^T (ascending), without i itself
+    auto merge_row = [&](int64_t i, int32_t* out) -> int64_t {
+        int64_t a = rowptr[i], ae = rowptr[i + 1], t = tptr[i], te = tptr[i + 1], n = 0;
+        while (a < ae || t < te) {
+            int32_t x;
+            if (t >= te || (a < ae && colidx[a] <= tadj[t])) {
+                x = colidx[a++];
+                if (t < te && tadj[t] == x) ++t;
+            } else x = tadj[t++];
+            if (x == i) continue;
+            if (out) out[n] = x;
+            ++n;
+        }
+        return n;
+    };
+    gptr.assign(M + 1, 0);
+    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
+        for (int64_t i = b; i < e; ++i) gptr[i + 1] = merge_row(i, nullptr);
+    });
+    for (int64_t i = 0; i < M; ++i) gptr[i + 1] += gptr[i];
+    gadj.resize(gptr[M]);
+    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
+        for (int64_t i = b; i < e; ++i) merge_row(i, gadj.data() + gptr[i]);
+    });
+}
+
+struct Edge {
+    int32_t to;
+    uint32_t w;
+};
+
+// Step I.  parent[v] = community v was merged into (-1: root); children lists in merge order.
+void build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::vector<int32_t>& gadj,
+                      std::vector<int32_t>& parent, std::vector<int32_t>& first_child,
+                      std::vector<int32_t>& next_sibling) {
+    const int64_t two_m = gptr[M];
+    // visiting order: counting sort by degree, stable in the id
+    std::vector<int32_t> order(M);
+    {
+        int64_t maxdeg = 0;
+        for (int64_t i = 0; i < M; ++i) maxdeg = std::max(maxdeg, gptr[i + 1] - gptr[i]);
+        std::vector<int64_t> start(maxdeg + 2, 0);
+        for (int64_t i = 0; i < M; ++i) start[gptr[i + 1] - gptr[i] + 1]++;
+        for (int64_t d = 0; d <= maxdeg; ++d) start[d + 1] += start[d];
+        for (int64_t i = 0; i < M; ++i) order[start[gptr[i + 1] - gptr[i]]++] = (int32_t)i;
+    }
+    parent.assign(M, -1);
+    first_child.assign(M, -1);
+    next_sibling.assign(M, -1);
+    std::vector<int32_t> last_child(M, -1), up(M);
+    std::vector<int64_t> dsum(M);
+    std::vector<std::vector<Edge>> agg(M);  // community edges of v as of v's turn
+    std::vector<uint32_t> weight(M, 0);     // scratch: weight towards each community
+    std::vector<int32_t> touched;
+    std::vector<char> done(M, 0);           // vertex has had its turn
+    for (int64_t i = 0; i < M; ++i) { up[i] = (int32_t)i; dsum[i] = gptr[i + 1] - gptr[i]; }
+    auto find = [&](int32_t x) {
+        while (up[x] != x) { up[x] = up[up[x]]; x = up[x]; }
+        return x;
+    };
+    for (int64_t step = 0; step < M; ++step) {
+        const int32_t v = order[step];
+        touched.clear();
+        auto add = [&](int32_t y, uint32_t w) {
+            int32_t r = find(y);
+            if (r == v) return;
+            if (weight[r] == 0) touched.push_back(r);
+            weight[r] += w;
+        };
+        for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) add(gadj[p], 1);
+        for (int32_t c = first_child[v]; c >= 0; c = next_sibling[c]) {
+            for (const Edge& e : agg[c]) add(e.to, e.w);
+            std::vector<Edge>().swap(agg[c]);
+        }
+        int32_t best = -1;
+        int64_t best_s = 0;
+        for (int32_t r : touched) {
+            int64_t s = (int64_t)weight[r] * two_m - dsum[r] * dsum[v];
+            if (best < 0 || s > best_s || (s == best_s && r < best)) { best = r; best_s = s; }
+        }
+        const bool merge = best >= 0 && best_s > 0;
+        // v's edge list is needed later only if the community it joins has its turn still ahead
+        if (merge && !done[best]) {
+            auto& mine = agg[v];
+            mine.reserve(touched.size());
+            for (int32_t r : touched) mine.push_back(Edge{r, weight[r]});
+        }
+        for (int32_t r : touched) weight[r] = 0;
+        if (merge) {
+            parent[v] = best;
+            up[v] = best;
+            if (last_child[best] < 0) first_child[best] = v; else next_sibling[last_child[best]] = v;
+            last_child[best] = v;
+            dsum[best] += dsum[v];
+        }
+        done[v] = 1;
+    }
+}
+
+}  // namespace
+
+void reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
+                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent) {
+    std::vector<int64_t> gptr;
+    std::vector<int32_t> gadj;
+    build_graph(M, rowptr, colidx, gptr, gadj);
+    std::vector<int32_t> first_child, next_sibling;
+    build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling);
+    std::vector<int32_t>().swap(gadj);
+    std::vector<int64_t>().swap(gptr);
+
+    // leaf sequence and segments
+    std::vector<int32_t> seq;
+    std::vector<int64_t> seg_start;
+    seq.reserve(M);
+    std::vector<int32_t> stack;
+    for (int64_t r = 0; r < M; ++r) {
+        if (parent[r] >= 0) continue;
+        const int64_t tree_begin = (int64_t)seq.size();
+        // iterative pre-order: children pushed in reverse so that the first child pops first
+        stack.push_back((int32_t)r);
+        while (!stack.empty()) {
+            int32_t x = stack.back();
+            stack.pop_back();
+            seq.push_back(x);
+            const size_t mark = stack.size();
+            for (int32_t c = first_child[x]; c >= 0; c = next_sibling[c]) stack.push_back(c);
+            std::reverse(stack.begin() + mark, stack.end());
+        }
+        for (int64_t s = tree_begin; s < (int64_t)seq.size(); s += seg_len) seg_start.push_back(s);
+    }
+    seg_start.push_back(M);
+    perm.resize(M);
+    iperm.resize(M);
+
+    // Step II, one segment at a time (segments are independent)
+    const int64_t nseg = (int64_t)seg_start.size() - 1;
+    parallel_chunks(nseg, 8, [&](int64_t sb, int64_t se) {
+        std::vector<std::pair<int32_t, int32_t>> cp;  // (column, position in segment)
+        std::vector<int32_t> col_begin, count, hit;
+        std::vector<char> visited;
+        for (int64_t sg = sb; sg < se; ++sg) {
+            const int64_t b = seg_start[sg], n = seg_start[sg + 1] - b;
+            if (n == 1) { perm[b] = seq[b]; continue; }
+            cp.clear();
+            for (int64_t q = 0; q < n; ++q) {
+                const int32_t row = seq[b + q];
+                for (int64_t p = rowptr[row]; p < rowptr[row + 1]; ++p) cp.push_back({colidx[p], (int32_t)q});
+            }
+            std::sort(cp.begin(), cp.end());
+            visited.assign(n, 0);
+            count.assign(n, 0);
+            int64_t out = b;
+            for (int64_t cur = 0; cur < n; ++cur) {
+                if (visited[cur]) continue;
+                int64_t v = cur;
+                for (;;) {
+                    visited[v] = 1;
+                    perm[out++] = seq[b + v];
+                    hit.clear();
+                    const int32_t row = seq[b + v];
+                    for (int64_t p = rowptr[row]; p < rowptr[row + 1]; ++p) {
+                        auto it = std::lower_bound(cp.begin(), cp.end(), std::make_pair(colidx[p], (int32_t)-1));
+                        for (; it != cp.end() && it->first == colidx[p]; ++it) {
+                            if (visited[it->second]) continue;
+                            if (count[it->second]++ == 0) hit.push_back(it->second);
+                        }
+                    }
+                    int64_t best = -1;
+                    int32_t best_n = 0;
+                    for (int32_t q : hit) {
+                        if (count[q] > best_n || (count[q] == best_n && q < best)) { best = q; best_n = count[q]; }
+                        count[q] = 0;
+                    }
+                    if (best < 0) break;
+                    v = best;
+                }
+            }
+        }
+    });
+    parallel_chunks(M, 1 << 16, [&](int64_t b, int64_t e) {
+        for (int64_t r = b; r < e; ++r) iperm[perm[r]] = (int32_t)r;
+    });
+}
+
+}  // namespace accspmm

@@ -1,0 +1,180 @@
+"""CPU-only checks of the library: it loads, exports what the header declares, mirrors the
+header's structs, validates its input, fails loudly without a GPU, and its two host stages
+(reordering, schedule) agree with the oracle."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2501_09251_amd as acc
+import workloads as wl
+from _util import csr_from_rows, csr_from_edges, random_sym_csr, random_csr
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "acc_spmm.h")
+
+
+def _has_gpu():
+    n = ctypes.c_int(0)
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")
+        return hip.hipGetDeviceCount(ctypes.byref(n)) == 0 and n.value > 0
+    except OSError:
+        return False
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(HEADER).read()
+    declared = set(re.findall(r"ACC_SPMM_API\s+[\w\*\s]+?\b(acc_spmm_\w+)\s*\(", text))
+    assert declared == set(acc.EXPORTED_SYMBOLS)
+    L = acc.load()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_ctypes_structs_mirror_the_header(tmp_path):
+    fields_o = [f for f, _ in acc.acc_spmm_options._fields_]
+    fields_s = [f for f, _ in acc.acc_spmm_stats._fields_]
+    prog = ['#include <stdio.h>', '#include <stddef.h>', '#include "acc_spmm.h"', 'int main(void){',
+            'printf("%zu %zu\\n", sizeof(acc_spmm_options), sizeof(acc_spmm_stats));']
+    prog += [f'printf("%zu\\n", offsetof(acc_spmm_options, {f}));' for f in fields_o]
+    prog += [f'printf("%zu\\n", offsetof(acc_spmm_stats, {f}));' for f in fields_s]
+    prog += ['return 0;}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(prog))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    out = subprocess.check_output([str(exe)]).decode().split()
+    assert int(out[0]) == ctypes.sizeof(acc.acc_spmm_options) and int(out[1]) == ctypes.sizeof(acc.acc_spmm_stats)
+    offs = [int(x) for x in out[2:]]
+    assert offs[:len(fields_o)] == [getattr(acc.acc_spmm_options, f).offset for f in fields_o]
+    assert offs[len(fields_o):] == [getattr(acc.acc_spmm_stats, f).offset for f in fields_s]
+
+
+def _plan_error(M, K, rowptr, colidx, vals, **opt):
+    with pytest.raises(acc.AccSpmmError) as e:
+        h = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals, acc.make_options(**opt) if opt else None)
+        acc.acc_spmm_destroy(h)
+        raise AssertionError("plan unexpectedly succeeded")
+    return e.value.code
+
+
+def test_invalid_input_is_reported_not_crashed():
+    v = lambda n: np.zeros(n, np.uint16)
+    assert _plan_error(2, 4, [0, 2, 1], [0, 1], v(2)) == -2            # rowptr decreases
+    assert _plan_error(2, 4, [0, 1, 1], [0, 1], v(2)) == -2            # rowptr[M] != nnz
+    assert _plan_error(2, 4, [0, 1, 2], [0, 4], v(2)) == -2            # column out of range
+    assert _plan_error(2, 4, [0, 1, 2], [0, -1], v(2)) == -2
+    assert _plan_error(1, 4, [0, 3], [2, 0, 2], v(3)) == -2            # duplicate column (unsorted row)
+    assert _plan_error(1, 4, [1, 1], [], v(0)) == -2                   # rowptr[0] != 0
+    assert _plan_error(1, 4, [0, 1], [0], v(1), window_height=12, tile_width=16) == -3
+    assert _plan_error(1, 4, [0, 1], [0], v(1), reorder=7) == -1
+    bad = acc.make_options()
+    bad.struct_size = 3
+    with pytest.raises(acc.AccSpmmError) as e:
+        acc.acc_spmm_plan_ex(1, 4, 1, [0, 1], [0], v(1), bad)
+    assert e.value.code == -1
+    code, msg = acc.acc_spmm_last_error()
+    assert code == -1 and "struct_size" in msg
+
+
+@pytest.mark.skipif(_has_gpu(), reason="only meaningful on a machine without a GPU")
+def test_no_gpu_means_a_loud_error_not_a_fallback():
+    code = _plan_error(2, 2, [0, 1, 2], [0, 1], np.zeros(2, np.uint16))
+    assert code == -5 and "no HIP device" in acc.acc_spmm_last_error()[1]
+
+
+# --------------------------------------------------------------- host stage: reordering
+@pytest.mark.parametrize("seed", range(6))
+def test_reorder_host_equals_oracle_on_random_graphs(seed):
+    rng = np.random.default_rng(seed)
+    M = int(rng.integers(30, 400))
+    if seed % 2:
+        rowptr, colidx, _ = random_sym_csr(rng, M, float(rng.uniform(1, 10)))
+    else:
+        rowptr, colidx, _ = random_csr(rng, M, M, 0.03, empty_row_frac=0.2)
+    for seg in (5, 64, 1024):
+        perm, iperm, parent = acc.acc_spmm_reorder_host(M, len(colidx), rowptr, colidx, seg)
+        oparent, ochild = oracle.dendrogram(rowptr, colidx)
+        operm, oiperm = oracle.ordering(rowptr, colidx, oparent, ochild, seg)
+        np.testing.assert_array_equal(parent, oparent)
+        np.testing.assert_array_equal(perm, operm)
+        np.testing.assert_array_equal(iperm, oiperm)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(1, 0), (2, 5), (3, 6), (4, 3), (5, 8)])
+def test_reorder_host_equals_oracle_on_the_workloads(cfg, shrink):
+    w = wl.config(cfg, shrink, with_B=False)
+    perm, iperm, parent = acc.acc_spmm_reorder_host(w.M, w.nnz, w.rowptr, w.colidx)
+    operm, oiperm = oracle.reorder(w.rowptr, w.colidx)
+    np.testing.assert_array_equal(perm, operm)
+    np.testing.assert_array_equal(iperm, oiperm)
+    assert sorted(perm.tolist()) == list(range(w.M))
+
+
+def test_reorder_host_accepts_unsorted_rows_and_special_graphs():
+    rowptr, colidx, _ = csr_from_rows([[3, 1], [0], [], [0, 2]])
+    perm, _, _ = acc.acc_spmm_reorder_host(4, 5, rowptr, colidx)
+    srp, sci, _ = csr_from_rows([[1, 3], [0], [], [0, 2]])
+    np.testing.assert_array_equal(perm, oracle.reorder(srp, sci)[0])
+    for M, edges in ((12, [(0, i) for i in range(1, 12)]), (5, []), (9, [(i, i + 1) for i in range(8)])):
+        rowptr, colidx, _ = csr_from_edges(M, edges)
+        perm, _, _ = acc.acc_spmm_reorder_host(M, len(colidx), rowptr, colidx, 4)
+        np.testing.assert_array_equal(perm, oracle.reorder(rowptr, colidx, 4)[0])
+
+
+# ----------------------------------------------------------------- host stage: schedule
+def _check_schedule(rwo, items, cap, balanced, slots):
+    W = len(rwo) - 1
+    covered_w = np.zeros(W, np.int32)
+    tiles = np.zeros(int(rwo[-1]), np.int32)
+    seen_slots = []
+    for w0, w1, t0, t1 in items.tolist():
+        if w1 < 0:                                   # slice of a heavy window
+            assert rwo[w0] <= t0 < t1 <= rwo[w0 + 1] and t1 - t0 <= cap
+            assert rwo[w0 + 1] - rwo[w0] > cap
+            seen_slots.append(-w1 - 1)
+        else:                                        # run of whole windows
+            assert 0 <= w0 < w1 <= W and t0 == rwo[w0] and t1 == rwo[w1]
+            covered_w[w0:w1] += 1
+            if balanced:
+                assert t1 - t0 <= cap or w1 - w0 == 1
+        tiles[t0:t1] += 1
+    assert np.all(tiles == 1)                        # every tile exactly once
+    heavy = np.diff(rwo) > cap if balanced else np.zeros(W, bool)
+    assert np.all(covered_w[~heavy] == 1) and np.all(covered_w[heavy] == 0)   # every window written once
+    assert sorted(seen_slots) == list(range(slots))
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_schedule_partitions_tiles_and_windows(seed):
+    rng = np.random.default_rng(seed)
+    W = int(rng.integers(1, 300))
+    t = rng.integers(0, 12, W)
+    t[rng.integers(0, W, 3)] = rng.integers(100, 2000, 3)     # a few heavy windows
+    t[rng.integers(0, W, 10)] = 0                             # and empty ones
+    rwo = np.concatenate([[0], np.cumsum(t)]).astype(np.int32)
+    expect_ibd = np.abs(t - t.mean()).mean()                  # Eq. 3, written out
+    for cap in (16, 64):
+        items, ibd, slots = acc.acc_spmm_schedule_host(rwo, acc.ACC_SPMM_ON, cap)
+        assert abs(ibd - expect_ibd) < 1e-9
+        _check_schedule(rwo, items, cap, True, slots)
+    items, _, slots = acc.acc_spmm_schedule_host(rwo, acc.ACC_SPMM_OFF, 16)
+    assert len(items) == W and slots == 0
+    _check_schedule(rwo, items, 16, False, 0)
+
+
+def test_schedule_auto_follows_the_ibd_threshold():
+    flat = np.arange(0, 101 * 5, 5, dtype=np.int32)            # every window has 5 tiles: IBD = 0
+    items, ibd, _ = acc.acc_spmm_schedule_host(flat, acc.ACC_SPMM_AUTO, 64)
+    assert ibd == 0 and len(items) == 100                      # not applied: one item per window
+    t = np.array([0] * 99 + [4000])
+    skew = np.concatenate([[0], np.cumsum(t)]).astype(np.int32)
+    items, ibd, slots = acc.acc_spmm_schedule_host(skew, acc.ACC_SPMM_AUTO, 64)
+    assert ibd > 8 and slots == -(-4000 // 64)
+    items2, _, _ = acc.acc_spmm_schedule_host(skew, acc.ACC_SPMM_AUTO, 64, ibd_threshold=1e9)
+    assert len(items2) == 100

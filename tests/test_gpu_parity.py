@@ -1,0 +1,267 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle.
+
+Tolerance for C (fp16 inputs, exact fp16 x fp16 products, fp32 accumulation in any order):
+|C - C_ref| <= 2e-3 * (|A|.|B|) + 1e-5 elementwise.  Format arrays and the permutation are
+compared bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2501_09251_amd as acc
+import workloads as wl
+from _util import csr_from_rows, random_csr, f16
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    acc.load()
+
+
+def run_spmm(plan, B_u16, M, N, naive=False):
+    dev = torch.device("cuda:0")
+    Bd = torch.from_numpy(B_u16.view(np.int16)).to(dev)
+    # poison C: every element must be overwritten
+    C = torch.full((max(M, 1), N), float("nan"), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    (acc.acc_spmm_execute_csr_naive if naive else acc.acc_spmm_execute)(plan, Bd, N, C, stream)
+    torch.cuda.synchronize()
+    return C[:M].cpu().numpy()
+
+
+def check_against_oracle(rowptr, colidx, vals, B, C, rows=None):
+    C_ref, bound = oracle.spmm(rowptr, colidx, vals, B, rows=rows)
+    got = C if rows is None else C[rows]
+    ok, ratio = oracle.within_bound(got, C_ref, bound)
+    assert ok, f"outside tolerance, worst error/limit = {ratio}"
+    return ratio
+
+
+def check_format(plan, rowptr, colidx, vals, WH=16, TW=16):
+    perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
+    fmt = oracle.encode(rowptr, colidx, vals, perm, WH, TW)
+    for which, key in ((acc.ACC_SPMM_ARR_ROW_WINDOW_OFFSET, "row_window_offset"), (acc.ACC_SPMM_ARR_TC_OFFSET, "tc_offset"),
+                       (acc.ACC_SPMM_ARR_SPARSE_A_TO_B, "sparse_a_to_b"), (acc.ACC_SPMM_ARR_TC_LOCAL_BIT, "tc_local_bit"),
+                       (acc.ACC_SPMM_ARR_VALUES, "vals")):
+        np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, which), fmt[key], err_msg=key)
+    return perm, fmt
+
+
+def sorted_rows(rowptr, colidx, vals):
+    """Oracle input must have ascending columns; the library accepts any order."""
+    ci, va = colidx.copy(), vals.copy()
+    for i in range(len(rowptr) - 1):
+        s = slice(rowptr[i], rowptr[i + 1])
+        o = np.argsort(ci[s], kind="stable")
+        ci[s], va[s] = ci[s][o], va[s][o]
+    return ci, va
+
+
+# ------------------------------------------------------------------ small, element by element
+@pytest.mark.parametrize("cfg,shrink", [(1, 0), (2, 6), (3, 6), (4, 4), (5, 7)])
+@pytest.mark.parametrize("mode", ["default", "plain"])
+def test_workloads_small_full_comparison(cfg, shrink, mode):
+    w = wl.config(cfg, shrink)
+    opt = None if mode == "default" else acc.make_options(reorder=acc.ACC_SPMM_OFF, load_balance=acc.ACC_SPMM_OFF)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+    try:
+        perm, fmt = check_format(plan, w.rowptr, w.colidx, w.vals)
+        st = acc.acc_spmm_plan_stats(plan)
+        assert st["num_tiles"] == len(fmt["tc_offset"]) - 1 and st["nnz"] == w.nnz
+        assert abs(st["ibd"] - oracle.ibd(fmt["row_window_offset"])) < 1e-9
+        if st["reorder_applied"]:
+            np.testing.assert_array_equal(perm, oracle.reorder(w.rowptr, w.colidx)[0])
+        else:
+            np.testing.assert_array_equal(perm, np.arange(w.M))
+        C = run_spmm(plan, w.B, w.M, w.N)
+        check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("N", [16, 32, 64, 128, 256, 384, 512])
+@pytest.mark.parametrize("lb", [acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON])
+def test_all_widths_with_and_without_load_balancing(N, lb):
+    rng = np.random.default_rng(N + lb)
+    M, K = 333, 500                                    # several windows, ragged tail (333 = 20*16 + 13)
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.04)
+    # one heavy row so that its window is split when balancing with a small cap
+    heavy = np.sort(rng.choice(K, 450, replace=False)).astype(np.int32)
+    rows = [colidx[rowptr[i]:rowptr[i + 1]].tolist() for i in range(M)]
+    rows[40] = heavy.tolist()
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    B = f16(rng.standard_normal((K, N)))
+    plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                acc.make_options(load_balance=lb, max_tiles_per_item=8, keep_csr=1))
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        assert (st["num_split_windows"] >= 1) == (lb == acc.ACC_SPMM_ON)
+        check_format(plan, rowptr, colidx, vals)
+        C = run_spmm(plan, B, M, N)
+        check_against_oracle(rowptr, colidx, vals, B, C)
+        C2 = run_spmm(plan, B, M, N)
+        np.testing.assert_array_equal(C, C2)          # fixed summation order: bitwise repeatable
+        Cn = run_spmm(plan, B, M, N, naive=True)
+        check_against_oracle(rowptr, colidx, vals, B, Cn)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_identity_and_permutation_matrices_are_exact():
+    rng = np.random.default_rng(0)
+    n, N = 100, 64
+    B = f16(rng.standard_normal((n, N)))
+    p = rng.permutation(n)
+    for cols in (np.arange(n), p):
+        rowptr, colidx, vals = csr_from_rows([[int(c)] for c in cols], np.ones(n))
+        plan = acc.acc_spmm_plan(n, n, n, rowptr, colidx, vals)
+        try:
+            C = run_spmm(plan, B, n, N)
+            np.testing.assert_array_equal(C, B.view(np.float16).astype(np.float32)[cols])
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+
+def test_reordering_is_invisible_in_C():
+    w = wl.config(4, 5)
+    out = []
+    for ro in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON):
+        plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(reorder=ro))
+        try:
+            st = acc.acc_spmm_plan_stats(plan)
+            assert st["reorder_applied"] == (ro == acc.ACC_SPMM_ON)
+            out.append((run_spmm(plan, w.B, w.M, w.N), st["num_tiles"]))
+        finally:
+            acc.acc_spmm_destroy(plan)
+    for C, _ in out:
+        check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C)
+    assert out[1][1] < 0.7 * out[0][1]                # the hidden blocks are recovered: far fewer tiles
+
+
+def test_linearity_in_B_exact_on_small_integers():
+    rng = np.random.default_rng(5)
+    M = K = 200
+    rowptr, colidx, _ = random_csr(rng, M, K, 0.05)
+    vals = f16(rng.integers(-4, 5, len(colidx)))
+    B1 = rng.integers(-8, 9, (K, 32)).astype(np.float64)
+    B2 = rng.integers(-8, 9, (K, 32)).astype(np.float64)
+    plan = acc.acc_spmm_plan(M, K, len(colidx), rowptr, colidx, vals)
+    try:
+        C1, C2, C12 = (run_spmm(plan, f16(b), M, 32) for b in (B1, B2, 4 * B1 + B2))
+        np.testing.assert_array_equal(C12, 4 * C1 + C2)     # all sums are small integers: exact in fp32
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+# ------------------------------------------------------------------------------- edge cases
+def test_edge_cases():
+    rng = np.random.default_rng(9)
+    N = 32
+    # (M, K, rows)
+    cases = {
+        "empty matrix rows": (5, 7, [[] for _ in range(5)]),
+        "single entry": (1, 1, [[0]]),
+        "fewer rows than a window": (3, 40, [[0, 39], [], [5, 6, 7]]),
+        "first window empty": (40, 10, [[] for _ in range(16)] + [[i % 10] for i in range(24)]),
+        "exactly one full tile": (16, 16, [list(range(16)) for _ in range(16)]),
+        "17 columns: second tile padded": (16, 17, [list(range(17)) for _ in range(16)]),
+        "rectangular wide": (20, 3000, [sorted(rng.choice(3000, 50, replace=False).tolist()) for _ in range(20)]),
+        "rectangular tall": (300, 5, [[int(rng.integers(0, 5))] for _ in range(300)]),
+        "unsorted columns": (2, 9, [[8, 0, 3], [2, 1]]),
+    }
+    for name, (M, K, rows) in cases.items():
+        rowptr, colidx, _ = csr_from_rows(rows)
+        vals = f16(rng.uniform(-1, 1, len(colidx)))
+        B = f16(rng.standard_normal((K, N)))
+        for lb in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON):
+            plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                        acc.make_options(load_balance=lb, max_tiles_per_item=2, keep_csr=1))
+            try:
+                sci, sva = sorted_rows(rowptr, colidx, vals)
+                check_format(plan, rowptr, sci, sva)
+                C = run_spmm(plan, B, M, N)
+                check_against_oracle(rowptr, sci, sva, B, C)
+                Cn = run_spmm(plan, B, M, N, naive=True)
+                check_against_oracle(rowptr, sci, sva, B, Cn)
+            finally:
+                acc.acc_spmm_destroy(plan)
+    # M == 0
+    plan = acc.acc_spmm_plan(0, 4, 0, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.uint16))
+    acc.acc_spmm_execute(plan, torch.zeros(4, N, dtype=torch.float16, device="cuda"), N,
+                         torch.zeros(1, N, device="cuda"), None)
+    acc.acc_spmm_destroy(plan)
+
+
+def test_paper_geometry_8x8_format_and_closed_form_size():
+    w = wl.config(2, 7)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(window_height=8, tile_width=8, reorder=acc.ACC_SPMM_ON))
+    try:
+        perm, fmt = check_format(plan, w.rowptr, w.colidx, w.vals, 8, 8)
+        np.testing.assert_array_equal(perm, oracle.reorder(w.rowptr, w.colidx)[0])
+        st = acc.acc_spmm_plan_stats(plan)
+        # Section 3.3: (ceil(M/8) + NumTCBlock*11 + 2) * 4 bytes
+        assert st["index_bytes"] == (-(-w.M // 8) + 11 * st["num_tiles"] + 2) * 4
+        with pytest.raises(acc.AccSpmmError) as e:
+            run_spmm(plan, w.B, w.M, w.N)
+        assert e.value.code == -3
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_execute_argument_errors():
+    rowptr, colidx, vals = csr_from_rows([[0]])
+    plan = acc.acc_spmm_plan(1, 1, 1, rowptr, colidx, vals)
+    try:
+        B = torch.zeros(1, 48, dtype=torch.float16, device="cuda")
+        C = torch.zeros(1, 48, device="cuda")
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_execute(plan, B, 48, C, None)
+        assert e.value.code == -3
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_execute(plan, B, 32, None, None)
+        assert e.value.code == -1
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_execute_csr_naive(plan, B, 32, C, None)    # built without keep_csr
+        assert e.value.code == -1
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+# -------------------------------------------------- full size, as the benchmark launches it
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_sampled_rows(cfg):
+    print(f"[full-size] generating workload {cfg}", flush=True)
+    w = wl.config(cfg)
+    print(f"[full-size] planning {w.name}: M={w.M} nnz={w.nnz}", flush=True)
+    plan = acc.acc_spmm_plan(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals)     # defaults, as bench.py
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        print(f"[full-size] plan: {st}", flush=True)
+        perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
+        assert np.array_equal(np.sort(perm), np.arange(w.M))                       # a bijection
+        rwo = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_ROW_WINDOW_OFFSET)
+        tco = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_TC_OFFSET)
+        assert rwo[-1] == st["num_tiles"] and tco[-1] == w.nnz and np.all(np.diff(tco) >= 1)
+        items = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_WORK_ITEMS).reshape(-1, 4)
+        assert (items[:, 3] - items[:, 2]).sum() == st["num_tiles"]
+        print("[full-size] executing", flush=True)
+        C = run_spmm(plan, w.B, w.M, w.N)
+        assert np.isfinite(C).all()
+        rng = np.random.default_rng(cfg)
+        deg = np.diff(w.rowptr)
+        rows = np.unique(np.concatenate([
+            rng.integers(0, w.M, 3000), np.argsort(deg)[-40:], np.arange(64), np.arange(w.M - 64, w.M),
+            np.nonzero(deg == 0)[0][:200]]))
+        print(f"[full-size] checking {len(rows)} rows against the oracle", flush=True)
+        ratio = check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C, rows=rows)
+        print(f"[full-size] worst error/limit = {ratio:.3g}", flush=True)
+    finally:
+        acc.acc_spmm_destroy(plan)

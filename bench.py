@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpMM hot path on one MI355X.
+
+One "step" is one acc_spmm_execute (tile kernel + split-window combine) on a workload whose
+plan was built once beforehand; plan time is reported separately (the paper amortises its
+preprocessing over iterative use, Section 4.3.2).  Prints ONE JSON line:
+
+  value       effective GFLOP/s = 2*nnz*N / t_step, inputs resident in HBM
+  roofline    algorithmic bytes of the tile kernel (A values + A indices + each window's
+              distinct B rows + C, counted from the plan) / its average duration measured
+              with HIP events on the launch stream, against 8 TB/s
+  cpu_baseline  the fp64 CSR oracle timed on the host cores on a bounded row sample
+  naive_gpu   the one-wavefront-per-row CSR kernel on the same inputs
+
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--shrink S]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PAPER_CONTEXT = ("paper reports speedups over cuSPARSE only (avg 2.52x RTX 4090, 1.91x A800, 1.58x H100, TF32); "
+                 "no absolute throughput is published")
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 of BASELINE.json (default: 5, the metric's config)")
+    ap.add_argument("--shrink", type=int, default=0, help="divide the row count by 2^shrink (debugging)")
+    ap.add_argument("--reorder", choices=["off", "on", "auto"], default="auto")
+    ap.add_argument("--load-balance", choices=["off", "on", "auto"], default="auto")
+    ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
+    ap.add_argument("--no-prefetch", action="store_true")
+    ap.add_argument("--plain-stores", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-naive", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2501_09251_amd as acc
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+    acc.load()
+    dev = torch.device("cuda:0")
+    mode = {"off": acc.ACC_SPMM_OFF, "on": acc.ACC_SPMM_ON, "auto": acc.ACC_SPMM_AUTO}
+
+    t0 = time.time()
+    w = wl.config(args.config, args.shrink)
+    t_gen = time.time() - t0
+    log(f"[bench] workload {w.name}: M={w.M} nnz={w.nnz} N={w.N} generated in {t_gen:.1f}s")
+
+    t0 = time.time()
+    opt = acc.make_options(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
+                           max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
+                           no_prefetch=int(args.no_prefetch), plain_stores=int(args.plain_stores))
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+    t_plan = time.time() - t0
+    st = acc.acc_spmm_plan_stats(plan)
+    tr = acc.acc_spmm_plan_traffic(plan, w.N)
+    log(f"[bench] plan built in {t_plan:.1f}s: tiles={st['num_tiles']} items={st['num_items']} "
+        f"split={st['num_split_windows']} ibd={st['ibd']:.2f} reorder={st['reorder_applied']} lb={st['load_balance_applied']}")
+
+    B = torch.from_numpy(w.B.view(np.int16)).to(dev)
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    torch.cuda.synchronize()
+
+    # ---- timed region: W warm-ups, then exactly K steps between two synchronisations
+    for _ in range(args.warmup):
+        acc.acc_spmm_execute(plan, B, w.N, C, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        acc.acc_spmm_execute(plan, B, w.N, C, stream)
+    torch.cuda.synchronize()
+    t_step = (time.perf_counter() - t0) / args.steps
+    flops = 2.0 * w.nnz * w.N
+    value = flops / t_step / 1e9
+
+    # ---- per-kernel durations (HIP events on the launch stream), same launches
+    tiles_ms, combine_ms = [], []
+    for _ in range(args.steps):
+        a, b = acc.acc_spmm_execute_timed(plan, B, w.N, C, stream)
+        tiles_ms.append(a)
+        combine_ms.append(b)
+    tiles_avg = float(np.mean(tiles_ms))
+    alg_bytes = tr["a_bytes"] + tr["b_bytes"] + tr["c_bytes"]
+    achieved = alg_bytes / (tiles_avg * 1e-3) / 1e9 if tiles_avg > 0 else 0.0
+
+    # ---- spot check of the timed result against the oracle (sampled rows)
+    import oracle
+    rng = np.random.default_rng(1)
+    rows = np.unique(np.concatenate([rng.integers(0, w.M, 512), np.argsort(np.diff(w.rowptr))[-8:]]))
+    C_rows = C[torch.from_numpy(rows).to(dev)].cpu().numpy()
+    C_ref, bound = oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=rows)
+    ok, ratio = oracle.within_bound(C_rows, C_ref, bound)
+    log(f"[bench] parity spot check on {len(rows)} rows: ok={ok} worst error/limit={ratio:.3g}")
+
+    # ---- naive GPU baseline
+    naive = None
+    if not args.no_naive:
+        acc.acc_spmm_execute_csr_naive(plan, B, w.N, C, stream)
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            acc.acc_spmm_execute_csr_naive(plan, B, w.N, C, stream)
+        torch.cuda.synchronize()
+        t_naive = (time.perf_counter() - t0) / reps
+        naive = {"value": flops / t_naive / 1e9, "unit": "GFLOP/s", "ms": t_naive * 1e3,
+                 "kind": "one wavefront per CSR row, fp32 FMA"}
+
+    # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows
+    cpu = None
+    if not args.no_cpu_baseline:
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        probe = rng.integers(0, w.M, 4096).astype(np.int64)
+        t0 = time.perf_counter()
+        oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=probe, want_bound=False)
+        dt = max(time.perf_counter() - t0, 1e-4)
+        per_row = dt / len(probe)
+        n_rows = int(min(w.M, max(4096, args.cpu_seconds / per_row)))
+        sample = np.sort(rng.choice(w.M, n_rows, replace=False)).astype(np.int64) if n_rows < w.M else np.arange(w.M, dtype=np.int64)
+        nnz_s = int((w.rowptr[sample + 1] - w.rowptr[sample]).sum())
+        t0 = time.perf_counter()
+        oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=sample, want_bound=False)
+        dt = time.perf_counter() - t0
+        cpu = {"value": 2.0 * nnz_s * w.N / dt / 1e9, "unit": "GFLOP/s", "cores": threads, "kind": "oracle",
+               "sample": f"{n_rows} random rows ({nnz_s} nnz) of the same workload, fp64 CSR SpMM, {dt:.1f}s"}
+
+    acc.acc_spmm_destroy(plan)
+    out = {
+        "metric": "SpMM effective GFLOP/s (2*nnz*N/t)",
+        "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
+                   "reorder": args.reorder, "load_balance": args.load_balance},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
+                     "combine_ms_avg": float(np.mean(combine_ms)),
+                     "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"],
+                     "c_bytes": tr["c_bytes"], "b_bytes_upper_nnzN2": 2 * w.nnz * w.N, "b_bytes_lower_KN2": 2 * w.K * w.N,
+                     "mfma_flops_issued": tr["mfma_flops"]},
+        "cpu_baseline": cpu,
+        "naive_gpu": naive,
+        "plan": {"seconds": t_plan, "validate_s": st["t_validate_s"], "reorder_s": st["t_reorder_s"],
+                 "encode_s": st["t_encode_s"], "schedule_s": st["t_schedule_s"],
+                 "tiles": st["num_tiles"], "tiles_identity_order": st["num_tiles_identity"],
+                 "mean_nnz_per_tile": st["mean_nnz_per_tile"], "ibd": st["ibd"], "items": st["num_items"],
+                 "split_windows": st["num_split_windows"], "partial_slots": st["num_partial_slots"],
+                 "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"]},
+        "parity_spot_check": {"rows": int(len(rows)), "ok": bool(ok), "worst_error_over_limit": ratio},
+        "generate_s": t_gen,
+        "paper_context": PAPER_CONTEXT,
+    }
+    print(json.dumps(out))
+    return 0 if ok else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

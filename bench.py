@@ -50,7 +50,9 @@ def main() -> int:
     ap.add_argument("--plain-stores", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-naive", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel on 1 GiB (for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
@@ -88,6 +90,14 @@ def main() -> int:
     C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     torch.cuda.synchronize()
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            acc.acc_spmm_calibration_copy(dst, src, src.numel() * 4, stream)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: W warm-ups, then exactly K steps between two synchronisations
     for _ in range(args.warmup):

@@ -51,7 +51,9 @@ typedef struct {
     int32_t struct_size;
     /* Row reordering (Section 3.2, Algorithm 1).  OFF: identity.  ON: always apply.
      * AUTO (default when struct is NULL): compute it, keep it only if it lowers the number
-     * of tiles (the paper notes in Section 4.3.5 that reordering can lose).
+     * of tiles (the paper notes in Section 4.3.5 that reordering can lose); AUTO also stops
+     * the dendrogram construction, and keeps the identity, once it has visited 8 edge
+     * records per graph entry (large uniform meshes, where nothing is gained).
      * Requires M == K; for M != K the dendrogram step is skipped and the order is the
      * identity. */
     int32_t reorder;
@@ -98,6 +100,7 @@ typedef struct {
     double mean_nnz_per_tile;   /* MeanNNZTC (Section 4.3.1) = nnz / T                       */
     int64_t index_bytes;        /* RowWindowOffset + TCOffset + SparseAToB + TCLocalBit      */
     int64_t schedule_bytes;     /* work items + permutation                                  */
+    double reorder_work_ratio;  /* dendrogram edge-record visits per graph entry (0 if not run)  */
     double t_validate_s, t_reorder_s, t_encode_s, t_schedule_s, t_total_s;
 } acc_spmm_stats;
 
@@ -191,12 +194,22 @@ ACC_SPMM_API int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, i
 ACC_SPMM_API int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst, size_t* bytes);
 
 /*
+ * Measurement aid: a plain streaming copy kernel (16 bytes per lane, grid-stride) that
+ * reads `bytes` from src and writes them to dst (both DEVICE, 16-byte aligned, bytes a
+ * multiple of 16).  Hardware counters read for it calibrate the counters read for the
+ * SpMM kernels.
+ */
+ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/*
  * The two host-side stages of acc_spmm_plan, callable on their own (no GPU needed).
  *
  * acc_spmm_reorder_host: the row reordering of Section 3.2 (Algorithm 1) for a square
  * M x M pattern.  csr_rowptr / csr_colidx as for acc_spmm_plan (HOST).  segment_length
  * 0 = default.  Outputs, HOST int32[M] each: perm (new -> input row), iperm (its inverse),
  * parent (dendrogram: community each vertex was merged into, -1 for roots; may be NULL).
+ * *work_ratio (may be NULL) receives the dendrogram step's edge-record visits per graph
+ * entry (vertices + directed edges), the quantity acc_spmm_plan's AUTO mode limits.
  *
  * acc_spmm_schedule_host: Section 3.5 for 16x16 tiles.  row_window_offset is HOST
  * int32[W+1].  load_balance / max_tiles_per_item / ibd_threshold as in acc_spmm_options.
@@ -205,7 +218,8 @@ ACC_SPMM_API int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, vo
  * capacity in items.  Returns the number of work items, or a negative acc_spmm_status.
  */
 ACC_SPMM_API int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
-                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent);
+                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent,
+                                       double* work_ratio);
 
 ACC_SPMM_API int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,
                                int32_t max_tiles_per_item, float ibd_threshold, double* ibd_out,

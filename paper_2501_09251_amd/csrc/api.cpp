@@ -21,6 +21,7 @@ double now_s() {
 constexpr int32_t kDefaultCap = 64;
 constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
+constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry
 }  // namespace
 
 void set_error(int code, const std::string& msg) {
@@ -126,11 +127,20 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         d_perm.upload(identity.data(), M);
         bool use_reorder = false;
         int64_t tiles_identity = -1;
-        double t_reorder = 0.0;
+        double t_reorder = 0.0, reorder_work = 0.0;
         if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
             const double r0 = now_s();
-            reorder_rows(M, rowptr, colidx, opt.segment_length, P.perm, P.iperm, P.parent);
+            // AUTO gives up on inputs whose dendrogram is expensive to build (large uniform
+            // meshes), where the identity order is kept anyway; ON always completes.
+            const double budget = opt.reorder == ACC_SPMM_AUTO ? kAutoReorderWorkBudget : 0.0;
+            const bool complete = reorder_rows(M, rowptr, colidx, opt.segment_length, P.perm, P.iperm, P.parent,
+                                               budget, &reorder_work);
+            if (!complete) {
+                P.parent.clear();
+                t_reorder = now_s() - r0;
+            }
             DeviceFormat probe;
+            if (complete) {
             encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
             tiles_identity = probe.T;
             DevBuf<int32_t> d_new;
@@ -139,6 +149,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
             use_reorder = opt.reorder == ACC_SPMM_ON || probe.T < tiles_identity;
             if (use_reorder) d_perm.upload(P.perm.data(), M);
             t_reorder = now_s() - r0;
+            }
         }
         if (!use_reorder) {
             P.perm = identity;
@@ -189,6 +200,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.mean_nnz_per_tile = P.fmt.T ? (double)nnz / (double)P.fmt.T : 0.0;
         st.index_bytes = 4 * (W + 1) + 4 * (P.fmt.T + 1) + 4 * P.fmt.T * TW + 8 * P.fmt.T * P.fmt.NW;
         st.schedule_bytes = (int64_t)(sizeof(WorkItem) * P.items.size() + sizeof(SplitWindow) * P.splits.size()) + 4 * W * WH;
+        st.reorder_work_ratio = reorder_work;
         st.t_validate_s = t1 - t0;
         st.t_reorder_s = t_reorder;
         st.t_encode_s = t_encode;
@@ -289,8 +301,13 @@ int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, int64_t* a_byt
     });
 }
 
+int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    return guarded([&] { launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)); });
+}
+
 int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
-                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent) {
+                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent,
+                          double* work_ratio) {
     return guarded([&] {
         if (M < 0 || nnz < 0 || !csr_rowptr || (nnz > 0 && !csr_colidx) || !perm || !iperm)
             fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
@@ -298,7 +315,8 @@ int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, con
         std::vector<uint16_t> fixed_val, dummy((size_t)nnz, 0);
         if (validate_csr(M, M, nnz, csr_rowptr, csr_colidx, dummy.data(), fixed_col, fixed_val)) csr_colidx = fixed_col.data();
         std::vector<int32_t> p, ip, par;
-        reorder_rows(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, p, ip, par);
+        reorder_rows(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, p, ip, par, 0.0,
+                     work_ratio);
         std::copy(p.begin(), p.end(), perm);
         std::copy(ip.begin(), ip.end(), iperm);
         if (parent) std::copy(par.begin(), par.end(), parent);

@@ -17,6 +17,8 @@
 // Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
 // values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
 // words of tile t+DEPTH+1 are requested one step before they are needed for addresses.
+#include <algorithm>
+
 #include "internal.h"
 
 namespace accspmm {
@@ -307,6 +309,12 @@ __global__ __launch_bounds__(256) void csr_row_per_wave_kernel(int64_t M, const 
     }
 }
 
+__global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restrict__ dst, const uintx4* __restrict__ src,
+                                                               size_t n16) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
 template <int FPL, int NS>
 void launch_variant(const ExecParams& p, int n_slab_launches, bool no_prefetch, bool plain_stores,
                     hipStream_t stream) {
@@ -390,6 +398,17 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
         ACC_HIP(hipEventElapsedTime(tiles_ms, ev[0], ev[1]));
         if (combine_ms && !plan.splits.empty()) ACC_HIP(hipEventElapsedTime(combine_ms, ev[1], ev[2]));
     }
+}
+
+void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+    if (!dst || !src || (bytes & 15) || ((reinterpret_cast<uintptr_t>(dst) | reinterpret_cast<uintptr_t>(src)) & 15))
+        fail(ACC_SPMM_ERR_INVALID_ARG, "calibration copy needs 16-byte aligned pointers and size");
+    if (!bytes) return;
+    const size_t n16 = bytes / 16;
+    const unsigned blocks = (unsigned)std::min<size_t>((n16 + 255) / 256, 256 * 64);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<uintx4*>(dst),
+                       static_cast<const uintx4*>(src), n16);
+    ACC_HIP(hipGetLastError());
 }
 
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream) {

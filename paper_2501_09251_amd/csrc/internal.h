@@ -79,8 +79,12 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
                       bool tiles_only);
 
 // reorder.cpp: Algorithm 1 on the host.  perm/iperm/parent get M entries.
-void reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
-                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent);
+// work_budget > 0 limits the dendrogram construction to that many edge-record visits per
+// graph entry (vertices + directed edges); when exceeded the function returns false and the
+// outputs are unspecified.  *work_ratio (may be null) receives the visits per graph entry.
+bool reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
+                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent,
+                  double work_budget, double* work_ratio);
 
 // schedule.cpp: Section 3.5.
 double imbalance_degree(const std::vector<int32_t>& rwo);
@@ -111,6 +115,7 @@ struct Plan {
 // tiles_ms / combine_ms non-null: time the two kernels with events and wait for them
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream,
                     float* tiles_ms = nullptr, float* combine_ms = nullptr);
+void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 
 }  // namespace accspmm

@@ -106,9 +106,11 @@ struct Edge {
 };
 
 // Step I.  parent[v] = community v was merged into (-1: root); children lists in merge order.
-void build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::vector<int32_t>& gadj,
+// `work` counts the edge records visited; when it exceeds `work_limit` (> 0) the
+// construction stops early and returns false.
+bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::vector<int32_t>& gadj,
                       std::vector<int32_t>& parent, std::vector<int32_t>& first_child,
-                      std::vector<int32_t>& next_sibling) {
+                      std::vector<int32_t>& next_sibling, int64_t work_limit, int64_t& work) {
     const int64_t two_m = gptr[M];
     // visiting order: counting sort by degree, stable in the id
     std::vector<int32_t> order(M);
@@ -134,8 +136,10 @@ void build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
         while (up[x] != x) { up[x] = up[up[x]]; x = up[x]; }
         return x;
     };
+    work = 0;
     for (int64_t step = 0; step < M; ++step) {
         const int32_t v = order[step];
+        if (work_limit > 0 && work > work_limit) return false;
         touched.clear();
         auto add = [&](int32_t y, uint32_t w) {
             int32_t r = find(y);
@@ -144,8 +148,10 @@ void build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
             weight[r] += w;
         };
         for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) add(gadj[p], 1);
+        work += gptr[v + 1] - gptr[v] + 1;
         for (int32_t c = first_child[v]; c >= 0; c = next_sibling[c]) {
             for (const Edge& e : agg[c]) add(e.to, e.w);
+            work += (int64_t)agg[c].size();
             std::vector<Edge>().swap(agg[c]);
         }
         int32_t best = -1;
@@ -171,17 +177,24 @@ void build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
         }
         done[v] = 1;
     }
+    return true;
 }
 
 }  // namespace
 
-void reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
-                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent) {
+bool reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
+                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent,
+                  double work_budget, double* work_ratio) {
     std::vector<int64_t> gptr;
     std::vector<int32_t> gadj;
     build_graph(M, rowptr, colidx, gptr, gadj);
     std::vector<int32_t> first_child, next_sibling;
-    build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling);
+    const int64_t graph_size = gptr[M] + M;
+    int64_t work = 0;
+    const bool complete = build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling,
+                                           work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0, work);
+    if (work_ratio) *work_ratio = graph_size ? (double)work / (double)graph_size : 0.0;
+    if (!complete) return false;
     std::vector<int32_t>().swap(gadj);
     std::vector<int64_t>().swap(gptr);
 
@@ -257,6 +270,7 @@ void reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32
     parallel_chunks(M, 1 << 16, [&](int64_t b, int64_t e) {
         for (int64_t r = b; r < e; ++r) iperm[perm[r]] = (int32_t)r;
     });
+    return true;
 }
 
 }  // namespace accspmm

@@ -30,6 +30,11 @@ sys.path.insert(0, ROOT)
 PAPER_CONTEXT = ("paper reports speedups over cuSPARSE only (avg 2.52x RTX 4090, 1.91x A800, 1.58x H100, TF32); "
                  "no absolute throughput is published")
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per launch of the tile kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by the library's plain copy kernel (summaries under profiles/); None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+    "rmat-2^23-deg32-N128": 63.49e9,
+}
 
 
 def log(*a):
@@ -171,7 +176,8 @@ def main() -> int:
         "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
                    "reorder": args.reorder, "load_balance": args.load_balance},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if args.reorder == "auto" and args.load_balance == "auto" else None,
                      "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
                      "combine_ms_avg": float(np.mean(combine_ms)),
                      "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"],

@@ -51,7 +51,8 @@ typedef struct {
     int32_t struct_size;
     /* Row reordering (Section 3.2, Algorithm 1).  OFF: identity.  ON: always apply.
      * AUTO (default when struct is NULL): compute it, keep it only if it lowers the number
-     * of tiles (the paper notes in Section 4.3.5 that reordering can lose); AUTO also stops
+     * of tiles by at least 4 % (the paper notes in Section 4.3.5 that reordering can lose:
+     * it gives up the locality of the input order); AUTO also stops
      * the dendrogram construction, and keeps the identity, once it has visited 8 edge
      * records per graph entry (large uniform meshes, where nothing is gained).
      * Requires M == K; for M != K the dendrogram step is skipped and the order is the
@@ -61,7 +62,7 @@ typedef struct {
      * heavy windows / pack light ones.  AUTO: apply iff IBD (Eq. 3) > ibd_threshold. */
     int32_t load_balance;
     /* Most tiles one work item may hold; heavier windows are split (Section 3.5 uses 32
-     * for 8x8x16 tiles on NVIDIA parts).  0 = default (see acc_spmm_stats.max_tiles_per_item). */
+     * for 8x8x16 tiles on NVIDIA parts).  0 = default 256. */
     int32_t max_tiles_per_item;
     /* Tile geometry: rows per row window and condensed columns per tile.  0 = default
      * (16,16), the geometry the execute kernel runs.  (8,8), the paper's geometry
@@ -78,9 +79,14 @@ typedef struct {
     /* Ablation switch: 0 = default (software-pipelined loads, Section 3.4), 1 = issue each
      * tile's loads only when the tile is computed. */
     int32_t no_prefetch;
-    /* Ablation switch: 0 = default (streaming stores for C, the counterpart of the
-     * write-through policy of Section 3.4), 1 = plain stores. */
-    int32_t plain_stores;
+    /* Cache policy of the C stores (Section 3.4 writes C through, uncached): 0 = default,
+     * ordinary stores, which measure about 5 % faster on MI355X; 1 = streaming
+     * (non-temporal) stores, the counterpart of the paper's write-through policy. */
+    int32_t streaming_stores;
+    /* Tiles of B rows kept in flight per wavefront while one tile is multiplied (1..3).
+     * 0 = default (3 for N = 128, 2 for N >= 256, 1 for N <= 64).  Ignored when no_prefetch
+     * is set. */
+    int32_t pipeline_depth;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */

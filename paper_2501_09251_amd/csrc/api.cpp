@@ -18,7 +18,8 @@ double now_s() {
     return duration<double>(steady_clock::now().time_since_epoch()).count();
 }
 
-constexpr int32_t kDefaultCap = 64;
+constexpr int32_t kDefaultCap = 256;
+constexpr double kAutoReorderMinGain = 0.04;     // AUTO keeps the reordering only for >= 4 % fewer tiles
 constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
 constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry
@@ -95,6 +96,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.segment_length == 0) opt.segment_length = kDefaultSegLen;
     if (opt.segment_length < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "segment_length must be positive");
     if (opt.ibd_threshold == 0.f) opt.ibd_threshold = kDefaultIbdThreshold;
+    if (opt.pipeline_depth < 0 || opt.pipeline_depth > 3) fail(ACC_SPMM_ERR_INVALID_ARG, "pipeline_depth must be 0..3");
 
     std::vector<int32_t> fixed_col;
     std::vector<uint16_t> fixed_val;
@@ -146,7 +148,8 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
             DevBuf<int32_t> d_new;
             d_new.upload(P.perm.data(), M);
             encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
-            use_reorder = opt.reorder == ACC_SPMM_ON || probe.T < tiles_identity;
+            use_reorder = opt.reorder == ACC_SPMM_ON ||
+                          (double)probe.T <= (1.0 - kAutoReorderMinGain) * (double)tiles_identity;
             if (use_reorder) d_perm.upload(P.perm.data(), M);
             t_reorder = now_s() - r0;
             }

@@ -43,10 +43,10 @@ struct ExecParams {
     const uint16_t* __restrict__ B;
     float* __restrict__ C;
     float* __restrict__ ws;
-    int64_t W;
     int32_t n_items;
     int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
     int32_t N;
+    bool wide;         // B needs 64-bit row offsets
 };
 
 template <int FPL>
@@ -83,9 +83,24 @@ struct TileData {       // what the multiply needs
     uint32_t nib;       // this lane's four bitmap bits
 };
 
-template <int FPL, int NS, int DEPTH, bool NT>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecParams p, int slab0) {
+// The index arrays are passed as separate const __restrict__ kernel arguments (not inside a
+// struct) so that the compiler knows they are read-only and wave-uniform accesses to them
+// become scalar loads.
+// WIDE = false: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
+// with one 24-bit multiply in 32 bits and added to the uniform base by the load itself.
+template <int FPL, int NS, int DEPTH, bool NT, bool WIDE>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
+    const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
+    const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
+    const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, float* __restrict__ g_C,
+    float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg) {
     constexpr int R = DEPTH + 1;
+    struct {
+        const int32_t* __restrict__ rwo; const int32_t* __restrict__ tco; const int32_t* __restrict__ a2b;
+        const uint64_t* __restrict__ bits; const uint16_t* __restrict__ vals; const int32_t* __restrict__ perm_pad;
+        const WorkItem* __restrict__ items; const uint16_t* __restrict__ B; float* __restrict__ C; float* __restrict__ ws;
+        int32_t n_items, n_blocks, N;
+    } p{g_rwo, g_tco, g_a2b, g_bits, g_vals, g_perm_pad, g_items, g_B, g_C, g_ws, n_items, n_blocks, N_arg};
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, c = lane & 15;
     // Consecutive blocks go to different XCDs (round-robin over 8); give each XCD one
@@ -103,13 +118,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecPar
     const bool partial = w_end_raw < 0;
     const int w_end = partial ? w_begin + 1 : w_end_raw;
     const int N = p.N;
-    const int slab_base = (slab0 + blockIdx.y * NS) * 128;  // first feature of this launch's slabs (NS>1 or grid.y>1 only when FPL==8)
+    const int slab_base = (int)(blockIdx.y * NS) * 128;  // first feature of this launch's slabs (NS>1 or grid.y>1 only when FPL==8)
     const int f0 = slab_base + c * FPL;
 
     // lane constants of the bitmap decode: bit index of (row c, k 4g) is c*16 + 4g
     const int wq = c >> 2;
     const int sh = ((c & 3) << 4) | (g << 2);
     const uint64_t below_mask = (1ull << sh) - 1ull;
+    const bool w1 = wq >= 1, w2 = wq >= 2, w3 = wq >= 3;
 
     floatx4 acc[NS][FPL];
 #pragma unroll
@@ -117,24 +133,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecPar
 #pragma unroll
         for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    auto flush = [&](int w) {
-        float* base;
-        intx4 rows;
-        if (partial) {
-            const int slot = -w_end_raw - 1;
-            base = p.ws + (size_t)slot * 16 * (size_t)N;
-            rows = intx4{4 * g, 4 * g + 1, 4 * g + 2, 4 * g + 3};
-        } else {
-            base = p.C;
-            rows = *reinterpret_cast<const intx4*>(p.perm_pad + (size_t)w * 16 + 4 * g);
-        }
+    // Rows of C owned by this lane for the window being accumulated (requested when the window
+    // starts, so that closing the window does not wait on a fresh load).
+    intx4 rows_cur = intx4{4 * g, 4 * g + 1, 4 * g + 2, 4 * g + 3};
+    auto load_rows = [&](int w) {
+        rows_cur = *reinterpret_cast<const intx4*>(p.perm_pad + (size_t)w * 16 + 4 * g);
+    };
+    float* const out_base = partial ? p.ws + (size_t)(-w_end_raw - 1) * 16 * (size_t)N : p.C;
+
+    auto flush = [&]() {  // store the accumulators to rows_cur and clear them
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const int row = rows[r];
+            const int row = rows_cur[r];
             if (row >= 0) {
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
-                    float* dst = base + (size_t)row * (size_t)N + f0 + s * 128;
+                    float* dst = out_base + (size_t)row * (size_t)N + f0 + s * 128;
                     if constexpr (FPL >= 4) {
 #pragma unroll
                         for (int m = 0; m < FPL; m += 4) {
@@ -169,21 +183,34 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecPar
     auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint16_t* row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
+            const uint16_t* row;
+            if constexpr (WIDE) {
+                row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
+            } else {
+                const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
+                row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
+            }
 #pragma unroll
             for (int s = 0; s < NS; ++s) load_chunk<FPL>(row + s * 128, d.b[s][q]);
         }
-        const int p0 = __builtin_popcountll(m.bm[0]);
-        const int p1 = p0 + __builtin_popcountll(m.bm[1]);
-        const int p2 = p1 + __builtin_popcountll(m.bm[2]);
-        const uint64_t word = wq == 0 ? m.bm[0] : wq == 1 ? m.bm[1] : wq == 2 ? m.bm[2] : m.bm[3];
-        const int pre = wq == 0 ? 0 : wq == 1 ? p0 : wq == 2 ? p1 : p2;
+        // this lane's bitmap word and the popcount of the words below it, by plain selects
+        const int c0 = __builtin_popcountll(m.bm[0]), c1 = __builtin_popcountll(m.bm[1]),
+                  c2 = __builtin_popcountll(m.bm[2]);
+        uint64_t word = m.bm[0];
+        word = w1 ? m.bm[1] : word;
+        word = w2 ? m.bm[2] : word;
+        word = w3 ? m.bm[3] : word;
+        const int pre = (w1 ? c0 : 0) + (w2 ? c1 : 0) + (w3 ? c2 : 0);
         const uint32_t nib = (uint32_t)(word >> sh) & 15u;
         const uint32_t i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
         const uint32_t i1 = i0 + (nib & 1u);
         const uint32_t i2 = i1 + ((nib >> 1) & 1u);
         const uint32_t i3 = i2 + ((nib >> 2) & 1u);
-        d.h[0] = p.vals[i0]; d.h[1] = p.vals[i1]; d.h[2] = p.vals[i2]; d.h[3] = p.vals[i3];
+        const char* vb = reinterpret_cast<const char*>(p.vals);
+        d.h[0] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i0 << 1));
+        d.h[1] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i1 << 1));
+        d.h[2] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i2 << 1));
+        d.h[3] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i3 << 1));
         d.nib = nib;
     };
 
@@ -205,27 +232,36 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(ExecPar
             }
     };
 
-    // window bookkeeping (all wave-uniform)
+    // window bookkeeping (all wave-uniform): w is the window being accumulated, wend its
+    // one-past-last tile, wend_next that of window w+1 (requested one window ahead)
     int w = w_begin;
     int wend = partial ? te : p.rwo[w + 1];
-    // leading empty windows
-    while (!partial && wend == tb && w < w_end) {
-        flush(w);
+    int wend_next = partial ? te : p.rwo[(w + 2 < w_end) ? w + 2 : w_end];
+    auto next_window = [&]() {
         ++w;
-        if (w < w_end) wend = p.rwo[w + 1];
+        wend = wend_next;
+        if (w < w_end) {
+            load_rows(w);
+            wend_next = p.rwo[(w + 2 < w_end) ? w + 2 : w_end];
+        }
+    };
+    if (!partial) {
+        load_rows(w);
+        while (w < w_end && wend == tb) {  // leading empty windows: rows of zeros
+            flush();
+            next_window();
+        }
     }
     if (tb >= te) return;
 
     auto after_tile = [&](int tt) {  // tile tt has been multiplied: close the window(s) ending there
-        if (tt + 1 != wend) return;
-        flush(w);
-        ++w;
+        if (__builtin_expect(tt + 1 != wend, 1)) return;
+        flush();
         if (partial) return;
-        if (w < w_end) wend = p.rwo[w + 1];
+        next_window();
         while (w < w_end && wend == tt + 1) {  // empty windows inside the run
-            flush(w);
-            ++w;
-            if (w < w_end) wend = p.rwo[w + 1];
+            flush();
+            next_window();
         }
     };
 
@@ -315,17 +351,32 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
         dst[i] = src[i];
 }
 
-template <int FPL, int NS>
-void launch_variant(const ExecParams& p, int n_slab_launches, bool no_prefetch, bool plain_stores,
-                    hipStream_t stream) {
+template <int FPL, int NS, int DEPTH, bool NT, bool WIDE>
+void launch_one(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
     dim3 grid(blocks, n_slab_launches), block(kWavesPerBlock * 64);
-    if (no_prefetch) {
-        if (plain_stores) hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 0, false>), grid, block, 0, stream, p, 0);
-        else hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 0, true>), grid, block, 0, stream, p, 0);
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, NT, WIDE>), grid, block, 0, stream, p.rwo, p.tco, p.a2b, p.bits,
+                       p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N);
+}
+
+template <int FPL, int NS, int DEPTH>
+void launch_depth(const ExecParams& p, int n_slab_launches, bool plain_stores, hipStream_t stream) {
+    if (p.wide) {
+        if (plain_stores) launch_one<FPL, NS, DEPTH, false, true>(p, n_slab_launches, stream);
+        else launch_one<FPL, NS, DEPTH, true, true>(p, n_slab_launches, stream);
     } else {
-        if (plain_stores) hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 2, false>), grid, block, 0, stream, p, 0);
-        else hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, 2, true>), grid, block, 0, stream, p, 0);
+        if (plain_stores) launch_one<FPL, NS, DEPTH, false, false>(p, n_slab_launches, stream);
+        else launch_one<FPL, NS, DEPTH, true, false>(p, n_slab_launches, stream);
+    }
+}
+
+template <int FPL, int NS>
+void launch_variant(const ExecParams& p, int n_slab_launches, int depth, bool plain_stores, hipStream_t stream) {
+    switch (depth) {
+        case 0: launch_depth<FPL, NS, 0>(p, n_slab_launches, plain_stores, stream); break;
+        case 1: launch_depth<FPL, NS, 1>(p, n_slab_launches, plain_stores, stream); break;
+        case 3: launch_depth<FPL, NS, 3>(p, n_slab_launches, plain_stores, stream); break;
+        default: launch_depth<FPL, NS, 2>(p, n_slab_launches, plain_stores, stream); break;
     }
 }
 
@@ -368,11 +419,13 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.B = static_cast<const uint16_t*>(B);
     p.C = static_cast<float*>(C);
     p.ws = plan.workspace.p;
-    p.W = f.W;
     p.n_items = (int32_t)plan.items.size();
     p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     p.N = N;
-    const bool np = plan.opt.no_prefetch != 0, ps = plan.opt.plain_stores != 0;
+    p.wide = plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32);
+    const int default_depth = N == 128 ? 3 : (N >= 256 ? 2 : 1);
+    const int np = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
+    const bool ps = plan.opt.streaming_stores == 0;
     if (timed) ACC_HIP(hipEventRecord(ev[0], stream));
     if (p.n_items > 0) {
         switch (N) {

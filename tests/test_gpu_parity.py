@@ -114,6 +114,28 @@ def test_all_widths_with_and_without_load_balancing(N, lb):
         acc.acc_spmm_destroy(plan)
 
 
+@pytest.mark.parametrize("N", [32, 128, 256])
+def test_every_kernel_variant(N):
+    """All pipeline depths (0 = no prefetch) and both store policies give the same, correct C."""
+    w = wl.config(5, 9)
+    B = wl.dense(w.K, N, 77, "normal", 0.0, 1.0)
+    ref = None
+    for depth in (0, 1, 2, 3):
+        for streaming in (0, 1):
+            opt = acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16, streaming_stores=streaming,
+                                   no_prefetch=int(depth == 0), pipeline_depth=depth)
+            plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+            try:
+                C = run_spmm(plan, B, w.M, N)
+            finally:
+                acc.acc_spmm_destroy(plan)
+            if ref is None:
+                ref = C
+                check_against_oracle(w.rowptr, w.colidx, w.vals, B, C)
+            else:
+                np.testing.assert_array_equal(C, ref)      # same summation order in every variant
+
+
 def test_identity_and_permutation_matrices_are_exact():
     rng = np.random.default_rng(0)
     n, N = 100, 64

@@ -186,6 +186,8 @@ def main() -> int:
         "cpu_baseline": cpu,
         "naive_gpu": naive,
         "plan": {"seconds": t_plan, "validate_s": st["t_validate_s"], "reorder_s": st["t_reorder_s"],
+                 "reorder_graph_s": st["t_graph_s"], "reorder_dendrogram_s": st["t_dendrogram_s"],
+                 "reorder_ordering_s": st["t_ordering_s"], "reorder_work_ratio": st["reorder_work_ratio"],
                  "encode_s": st["t_encode_s"], "schedule_s": st["t_schedule_s"],
                  "tiles": st["num_tiles"], "tiles_identity_order": st["num_tiles_identity"],
                  "mean_nnz_per_tile": st["mean_nnz_per_tile"], "ibd": st["ibd"], "items": st["num_items"],

@@ -70,7 +70,8 @@ typedef struct {
      * acc_spmm_execute returns ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
     int32_t window_height;
     int32_t tile_width;
-    /* Leaves per segment in the ordering step's candidate search.  0 = default 1024. */
+    /* Leaves per segment in the ordering step's candidate search.  0 = default 1024; at
+     * most 4096. */
     int32_t segment_length;
     /* IBD threshold for load_balance == AUTO.  0 = default 8 (Section 3.5). */
     float ibd_threshold;
@@ -108,6 +109,7 @@ typedef struct {
     int64_t schedule_bytes;     /* work items + permutation                                  */
     double reorder_work_ratio;  /* dendrogram edge-record visits per graph entry (0 if not run)  */
     double t_validate_s, t_reorder_s, t_encode_s, t_schedule_s, t_total_s;
+    double t_graph_s, t_dendrogram_s, t_ordering_s; /* parts of t_reorder_s (the rest: tile counting) */
 } acc_spmm_stats;
 
 /* Arrays acc_spmm_plan_export can copy out (element type, element count). */
@@ -210,12 +212,15 @@ ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t by
 /*
  * The two host-side stages of acc_spmm_plan, callable on their own (no GPU needed).
  *
- * acc_spmm_reorder_host: the row reordering of Section 3.2 (Algorithm 1) for a square
- * M x M pattern.  csr_rowptr / csr_colidx as for acc_spmm_plan (HOST).  segment_length
- * 0 = default.  Outputs, HOST int32[M] each: perm (new -> input row), iperm (its inverse),
- * parent (dendrogram: community each vertex was merged into, -1 for roots; may be NULL).
- * *work_ratio (may be NULL) receives the dendrogram step's edge-record visits per graph
- * entry (vertices + directed edges), the quantity acc_spmm_plan's AUTO mode limits.
+ * acc_spmm_dendrogram_host: Step I of the row reordering of Section 3.2 (Algorithm 1,
+ * dendrogram construction) for a square M x M pattern, and the leaf sequence Step II
+ * starts from.  csr_rowptr / csr_colidx as for acc_spmm_plan (HOST).  segment_length
+ * 0 = default.  Outputs (HOST): parent int32[M] (community each vertex was merged into, -1
+ * for roots); leaf_sequence int32[M] (may be NULL: the rows in depth-first leaf order);
+ * segment_start int32[M+1] (may be NULL: first sequence position of every segment, followed
+ * by M).  *work_ratio (may be NULL) receives the edge-record visits per graph entry
+ * (vertices + directed edges), the quantity acc_spmm_plan's AUTO mode limits.
+ * Returns the number of segments, or a negative acc_spmm_status.
  *
  * acc_spmm_schedule_host: Section 3.5 for 16x16 tiles.  row_window_offset is HOST
  * int32[W+1].  load_balance / max_tiles_per_item / ibd_threshold as in acc_spmm_options.
@@ -223,9 +228,9 @@ ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t by
  * acc_spmm_plan_export) are written to `items` if it is not NULL; items_capacity is its
  * capacity in items.  Returns the number of work items, or a negative acc_spmm_status.
  */
-ACC_SPMM_API int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
-                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent,
-                                       double* work_ratio);
+ACC_SPMM_API int64_t acc_spmm_dendrogram_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr,
+                                              const int32_t* csr_colidx, int32_t segment_length, int32_t* parent,
+                                              int32_t* leaf_sequence, int32_t* segment_start, double* work_ratio);
 
 ACC_SPMM_API int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,
                                int32_t max_tiles_per_item, float ibd_threshold, double* ibd_out,

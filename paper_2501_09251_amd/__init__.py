@@ -33,7 +33,7 @@ _ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = [
     "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
-    "acc_spmm_reorder_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy",
+    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy",
 ]
 
 
@@ -60,6 +60,7 @@ class acc_spmm_stats(ctypes.Structure):
         ("reorder_work_ratio", ctypes.c_double),
         ("t_validate_s", ctypes.c_double), ("t_reorder_s", ctypes.c_double), ("t_encode_s", ctypes.c_double),
         ("t_schedule_s", ctypes.c_double), ("t_total_s", ctypes.c_double),
+        ("t_graph_s", ctypes.c_double), ("t_dendrogram_s", ctypes.c_double), ("t_ordering_s", ctypes.c_double),
     ]
 
     def as_dict(self):
@@ -104,8 +105,8 @@ def load():
     L.acc_spmm_plan_export.argtypes = [vp, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_size_t)]
     L.acc_spmm_calibration_copy.restype = ctypes.c_int
     L.acc_spmm_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
-    L.acc_spmm_reorder_host.restype = ctypes.c_int
-    L.acc_spmm_reorder_host.argtypes = [i64, i64, vp, vp, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    L.acc_spmm_dendrogram_host.restype = i64
+    L.acc_spmm_dendrogram_host.argtypes = [i64, i64, vp, vp, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.acc_spmm_schedule_host.restype = i64
     L.acc_spmm_schedule_host.argtypes = [i64, vp, i32, i32, ctypes.c_float, ctypes.POINTER(ctypes.c_double), vp, i64,
                                          ctypes.POINTER(ctypes.c_int64)]
@@ -220,16 +221,18 @@ def acc_spmm_plan_export(plan, which) -> np.ndarray:
     return out
 
 
-def acc_spmm_reorder_host(M, nnz, csr_rowptr, csr_colidx, segment_length=0, want_work=False):
-    """Host stage of the plan: returns (perm, iperm, parent) as int32 arrays (+ work ratio)."""
+def acc_spmm_dendrogram_host(M, nnz, csr_rowptr, csr_colidx, segment_length=0):
+    """Host stage of the plan (Step I): returns (parent, leaf_sequence, segment_start, work_ratio)."""
     rp, rp_p = _host(csr_rowptr, np.int32)
     ci, ci_p = _host(csr_colidx, np.int32)
-    perm, iperm, parent = (np.empty(M, np.int32) for _ in range(3))
+    parent, seq = np.empty(M, np.int32), np.empty(M, np.int32)
+    seg = np.empty(M + 1, np.int32)
     work = ctypes.c_double()
-    if load().acc_spmm_reorder_host(M, nnz, rp_p, ci_p, segment_length, perm.ctypes.data, iperm.ctypes.data,
-                                    parent.ctypes.data, ctypes.byref(work)) != 0:
+    nseg = load().acc_spmm_dendrogram_host(M, nnz, rp_p, ci_p, segment_length, parent.ctypes.data, seq.ctypes.data,
+                                           seg.ctypes.data, ctypes.byref(work))
+    if nseg < 0:
         _raise()
-    return (perm, iperm, parent, work.value) if want_work else (perm, iperm, parent)
+    return parent, seq, seg[: nseg + 1].copy(), work.value
 
 
 def acc_spmm_schedule_host(row_window_offset, load_balance=ACC_SPMM_AUTO, max_tiles_per_item=0, ibd_threshold=0.0):

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OUT = os.path.join(HERE, "libaccspmm.so")
-SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "encode.hip", "execute.hip"]
+SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "encode.hip", "ordering.hip", "execute.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -129,30 +129,41 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         d_perm.upload(identity.data(), M);
         bool use_reorder = false;
         int64_t tiles_identity = -1;
-        double t_reorder = 0.0, reorder_work = 0.0;
+        double t_reorder = 0.0, reorder_work = 0.0, reorder_phases[3] = {0.0, 0.0, 0.0};
         if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
             const double r0 = now_s();
             // AUTO gives up on inputs whose dendrogram is expensive to build (large uniform
             // meshes), where the identity order is kept anyway; ON always completes.
             const double budget = opt.reorder == ACC_SPMM_AUTO ? kAutoReorderWorkBudget : 0.0;
-            const bool complete = reorder_rows(M, rowptr, colidx, opt.segment_length, P.perm, P.iperm, P.parent,
-                                               budget, &reorder_work);
+            std::vector<int32_t> seq;
+            std::vector<int64_t> seg_start;
+            const bool complete = build_dendrogram_host(M, rowptr, colidx, opt.segment_length, budget, P.parent, seq,
+                                                        seg_start, &reorder_work, reorder_phases);
             if (!complete) {
                 P.parent.clear();
-                t_reorder = now_s() - r0;
+            } else {
+                const double o0 = now_s();
+                int32_t max_row_len = 0;
+                for (int64_t i = 0; i < M; ++i) max_row_len = std::max(max_row_len, rowptr[i + 1] - rowptr[i]);
+                DevBuf<int32_t> d_new;
+                ordering_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, seq, seg_start, opt.segment_length, max_row_len,
+                                   d_new);
+                reorder_phases[2] = now_s() - o0;
+                DeviceFormat probe;
+                encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
+                tiles_identity = probe.T;
+                encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
+                use_reorder = opt.reorder == ACC_SPMM_ON ||
+                              (double)probe.T <= (1.0 - kAutoReorderMinGain) * (double)tiles_identity;
+                if (use_reorder) {
+                    P.perm.resize(M);
+                    d_new.download(P.perm.data());
+                    P.iperm.resize(M);
+                    for (int64_t r = 0; r < M; ++r) P.iperm[P.perm[r]] = (int32_t)r;
+                    ACC_HIP(hipMemcpy(d_perm.p, d_new.p, sizeof(int32_t) * M, hipMemcpyDeviceToDevice));
+                }
             }
-            DeviceFormat probe;
-            if (complete) {
-            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
-            tiles_identity = probe.T;
-            DevBuf<int32_t> d_new;
-            d_new.upload(P.perm.data(), M);
-            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
-            use_reorder = opt.reorder == ACC_SPMM_ON ||
-                          (double)probe.T <= (1.0 - kAutoReorderMinGain) * (double)tiles_identity;
-            if (use_reorder) d_perm.upload(P.perm.data(), M);
             t_reorder = now_s() - r0;
-            }
         }
         if (!use_reorder) {
             P.perm = identity;
@@ -204,6 +215,9 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.index_bytes = 4 * (W + 1) + 4 * (P.fmt.T + 1) + 4 * P.fmt.T * TW + 8 * P.fmt.T * P.fmt.NW;
         st.schedule_bytes = (int64_t)(sizeof(WorkItem) * P.items.size() + sizeof(SplitWindow) * P.splits.size()) + 4 * W * WH;
         st.reorder_work_ratio = reorder_work;
+        st.t_graph_s = reorder_phases[0];
+        st.t_dendrogram_s = reorder_phases[1];
+        st.t_ordering_s = reorder_phases[2];
         st.t_validate_s = t1 - t0;
         st.t_reorder_s = t_reorder;
         st.t_encode_s = t_encode;
@@ -308,22 +322,26 @@ int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* st
     return guarded([&] { launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)); });
 }
 
-int acc_spmm_reorder_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
-                          int32_t segment_length, int32_t* perm, int32_t* iperm, int32_t* parent,
-                          double* work_ratio) {
-    return guarded([&] {
-        if (M < 0 || nnz < 0 || !csr_rowptr || (nnz > 0 && !csr_colidx) || !perm || !iperm)
+int64_t acc_spmm_dendrogram_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
+                                 int32_t segment_length, int32_t* parent, int32_t* leaf_sequence,
+                                 int32_t* segment_start, double* work_ratio) {
+    int64_t nseg = -1;
+    int rc = guarded([&] {
+        if (M < 0 || nnz < 0 || !csr_rowptr || (nnz > 0 && !csr_colidx) || !parent)
             fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
         std::vector<int32_t> fixed_col;
         std::vector<uint16_t> fixed_val, dummy((size_t)nnz, 0);
         if (validate_csr(M, M, nnz, csr_rowptr, csr_colidx, dummy.data(), fixed_col, fixed_val)) csr_colidx = fixed_col.data();
-        std::vector<int32_t> p, ip, par;
-        reorder_rows(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, p, ip, par, 0.0,
-                     work_ratio);
-        std::copy(p.begin(), p.end(), perm);
-        std::copy(ip.begin(), ip.end(), iperm);
-        if (parent) std::copy(par.begin(), par.end(), parent);
+        std::vector<int32_t> par, seq;
+        std::vector<int64_t> seg;
+        build_dendrogram_host(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, 0.0, par, seq,
+                              seg, work_ratio, nullptr);
+        std::copy(par.begin(), par.end(), parent);
+        if (leaf_sequence) std::copy(seq.begin(), seq.end(), leaf_sequence);
+        if (segment_start) for (size_t i = 0; i < seg.size(); ++i) segment_start[i] = (int32_t)seg[i];
+        nseg = (int64_t)seg.size() - 1;
     });
+    return rc == ACC_SPMM_OK ? nseg : rc;
 }
 
 int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,

@@ -2,8 +2,9 @@
 //
 // Step I (dendrogram construction) is sequential by definition: vertices are visited in
 // ascending degree and every decision depends on the merges made before it, so it runs on
-// one host thread over flat arrays.  Step II (ordering generation) is independent per
-// segment of the dendrogram's leaf sequence and runs on all host threads.
+// one host thread over flat arrays (the graph itself is built by all host threads).  This
+// file ends with the dendrogram's leaf sequence cut into segments; Step II (ordering
+// generation), which is independent per segment, runs on the GPU (ordering.hip).
 //
 // Readings of what the paper leaves open (Eq. 1 is printed as the modularity itself, the
 // tie-breaks and the search scope of Step II are not stated):
@@ -19,6 +20,7 @@
 //    with the current row (at least one), ties to the earliest leaf of the sequence.
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <thread>
 
 #include "internal.h"
@@ -137,22 +139,41 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
         return x;
     };
     work = 0;
+    // The loop is bound by random accesses into up[], weight[] and dsum[] (tens of MB).  Each
+    // turn therefore runs in three streaming passes over the gathered edge records, so that
+    // the cache misses of one pass are all in flight together: (1) collect the records and
+    // prefetch their union-find cells, (2) resolve roots and prefetch their weight cells,
+    // (3) accumulate.
+    std::vector<Edge> buf;
     for (int64_t step = 0; step < M; ++step) {
         const int32_t v = order[step];
         if (work_limit > 0 && work > work_limit) return false;
         touched.clear();
-        auto add = [&](int32_t y, uint32_t w) {
-            int32_t r = find(y);
-            if (r == v) return;
-            if (weight[r] == 0) touched.push_back(r);
-            weight[r] += w;
-        };
-        for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) add(gadj[p], 1);
-        work += gptr[v + 1] - gptr[v] + 1;
+        buf.clear();
+        for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) {
+            __builtin_prefetch(&up[gadj[p]]);
+            buf.push_back(Edge{gadj[p], 1u});
+        }
         for (int32_t c = first_child[v]; c >= 0; c = next_sibling[c]) {
-            for (const Edge& e : agg[c]) add(e.to, e.w);
-            work += (int64_t)agg[c].size();
+            for (const Edge& e : agg[c]) {
+                __builtin_prefetch(&up[e.to]);
+                buf.push_back(e);
+            }
             std::vector<Edge>().swap(agg[c]);
+        }
+        work += (int64_t)buf.size() + 1;
+        for (Edge& e : buf) {
+            e.to = find(e.to);
+            __builtin_prefetch(&weight[e.to]);
+        }
+        for (const Edge& e : buf) {
+            const int32_t r = e.to;
+            if (r == v) continue;
+            if (weight[r] == 0) {
+                touched.push_back(r);
+                __builtin_prefetch(&dsum[r]);
+            }
+            weight[r] += e.w;
         }
         int32_t best = -1;
         int64_t best_s = 0;
@@ -182,25 +203,31 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
 
 }  // namespace
 
-bool reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
-                  std::vector<int32_t>& perm, std::vector<int32_t>& iperm, std::vector<int32_t>& parent,
-                  double work_budget, double* work_ratio) {
+bool build_dendrogram_host(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
+                           double work_budget, std::vector<int32_t>& parent, std::vector<int32_t>& seq,
+                           std::vector<int64_t>& seg_start, double* work_ratio, double* phase_seconds) {
+    auto now = [] { return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
+    const double t0 = now();
     std::vector<int64_t> gptr;
     std::vector<int32_t> gadj;
     build_graph(M, rowptr, colidx, gptr, gadj);
+    const double t1 = now();
     std::vector<int32_t> first_child, next_sibling;
     const int64_t graph_size = gptr[M] + M;
     int64_t work = 0;
     const bool complete = build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling,
                                            work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0, work);
     if (work_ratio) *work_ratio = graph_size ? (double)work / (double)graph_size : 0.0;
+    const double t2 = now();
+    if (phase_seconds) { phase_seconds[0] = t1 - t0; phase_seconds[1] = t2 - t1; }
     if (!complete) return false;
     std::vector<int32_t>().swap(gadj);
     std::vector<int64_t>().swap(gptr);
 
-    // leaf sequence and segments
-    std::vector<int32_t> seq;
-    std::vector<int64_t> seg_start;
+    // leaf sequence: roots by ascending id; a root, then its children's subtrees in merge
+    // order; each tree's sequence is cut into segments of at most seg_len leaves
+    seq.clear();
+    seg_start.clear();
     seq.reserve(M);
     std::vector<int32_t> stack;
     for (int64_t r = 0; r < M; ++r) {
@@ -219,57 +246,6 @@ bool reorder_rows(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32
         for (int64_t s = tree_begin; s < (int64_t)seq.size(); s += seg_len) seg_start.push_back(s);
     }
     seg_start.push_back(M);
-    perm.resize(M);
-    iperm.resize(M);
-
-    // Step II, one segment at a time (segments are independent)
-    const int64_t nseg = (int64_t)seg_start.size() - 1;
-    parallel_chunks(nseg, 8, [&](int64_t sb, int64_t se) {
-        std::vector<std::pair<int32_t, int32_t>> cp;  // (column, position in segment)
-        std::vector<int32_t> col_begin, count, hit;
-        std::vector<char> visited;
-        for (int64_t sg = sb; sg < se; ++sg) {
-            const int64_t b = seg_start[sg], n = seg_start[sg + 1] - b;
-            if (n == 1) { perm[b] = seq[b]; continue; }
-            cp.clear();
-            for (int64_t q = 0; q < n; ++q) {
-                const int32_t row = seq[b + q];
-                for (int64_t p = rowptr[row]; p < rowptr[row + 1]; ++p) cp.push_back({colidx[p], (int32_t)q});
-            }
-            std::sort(cp.begin(), cp.end());
-            visited.assign(n, 0);
-            count.assign(n, 0);
-            int64_t out = b;
-            for (int64_t cur = 0; cur < n; ++cur) {
-                if (visited[cur]) continue;
-                int64_t v = cur;
-                for (;;) {
-                    visited[v] = 1;
-                    perm[out++] = seq[b + v];
-                    hit.clear();
-                    const int32_t row = seq[b + v];
-                    for (int64_t p = rowptr[row]; p < rowptr[row + 1]; ++p) {
-                        auto it = std::lower_bound(cp.begin(), cp.end(), std::make_pair(colidx[p], (int32_t)-1));
-                        for (; it != cp.end() && it->first == colidx[p]; ++it) {
-                            if (visited[it->second]) continue;
-                            if (count[it->second]++ == 0) hit.push_back(it->second);
-                        }
-                    }
-                    int64_t best = -1;
-                    int32_t best_n = 0;
-                    for (int32_t q : hit) {
-                        if (count[q] > best_n || (count[q] == best_n && q < best)) { best = q; best_n = count[q]; }
-                        count[q] = 0;
-                    }
-                    if (best < 0) break;
-                    v = best;
-                }
-            }
-        }
-    });
-    parallel_chunks(M, 1 << 16, [&](int64_t b, int64_t e) {
-        for (int64_t r = b; r < e; ++r) iperm[perm[r]] = (int32_t)r;
-    });
     return true;
 }
 

@@ -88,9 +88,21 @@ def test_no_gpu_means_a_loud_error_not_a_fallback():
     assert code == -5 and "no HIP device" in acc.acc_spmm_last_error()[1]
 
 
-# --------------------------------------------------------------- host stage: reordering
+# --------------------------------------------------------------- host stage: dendrogram
+def _check_dendrogram(rowptr, colidx, seg):
+    M = len(rowptr) - 1
+    parent, seq, seg_start, work = acc.acc_spmm_dendrogram_host(M, len(colidx), rowptr, colidx, seg)
+    oparent, ochild = oracle.dendrogram(rowptr, colidx)
+    np.testing.assert_array_equal(parent, oparent)
+    _, _, oseq, oseg = oracle.ordering(rowptr, colidx, oparent, ochild, seg, details=True)
+    np.testing.assert_array_equal(seq, oseq)
+    np.testing.assert_array_equal(seg_start, oseg)
+    assert work >= 1.0 or M == 0
+    return parent
+
+
 @pytest.mark.parametrize("seed", range(6))
-def test_reorder_host_equals_oracle_on_random_graphs(seed):
+def test_dendrogram_host_equals_oracle_on_random_graphs(seed):
     rng = np.random.default_rng(seed)
     M = int(rng.integers(30, 400))
     if seed % 2:
@@ -98,33 +110,23 @@ def test_reorder_host_equals_oracle_on_random_graphs(seed):
     else:
         rowptr, colidx, _ = random_csr(rng, M, M, 0.03, empty_row_frac=0.2)
     for seg in (5, 64, 1024):
-        perm, iperm, parent = acc.acc_spmm_reorder_host(M, len(colidx), rowptr, colidx, seg)
-        oparent, ochild = oracle.dendrogram(rowptr, colidx)
-        operm, oiperm = oracle.ordering(rowptr, colidx, oparent, ochild, seg)
-        np.testing.assert_array_equal(parent, oparent)
-        np.testing.assert_array_equal(perm, operm)
-        np.testing.assert_array_equal(iperm, oiperm)
+        _check_dendrogram(rowptr, colidx, seg)
 
 
 @pytest.mark.parametrize("cfg,shrink", [(1, 0), (2, 5), (3, 6), (4, 3), (5, 8)])
-def test_reorder_host_equals_oracle_on_the_workloads(cfg, shrink):
+def test_dendrogram_host_equals_oracle_on_the_workloads(cfg, shrink):
     w = wl.config(cfg, shrink, with_B=False)
-    perm, iperm, parent = acc.acc_spmm_reorder_host(w.M, w.nnz, w.rowptr, w.colidx)
-    operm, oiperm = oracle.reorder(w.rowptr, w.colidx)
-    np.testing.assert_array_equal(perm, operm)
-    np.testing.assert_array_equal(iperm, oiperm)
-    assert sorted(perm.tolist()) == list(range(w.M))
+    _check_dendrogram(w.rowptr, w.colidx, 1024)
 
 
-def test_reorder_host_accepts_unsorted_rows_and_special_graphs():
+def test_dendrogram_host_accepts_unsorted_rows_and_special_graphs():
     rowptr, colidx, _ = csr_from_rows([[3, 1], [0], [], [0, 2]])
-    perm, _, _ = acc.acc_spmm_reorder_host(4, 5, rowptr, colidx)
+    parent, _, _, _ = acc.acc_spmm_dendrogram_host(4, 5, rowptr, colidx)
     srp, sci, _ = csr_from_rows([[1, 3], [0], [], [0, 2]])
-    np.testing.assert_array_equal(perm, oracle.reorder(srp, sci)[0])
+    np.testing.assert_array_equal(parent, oracle.dendrogram(srp, sci)[0])
     for M, edges in ((12, [(0, i) for i in range(1, 12)]), (5, []), (9, [(i, i + 1) for i in range(8)])):
         rowptr, colidx, _ = csr_from_edges(M, edges)
-        perm, _, _ = acc.acc_spmm_reorder_host(M, len(colidx), rowptr, colidx, 4)
-        np.testing.assert_array_equal(perm, oracle.reorder(rowptr, colidx, 4)[0])
+        _check_dendrogram(rowptr, colidx, 4)
 
 
 # ----------------------------------------------------------------- host stage: schedule

@@ -167,6 +167,33 @@ def test_reordering_is_invisible_in_C():
     assert out[1][1] < 0.7 * out[0][1]                # the hidden blocks are recovered: far fewer tiles
 
 
+@pytest.mark.parametrize("seg_len", [3, 64, 1024, 3000])
+def test_permutation_is_bit_exact_for_all_segment_lengths(seg_len):
+    """Reordering (host dendrogram + GPU ordering kernel) against the oracle's permutation."""
+    from _util import random_sym_csr
+    rng = np.random.default_rng(seg_len)
+    graphs = [random_sym_csr(rng, 700, 6.0)[:2], random_csr(rng, 500, 500, 0.02, empty_row_frac=0.2)[:2]]
+    w = wl.config(4, 6)
+    graphs.append((w.rowptr, w.colidx))
+    w5 = wl.config(5, 10)            # heavy-tailed: hub rows and hub columns inside segments
+    graphs.append((w5.rowptr, w5.colidx))
+    for rowptr, colidx in graphs:
+        M = len(rowptr) - 1
+        vals = np.zeros(len(colidx), np.uint16)
+        plan = acc.acc_spmm_plan_ex(M, M, len(colidx), rowptr, colidx, vals,
+                                    acc.make_options(reorder=acc.ACC_SPMM_ON, segment_length=seg_len))
+        try:
+            perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
+            iperm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_IPERM)
+            parent = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_DENDROGRAM_PARENT)
+        finally:
+            acc.acc_spmm_destroy(plan)
+        operm, oiperm = oracle.reorder(rowptr, colidx, seg_len)
+        np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0])
+        np.testing.assert_array_equal(perm, operm)
+        np.testing.assert_array_equal(iperm, oiperm)
+
+
 def test_linearity_in_B_exact_on_small_integers():
     rng = np.random.default_rng(5)
     M = K = 200

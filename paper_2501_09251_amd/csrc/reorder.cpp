@@ -21,6 +21,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <memory>
 #include <thread>
 
 #include "internal.h"
@@ -107,6 +108,42 @@ struct Edge {
     uint32_t w;
 };
 
+// Recycling allocator for the per-community edge lists of Step I.  Lists live from a
+// vertex's turn to its parent's turn; handing their blocks (power-of-two sizes) back for
+// reuse keeps the loop on memory that is already mapped and warm, instead of taking a
+// first-touch page fault for every new list.
+class EdgeArena {
+public:
+    static int size_class(size_t n) {
+        int c = 3;
+        while (((size_t)1 << c) < n) ++c;
+        return c;
+    }
+    Edge* take(int cls) {
+        auto& fl = free_[cls];
+        if (!fl.empty()) {
+            Edge* p = fl.back();
+            fl.pop_back();
+            return p;
+        }
+        const size_t n = (size_t)1 << cls;
+        if (used_ + n > cap_) {
+            cap_ = std::max<size_t>(n, (size_t)1 << 22);
+            chunks_.emplace_back(new Edge[cap_]);
+            used_ = 0;
+        }
+        Edge* p = chunks_.back().get() + used_;
+        used_ += n;
+        return p;
+    }
+    void give_back(Edge* p, int cls) { free_[cls].push_back(p); }
+
+private:
+    std::vector<std::unique_ptr<Edge[]>> chunks_;
+    size_t used_ = 0, cap_ = 0;
+    std::vector<Edge*> free_[40];
+};
+
 // Step I.  parent[v] = community v was merged into (-1: root); children lists in merge order.
 // `work` counts the edge records visited; when it exceeds `work_limit` (> 0) the
 // construction stops early and returns false.
@@ -129,21 +166,26 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
     next_sibling.assign(M, -1);
     std::vector<int32_t> last_child(M, -1), up(M);
     std::vector<int64_t> dsum(M);
-    std::vector<std::vector<Edge>> agg(M);  // community edges of v as of v's turn
+    // community edges of v as of v's turn (kept only until the parent's turn)
+    EdgeArena arena;
+    std::vector<Edge*> agg_ptr(M, nullptr);
+    std::vector<int32_t> agg_len(M, 0);
     std::vector<uint32_t> weight(M, 0);     // scratch: weight towards each community
     std::vector<int32_t> touched;
     std::vector<char> done(M, 0);           // vertex has had its turn
     for (int64_t i = 0; i < M; ++i) { up[i] = (int32_t)i; dsum[i] = gptr[i + 1] - gptr[i]; }
-    auto find = [&](int32_t x) {
-        while (up[x] != x) { up[x] = up[up[x]]; x = up[x]; }
-        return x;
+    auto find = [&](int32_t x) {  // union-find root with full path compression
+        int32_t r = x;
+        while (up[r] != r) r = up[r];
+        while (up[x] != r) { const int32_t nx = up[x]; up[x] = r; x = nx; }
+        return r;
     };
     work = 0;
     // The loop is bound by random accesses into up[], weight[] and dsum[] (tens of MB).  Each
-    // turn therefore runs in three streaming passes over the gathered edge records, so that
-    // the cache misses of one pass are all in flight together: (1) collect the records and
-    // prefetch their union-find cells, (2) resolve roots and prefetch their weight cells,
-    // (3) accumulate.
+    // turn therefore runs in streaming passes over the gathered edge records, so that the
+    // cache misses of one pass are all in flight together: (1) collect the records and
+    // prefetch their union-find cells, (2) hop once and prefetch the next cell, (3) resolve
+    // roots and prefetch their weight cells, (4) accumulate.
     std::vector<Edge> buf;
     for (int64_t step = 0; step < M; ++step) {
         const int32_t v = order[step];
@@ -155,23 +197,30 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
             buf.push_back(Edge{gadj[p], 1u});
         }
         for (int32_t c = first_child[v]; c >= 0; c = next_sibling[c]) {
-            for (const Edge& e : agg[c]) {
-                __builtin_prefetch(&up[e.to]);
-                buf.push_back(e);
+            const Edge* list = agg_ptr[c];
+            const int32_t n = agg_len[c];
+            for (int32_t k = 0; k < n; ++k) {
+                __builtin_prefetch(&up[list[k].to]);
+                buf.push_back(list[k]);
             }
-            std::vector<Edge>().swap(agg[c]);
+            if (list) arena.give_back(agg_ptr[c], EdgeArena::size_class((size_t)n));
+            agg_ptr[c] = nullptr;
         }
         work += (int64_t)buf.size() + 1;
+        for (Edge& e : buf) {  // one hop up, and ask for the next cell
+            e.to = up[e.to];
+            __builtin_prefetch(&up[e.to]);
+        }
         for (Edge& e : buf) {
             e.to = find(e.to);
             __builtin_prefetch(&weight[e.to]);
+            __builtin_prefetch(&dsum[e.to]);
         }
         for (const Edge& e : buf) {
             const int32_t r = e.to;
             if (r == v) continue;
             if (weight[r] == 0) {
                 touched.push_back(r);
-                __builtin_prefetch(&dsum[r]);
             }
             weight[r] += e.w;
         }
@@ -184,9 +233,11 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
         const bool merge = best >= 0 && best_s > 0;
         // v's edge list is needed later only if the community it joins has its turn still ahead
         if (merge && !done[best]) {
-            auto& mine = agg[v];
-            mine.reserve(touched.size());
-            for (int32_t r : touched) mine.push_back(Edge{r, weight[r]});
+            Edge* mine = arena.take(EdgeArena::size_class(touched.size()));
+            size_t k = 0;
+            for (int32_t r : touched) mine[k++] = Edge{r, weight[r]};
+            agg_ptr[v] = mine;
+            agg_len[v] = (int32_t)touched.size();
         }
         for (int32_t r : touched) weight[r] = 0;
         if (merge) {

@@ -6,7 +6,8 @@
 //   1. lengths of the reordered rows -> exclusive scan -> reordered row pointers
 //   2. one 64-bit key (window, column) per stored entry
 //   3. radix sort of the keys; heads of equal runs are the distinct columns of each window
-//   4. distinct columns per window -> tiles per window -> RowWindowOffset (scan)
+//   4. distinct columns per window (a binary search per window boundary) -> tiles per window
+//      -> RowWindowOffset (scan)
 //   5. SparseAToB: each window's distinct columns, the last tile padded with the last column
 //   6. TCLocalBit: every entry finds its condensed column by binary search and sets its bit
 //   7. TCOffset: scan of the tiles' popcounts
@@ -51,13 +52,28 @@ __global__ void mark_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted
 }
 
 __global__ void compact_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, const int32_t* __restrict__ head,
-                                     const int32_t* __restrict__ upos, int32_t colbits, uint64_t* __restrict__ uniq,
-                                     int32_t* __restrict__ dw) {
+                                     const int32_t* __restrict__ upos, uint64_t* __restrict__ uniq) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n && head[i]) {
-        uniq[upos[i]] = sorted[i];
-        atomicAdd(&dw[sorted[i] >> colbits], 1);
+    if (i < n && head[i]) uniq[upos[i]] = sorted[i];
+}
+
+// ustart[w] = first position in the sorted distinct keys whose window is >= w (w = 0..W)
+__global__ void window_starts_kernel(int64_t W, int64_t n_unique, const uint64_t* __restrict__ uniq, int32_t colbits,
+                                     int32_t* __restrict__ ustart) {
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w > W) return;
+    const uint64_t key = (uint64_t)w << colbits;
+    int64_t lo = 0, n = n_unique;
+    while (n > 0) {
+        int64_t half = n >> 1;
+        if (uniq[lo + half] < key) { lo += half + 1; n -= half + 1; } else n = half;
     }
+    ustart[w] = (int32_t)lo;
+}
+
+__global__ void distinct_per_window_kernel(int64_t W, const int32_t* __restrict__ ustart, int32_t* __restrict__ dw) {
+    int64_t w = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (w < W) dw[w] = ustart[w + 1] - ustart[w];
 }
 
 __global__ void tiles_per_window_kernel(int64_t W, const int32_t* __restrict__ dw, int32_t TW, int32_t* __restrict__ tw) {
@@ -226,7 +242,7 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
     DevBuf<uint64_t> uniq;
     uniq.alloc(n_unique);
     hipLaunchKernelGGL(compact_heads_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, 0, nnz, sorted.p, head.p,
-                       upos.p, colbits, uniq.p, dw.p);
+                       upos.p, uniq.p);
     sorted.release();
     head.release();
     upos.release();
@@ -235,9 +251,11 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
     tw.alloc(W + 1);
     ustart.alloc(W + 1);
     ACC_HIP(hipMemset(tw.p, 0, sizeof(int32_t) * (W + 1)));
+    hipLaunchKernelGGL(window_starts_kernel, dim3(blocks_for(W + 1, 256)), dim3(256), 0, 0, W, (int64_t)n_unique, uniq.p,
+                       colbits, ustart.p);
+    hipLaunchKernelGGL(distinct_per_window_kernel, dim3(blocks_for(W, 256)), dim3(256), 0, 0, W, ustart.p, dw.p);
     hipLaunchKernelGGL(tiles_per_window_kernel, dim3(blocks_for(W, 256)), dim3(256), 0, 0, W, dw.p, TW, tw.p);
     exclusive_scan_i32(tmp, tw.p, out.row_window_offset.p, W + 1);
-    exclusive_scan_i32(tmp, dw.p, ustart.p, W + 1);
     int32_t T32 = 0;
     ACC_HIP(hipMemcpy(&T32, out.row_window_offset.p + W, sizeof(int32_t), hipMemcpyDeviceToHost));
     const int64_t T = T32;

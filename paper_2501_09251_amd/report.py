@@ -1,0 +1,93 @@
+"""Ablation and format report for one workload, in the structure of the paper's detailed
+evaluation (Section 4.3): reordering quality (MeanNNZTC, 4.3.1), index footprint of the
+bitmap format against CSR and an int8-per-entry tile format (4.3.2), pipeline on/off
+(4.3.3), load balancing on/off (4.3.4) and the switch-by-switch ablation (4.3.5).
+
+    python -m paper_2501_09251_amd.report --config 2
+
+Needs a GPU.  Prints one JSON object per line; every timing is the tile kernel plus the
+split-window combine kernel, from HIP events, averaged over --steps launches.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+
+import numpy as np
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--shrink", type=int, default=0)
+    ap.add_argument("--steps", type=int, default=10)
+    args = ap.parse_args()
+
+    import torch
+    import paper_2501_09251_amd as acc
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("report: no GPU visible", file=sys.stderr)
+        return 2
+    w = wl.config(args.config, args.shrink)
+    dev = torch.device("cuda:0")
+    B = torch.from_numpy(w.B.view(np.int16)).to(dev)
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    OFF, ON = acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON
+
+    def plan_with(**kw):
+        return acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(**kw))
+
+    def timed(**kw):
+        plan = plan_with(**kw)
+        try:
+            st = acc.acc_spmm_plan_stats(plan)
+            for _ in range(2):
+                acc.acc_spmm_execute(plan, B, w.N, C, stream)
+            torch.cuda.synchronize()
+            ts = [sum(acc.acc_spmm_execute_timed(plan, B, w.N, C, stream)) for _ in range(args.steps)]
+        finally:
+            acc.acc_spmm_destroy(plan)
+        ms = float(np.mean(ts))
+        return ms, 2.0 * w.nnz * w.N / (ms * 1e-3) / 1e9, st
+
+    # --- format (Section 4.3.2), paper geometry 8x8, with and without reordering
+    for ro in (OFF, ON):
+        plan = plan_with(window_height=8, tile_width=8, reorder=ro)
+        st = acc.acc_spmm_plan_stats(plan)
+        acc.acc_spmm_destroy(plan)
+        W, T = st["num_windows"], st["num_tiles"]
+        csr = 4 * (w.M + 1) + 4 * w.nnz
+        int8_tiles = 4 * (W + 1) + 4 * (T + 1) + 4 * 8 * T + w.nnz          # one int8 local id per entry
+        bitmap_tiles = st["index_bytes"]
+        print(json.dumps({"report": "format-8x8", "workload": w.name, "reordered": bool(ro), "tiles": T,
+                          "mean_nnz_per_tile": st["mean_nnz_per_tile"], "index_bytes_csr": csr,
+                          "index_bytes_int8_local_id_tiles": int8_tiles, "index_bytes_bitmap_tiles": bitmap_tiles,
+                          "bitmap_vs_csr": bitmap_tiles / csr, "bitmap_vs_int8": bitmap_tiles / int8_tiles}), flush=True)
+
+    # --- ablation (Section 4.3.5 order: reordering, cache policy, pipeline, load balancing)
+    steps = [
+        ("base: tiles only", dict(reorder=OFF, load_balance=OFF, no_prefetch=1, streaming_stores=1)),
+        ("+ reordering", dict(reorder=ON, load_balance=OFF, no_prefetch=1, streaming_stores=1)),
+        ("+ cache policy (ordinary C stores)", dict(reorder=ON, load_balance=OFF, no_prefetch=1)),
+        ("+ pipeline", dict(reorder=ON, load_balance=OFF)),
+        ("+ load balancing", dict(reorder=ON, load_balance=ON)),
+        ("library defaults (AUTO)", dict()),
+    ]
+    for name, kw in steps:
+        ms, gf, st = timed(**kw)
+        print(json.dumps({"report": "ablation", "workload": w.name, "step": name, "ms": ms, "gflops": gf,
+                          "tiles": st["num_tiles"], "items": st["num_items"], "ibd": st["ibd"],
+                          "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"]}),
+              flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -213,8 +213,10 @@ ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t by
  * The two host-side stages of acc_spmm_plan, callable on their own (no GPU needed).
  *
  * acc_spmm_dendrogram_host: Step I of the row reordering of Section 3.2 (Algorithm 1,
- * dendrogram construction) for a square M x M pattern, and the leaf sequence Step II
- * starts from.  csr_rowptr / csr_colidx as for acc_spmm_plan (HOST).  segment_length
+ * dendrogram construction) and the leaf sequence Step II starts from.  Input (HOST): the
+ * pattern graph as symmetric adjacency, graph_rowptr int64[M+1] and graph_adj int32 with
+ * vertex i's neighbours in graph_adj[graph_rowptr[i] .. graph_rowptr[i+1]), ascending,
+ * without i itself (inside acc_spmm_plan the GPU builds this from A + A^T).  segment_length
  * 0 = default.  Outputs (HOST): parent int32[M] (community each vertex was merged into, -1
  * for roots); leaf_sequence int32[M] (may be NULL: the rows in depth-first leaf order);
  * segment_start int32[M+1] (may be NULL: first sequence position of every segment, followed
@@ -228,9 +230,9 @@ ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t by
  * acc_spmm_plan_export) are written to `items` if it is not NULL; items_capacity is its
  * capacity in items.  Returns the number of work items, or a negative acc_spmm_status.
  */
-ACC_SPMM_API int64_t acc_spmm_dendrogram_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr,
-                                              const int32_t* csr_colidx, int32_t segment_length, int32_t* parent,
-                                              int32_t* leaf_sequence, int32_t* segment_start, double* work_ratio);
+ACC_SPMM_API int64_t acc_spmm_dendrogram_host(int64_t M, const int64_t* graph_rowptr, const int32_t* graph_adj,
+                                              int32_t segment_length, int32_t* parent, int32_t* leaf_sequence,
+                                              int32_t* segment_start, double* work_ratio);
 
 ACC_SPMM_API int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int32_t load_balance,
                                int32_t max_tiles_per_item, float ibd_threshold, double* ibd_out,

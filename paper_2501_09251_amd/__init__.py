@@ -106,7 +106,7 @@ def load():
     L.acc_spmm_calibration_copy.restype = ctypes.c_int
     L.acc_spmm_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
     L.acc_spmm_dendrogram_host.restype = i64
-    L.acc_spmm_dendrogram_host.argtypes = [i64, i64, vp, vp, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
+    L.acc_spmm_dendrogram_host.argtypes = [i64, vp, vp, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.acc_spmm_schedule_host.restype = i64
     L.acc_spmm_schedule_host.argtypes = [i64, vp, i32, i32, ctypes.c_float, ctypes.POINTER(ctypes.c_double), vp, i64,
                                          ctypes.POINTER(ctypes.c_int64)]
@@ -221,14 +221,17 @@ def acc_spmm_plan_export(plan, which) -> np.ndarray:
     return out
 
 
-def acc_spmm_dendrogram_host(M, nnz, csr_rowptr, csr_colidx, segment_length=0):
-    """Host stage of the plan (Step I): returns (parent, leaf_sequence, segment_start, work_ratio)."""
-    rp, rp_p = _host(csr_rowptr, np.int32)
-    ci, ci_p = _host(csr_colidx, np.int32)
+def acc_spmm_dendrogram_host(M, graph_rowptr, graph_adj, segment_length=0):
+    """Host stage of the plan (Step I) on a symmetric adjacency: returns (parent, leaf_sequence,
+    segment_start, work_ratio)."""
+    rp, rp_p = _host(graph_rowptr, np.int64)
+    ci, ci_p = _host(graph_adj, np.int32)
+    if len(rp) != M + 1 or len(ci) != rp[-1]:
+        raise ValueError("graph array lengths do not match M")
     parent, seq = np.empty(M, np.int32), np.empty(M, np.int32)
     seg = np.empty(M + 1, np.int32)
     work = ctypes.c_double()
-    nseg = load().acc_spmm_dendrogram_host(M, nnz, rp_p, ci_p, segment_length, parent.ctypes.data, seq.ctypes.data,
+    nseg = load().acc_spmm_dendrogram_host(M, rp_p, ci_p, segment_length, parent.ctypes.data, seq.ctypes.data,
                                            seg.ctypes.data, ctypes.byref(work))
     if nseg < 0:
         _raise()

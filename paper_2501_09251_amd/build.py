@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OUT = os.path.join(HERE, "libaccspmm.so")
-SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "encode.hip", "ordering.hip", "execute.hip"]
+SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "encode.hip", "graph.hip", "ordering.hip", "execute.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -38,7 +38,7 @@ def _stale(target: str, deps: list[str]) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     bdir = os.path.join(CSRC, "_build")
     os.makedirs(bdir, exist_ok=True)
-    headers = [os.path.join(CSRC, "internal.h"), os.path.join(INCLUDE, "acc_spmm.h")]
+    headers = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device_util.h"), os.path.join(INCLUDE, "acc_spmm.h")]
     jobs = []
     for src in SOURCES:
         s = os.path.join(CSRC, src)

@@ -137,8 +137,17 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
             const double budget = opt.reorder == ACC_SPMM_AUTO ? kAutoReorderWorkBudget : 0.0;
             std::vector<int32_t> seq;
             std::vector<int64_t> seg_start;
-            const bool complete = build_dendrogram_host(M, rowptr, colidx, opt.segment_length, budget, P.parent, seq,
-                                                        seg_start, &reorder_work, reorder_phases);
+            bool complete;
+            {
+                const double g0 = now_s();
+                HostGraph graph;
+                build_graph_on_device(M, nnz, P.d_rowptr.p, P.d_colidx.p, graph);
+                const double g1 = now_s();
+                complete = build_dendrogram_host(M, graph.ptr, graph.adj, opt.segment_length, budget, P.parent, seq,
+                                                 seg_start, &reorder_work);
+                reorder_phases[0] = g1 - g0;
+                reorder_phases[1] = now_s() - g1;
+            }
             if (!complete) {
                 P.parent.clear();
             } else {
@@ -322,20 +331,25 @@ int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* st
     return guarded([&] { launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)); });
 }
 
-int64_t acc_spmm_dendrogram_host(int64_t M, int64_t nnz, const int32_t* csr_rowptr, const int32_t* csr_colidx,
+int64_t acc_spmm_dendrogram_host(int64_t M, const int64_t* graph_rowptr, const int32_t* graph_adj,
                                  int32_t segment_length, int32_t* parent, int32_t* leaf_sequence,
                                  int32_t* segment_start, double* work_ratio) {
     int64_t nseg = -1;
     int rc = guarded([&] {
-        if (M < 0 || nnz < 0 || !csr_rowptr || (nnz > 0 && !csr_colidx) || !parent)
-            fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
-        std::vector<int32_t> fixed_col;
-        std::vector<uint16_t> fixed_val, dummy((size_t)nnz, 0);
-        if (validate_csr(M, M, nnz, csr_rowptr, csr_colidx, dummy.data(), fixed_col, fixed_val)) csr_colidx = fixed_col.data();
+        if (M < 0 || M >= ((int64_t)1 << 31) || !graph_rowptr || !parent) fail(ACC_SPMM_ERR_INVALID_ARG, "bad argument");
+        if (graph_rowptr[0] != 0) fail(ACC_SPMM_ERR_INVALID_CSR, "graph_rowptr[0] must be 0");
+        for (int64_t i = 0; i < M; ++i) {
+            if (graph_rowptr[i + 1] < graph_rowptr[i]) fail(ACC_SPMM_ERR_INVALID_CSR, "graph_rowptr decreases");
+            for (int64_t p = graph_rowptr[i]; p < graph_rowptr[i + 1]; ++p) {
+                const int32_t j = graph_adj[p];
+                if (j < 0 || j >= M || j == i || (p > graph_rowptr[i] && j <= graph_adj[p - 1]))
+                    fail(ACC_SPMM_ERR_INVALID_CSR, "neighbours must be ascending, in range and without self loops");
+            }
+        }
         std::vector<int32_t> par, seq;
         std::vector<int64_t> seg;
-        build_dendrogram_host(M, csr_rowptr, csr_colidx, segment_length > 0 ? segment_length : kDefaultSegLen, 0.0, par, seq,
-                              seg, work_ratio, nullptr);
+        build_dendrogram_host(M, graph_rowptr, graph_adj, segment_length > 0 ? segment_length : kDefaultSegLen, 0.0, par,
+                              seq, seg, work_ratio);
         std::copy(par.begin(), par.end(), parent);
         if (leaf_sequence) std::copy(seq.begin(), seq.end(), leaf_sequence);
         if (segment_start) for (size_t i = 0; i < seg.size(); ++i) segment_start[i] = (int32_t)seg[i];

@@ -13,15 +13,12 @@
 //   7. TCOffset: scan of the tiles' popcounts
 //   8. values: entry -> TCOffset[tile] + popcount(lower bits)
 // The sort and the scans are rocPRIM device primitives; the rest are the kernels below.
-#include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
-
-#include "internal.h"
+#include "device_util.h"
 
 namespace accspmm {
 namespace {
+
+using namespace detail;
 
 __global__ void row_lengths_kernel(int64_t M, const int32_t* __restrict__ rowptr, const int32_t* __restrict__ perm,
                                    int32_t* __restrict__ len) {
@@ -44,11 +41,6 @@ __global__ __launch_bounds__(256) void make_keys_kernel(int64_t M, const int32_t
     const int32_t src = rowptr[perm[r]], dst = new_rowptr[r], len = new_rowptr[r + 1] - dst;
     const uint64_t hi = (uint64_t)(r / WH) << colbits;
     for (int32_t k = lane; k < len; k += 64) keys[dst + k] = hi | (uint32_t)colidx[src + k];
-}
-
-__global__ void mark_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, int32_t* __restrict__ head) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) head[i] = (i == 0 || sorted[i] != sorted[i - 1]) ? 1 : 0;
 }
 
 __global__ void compact_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, const int32_t* __restrict__ head,
@@ -159,28 +151,6 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(int64_t M, const in
     }
 }
 
-struct Scratch {  // rocPRIM temporary storage, grown on demand
-    DevBuf<char> buf;
-    void* get(size_t bytes) {
-        if (bytes > buf.n) buf.alloc(bytes);
-        return buf.p;
-    }
-};
-
-void exclusive_scan_i32(Scratch& tmp, const int32_t* in, int32_t* out, size_t n) {
-    size_t bytes = 0;
-    ACC_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, 0, n, rocprim::plus<int32_t>()));
-    ACC_HIP(rocprim::exclusive_scan(tmp.get(bytes), bytes, in, out, 0, n, rocprim::plus<int32_t>()));
-}
-
-inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
-
-int bits_for(int64_t n) {  // bits needed to hold values in [0, n)
-    int b = 1;
-    while (((int64_t)1 << b) < n) ++b;
-    return b;
-}
-
 }  // namespace
 
 void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,
@@ -220,12 +190,7 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
     sorted.alloc(nnz);
     hipLaunchKernelGGL(make_keys_kernel, dim3(blocks_for(M, 4)), dim3(256), 0, 0, M, d_rowptr, d_colidx, d_perm,
                        new_rowptr.p, WH, colbits, keys.p);
-    {
-        size_t bytes = 0;
-        ACC_HIP(rocprim::radix_sort_keys(nullptr, bytes, keys.p, sorted.p, (size_t)nnz, 0u, (unsigned)(colbits + winbits)));
-        ACC_HIP(rocprim::radix_sort_keys(tmp.get(bytes), bytes, keys.p, sorted.p, (size_t)nnz, 0u,
-                                         (unsigned)(colbits + winbits)));
-    }
+    sort_keys_u64(tmp, keys.p, sorted.p, (size_t)nnz, (unsigned)(colbits + winbits));
     keys.release();
 
     // 4. distinct columns per window

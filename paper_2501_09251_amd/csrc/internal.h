@@ -78,16 +78,31 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
                       const uint16_t* d_vals, const int32_t* d_perm, int32_t WH, int32_t TW, DeviceFormat& out,
                       bool tiles_only);
 
+// Symmetric adjacency of the pattern graph in (pinned) host memory: vertex i's neighbours,
+// ascending, without i itself, are adj[ptr[i] .. ptr[i+1]).
+struct HostGraph {
+    int64_t M = 0;
+    int64_t* ptr = nullptr;
+    int32_t* adj = nullptr;
+    HostGraph() = default;
+    HostGraph(const HostGraph&) = delete;
+    HostGraph& operator=(const HostGraph&) = delete;
+    ~HostGraph();
+};
+
+// graph.hip: the pattern graph of A + A^T (no diagonal) from the device CSR.
+void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx, HostGraph& g);
+
 // reorder.cpp: Step I of Algorithm 1 on the host, and the dendrogram's leaf sequence.
-// parent gets M entries (-1 for roots); seq the M rows in leaf order; seg_start the first
-// sequence position of every segment, terminated by M.  work_budget > 0 limits the
-// dendrogram construction to that many edge-record visits per graph entry (vertices +
-// directed edges); when exceeded the function returns false and the outputs are unspecified.
-// *work_ratio (may be null) receives the visits per graph entry; phase_seconds (may be null)
-// receives the seconds spent building the graph [0] and the dendrogram [1].
-bool build_dendrogram_host(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
-                           double work_budget, std::vector<int32_t>& parent, std::vector<int32_t>& seq,
-                           std::vector<int64_t>& seg_start, double* work_ratio, double* phase_seconds);
+// gptr / gadj: the symmetric adjacency (HostGraph layout).  parent gets M entries (-1 for
+// roots); seq the M rows in leaf order; seg_start the first sequence position of every
+// segment, terminated by M.  work_budget > 0 limits the dendrogram construction to that many
+// edge-record visits per graph entry (vertices + directed edges); when exceeded the function
+// returns false and the outputs are unspecified.  *work_ratio (may be null) receives the
+// visits per graph entry.
+bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, int32_t seg_len, double work_budget,
+                           std::vector<int32_t>& parent, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start,
+                           double* work_ratio);
 
 // ordering.hip: Step II of Algorithm 1 on the GPU.  d_perm gets M entries (new -> old).
 void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,

@@ -12,15 +12,12 @@
 // (segment, column); after a radix sort, entries with equal keys are adjacent ("runs"), and
 // every entry remembers its run.  A chain step then walks, for each entry of the current
 // row, that entry's run, and bumps a counter in LDS for every unvisited row in it.
-#include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
-
-#include "internal.h"
+#include "device_util.h"
 
 namespace accspmm {
 namespace {
+
+using namespace detail;
 
 constexpr int kChainThreads = 256;
 
@@ -67,11 +64,6 @@ __global__ __launch_bounds__(256) void make_entry_keys_kernel(int64_t M, const i
         entry_id[dst + k] = (uint32_t)(dst + k);
         entry_q[dst + k] = q;
     }
-}
-
-__global__ void mark_run_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, int32_t* __restrict__ head) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) head[i] = (i == 0 || sorted[i] != sorted[i - 1]) ? 1 : 0;
 }
 
 // run_id[i] = (inclusive count of heads up to i) - 1.  For every sorted position: remember
@@ -162,22 +154,6 @@ __global__ __launch_bounds__(kChainThreads) void chain_segments_kernel(
     }
 }
 
-struct Scratch {
-    DevBuf<char> buf;
-    void* get(size_t bytes) {
-        if (bytes > buf.n) buf.alloc(bytes);
-        return buf.p;
-    }
-};
-
-inline unsigned blocks_for(int64_t n, int per) { return (unsigned)((n + per - 1) / per); }
-
-int bits_for(int64_t n) {
-    int b = 1;
-    while (((int64_t)1 << b) < n) ++b;
-    return b;
-}
-
 }  // namespace
 
 void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,
@@ -208,11 +184,7 @@ void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowp
         return;
     }
     Scratch tmp;
-    auto scan = [&](const int32_t* in, int32_t* out, size_t n) {
-        size_t bytes = 0;
-        ACC_HIP(rocprim::exclusive_scan(nullptr, bytes, in, out, 0, n, rocprim::plus<int32_t>()));
-        ACC_HIP(rocprim::exclusive_scan(tmp.get(bytes), bytes, in, out, 0, n, rocprim::plus<int32_t>()));
-    };
+    auto scan = [&](const int32_t* in, int32_t* out, size_t n) { exclusive_scan_i32(tmp, in, out, n); };
 
     // entry ranges of the rows in sequence order
     DevBuf<int32_t> len, seq_rowptr, seg_of;
@@ -251,7 +223,7 @@ void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowp
     head.alloc(nnz + 1);
     head_excl.alloc(nnz + 1);
     ACC_HIP(hipMemset(head.p + nnz, 0, sizeof(int32_t)));
-    hipLaunchKernelGGL(mark_run_heads_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, 0, nnz, sorted_keys.p, head.p);
+    hipLaunchKernelGGL(mark_heads_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, 0, nnz, sorted_keys.p, head.p);
     scan(head.p, head_excl.p, nnz + 1);
     sorted_keys.release();
     int32_t n_runs = 0;

@@ -2,9 +2,9 @@
 //
 // Step I (dendrogram construction) is sequential by definition: vertices are visited in
 // ascending degree and every decision depends on the merges made before it, so it runs on
-// one host thread over flat arrays (the graph itself is built by all host threads).  This
-// file ends with the dendrogram's leaf sequence cut into segments; Step II (ordering
-// generation), which is independent per segment, runs on the GPU (ordering.hip).
+// one host thread over flat arrays.  The graph it reads is built on the GPU (graph.hip);
+// this file ends with the dendrogram's leaf sequence cut into segments; Step II (ordering
+// generation), which is independent per segment, runs on the GPU again (ordering.hip).
 //
 // Readings of what the paper leaves open (Eq. 1 is printed as the modularity itself, the
 // tie-breaks and the search scope of Step II are not stated):
@@ -19,89 +19,12 @@
 //  - chaining inside a segment: next is the unvisited leaf sharing the most column indices
 //    with the current row (at least one), ties to the earliest leaf of the sequence.
 #include <algorithm>
-#include <atomic>
-#include <chrono>
 #include <memory>
-#include <thread>
 
 #include "internal.h"
 
 namespace accspmm {
 namespace {
-
-template <class F>
-void parallel_chunks(int64_t n, int64_t grain, F&& fn) {
-    unsigned hw = std::thread::hardware_concurrency();
-    int nt = (int)std::min<int64_t>(hw ? hw : 4, std::max<int64_t>(1, (n + grain - 1) / grain));
-    nt = std::min(nt, 32);
-    if (nt <= 1) {
-        fn((int64_t)0, n);
-        return;
-    }
-    std::atomic<int64_t> next{0};
-    std::vector<std::thread> th;
-    auto body = [&]() {
-        for (;;) {
-            int64_t b = next.fetch_add(grain);
-            if (b >= n) break;
-            fn(b, std::min(n, b + grain));
-        }
-    };
-    for (int t = 1; t < nt; ++t) th.emplace_back(body);
-    body();
-    for (auto& t : th) t.join();
-}
-
-// Symmetric adjacency (pattern of A + A^T, no diagonal) as CSR with ascending neighbours.
-void build_graph(int64_t M, const int32_t* rowptr, const int32_t* colidx, std::vector<int64_t>& gptr,
-                 std::vector<int32_t>& gadj) {
-    // transpose pattern by counting sort
-    std::vector<std::atomic<int32_t>> cnt(M);
-    for (auto& c : cnt) c.store(0, std::memory_order_relaxed);
-    parallel_chunks(M, 1 << 14, [&](int64_t b, int64_t e) {
-        for (int64_t i = b; i < e; ++i)
-            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p)
-                if (colidx[p] != i) cnt[colidx[p]].fetch_add(1, std::memory_order_relaxed);
-    });
-    std::vector<int64_t> tptr(M + 1, 0);
-    for (int64_t i = 0; i < M; ++i) tptr[i + 1] = tptr[i] + cnt[i].load(std::memory_order_relaxed);
-    std::vector<int32_t> tadj(tptr[M]);
-    for (auto& c : cnt) c.store(0, std::memory_order_relaxed);
-    parallel_chunks(M, 1 << 14, [&](int64_t b, int64_t e) {
-        for (int64_t i = b; i < e; ++i)
-            for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
-                int32_t j = colidx[p];
-                if (j != i) tadj[tptr[j] + cnt[j].fetch_add(1, std::memory_order_relaxed)] = (int32_t)i;
-            }
-    });
-    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
-        for (int64_t j = b; j < e; ++j) std::sort(tadj.begin() + tptr[j], tadj.begin() + tptr[j + 1]);
-    });
-    // union of row i of A (ascending) and row i of A^T (ascending), without i itself
-    auto merge_row = [&](int64_t i, int32_t* out) -> int64_t {
-        int64_t a = rowptr[i], ae = rowptr[i + 1], t = tptr[i], te = tptr[i + 1], n = 0;
-        while (a < ae || t < te) {
-            int32_t x;
-            if (t >= te || (a < ae && colidx[a] <= tadj[t])) {
-                x = colidx[a++];
-                if (t < te && tadj[t] == x) ++t;
-            } else x = tadj[t++];
-            if (x == i) continue;
-            if (out) out[n] = x;
-            ++n;
-        }
-        return n;
-    };
-    gptr.assign(M + 1, 0);
-    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
-        for (int64_t i = b; i < e; ++i) gptr[i + 1] = merge_row(i, nullptr);
-    });
-    for (int64_t i = 0; i < M; ++i) gptr[i + 1] += gptr[i];
-    gadj.resize(gptr[M]);
-    parallel_chunks(M, 1 << 12, [&](int64_t b, int64_t e) {
-        for (int64_t i = b; i < e; ++i) merge_row(i, gadj.data() + gptr[i]);
-    });
-}
 
 struct Edge {
     int32_t to;
@@ -147,7 +70,7 @@ private:
 // Step I.  parent[v] = community v was merged into (-1: root); children lists in merge order.
 // `work` counts the edge records visited; when it exceeds `work_limit` (> 0) the
 // construction stops early and returns false.
-bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::vector<int32_t>& gadj,
+bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
                       std::vector<int32_t>& parent, std::vector<int32_t>& first_child,
                       std::vector<int32_t>& next_sibling, int64_t work_limit, int64_t& work) {
     const int64_t two_m = gptr[M];
@@ -254,26 +177,16 @@ bool build_dendrogram(int64_t M, const std::vector<int64_t>& gptr, const std::ve
 
 }  // namespace
 
-bool build_dendrogram_host(int64_t M, const int32_t* rowptr, const int32_t* colidx, int32_t seg_len,
-                           double work_budget, std::vector<int32_t>& parent, std::vector<int32_t>& seq,
-                           std::vector<int64_t>& seg_start, double* work_ratio, double* phase_seconds) {
-    auto now = [] { return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count(); };
-    const double t0 = now();
-    std::vector<int64_t> gptr;
-    std::vector<int32_t> gadj;
-    build_graph(M, rowptr, colidx, gptr, gadj);
-    const double t1 = now();
+bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, int32_t seg_len, double work_budget,
+                           std::vector<int32_t>& parent, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start,
+                           double* work_ratio) {
     std::vector<int32_t> first_child, next_sibling;
     const int64_t graph_size = gptr[M] + M;
     int64_t work = 0;
     const bool complete = build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling,
                                            work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0, work);
     if (work_ratio) *work_ratio = graph_size ? (double)work / (double)graph_size : 0.0;
-    const double t2 = now();
-    if (phase_seconds) { phase_seconds[0] = t1 - t0; phase_seconds[1] = t2 - t1; }
     if (!complete) return false;
-    std::vector<int32_t>().swap(gadj);
-    std::vector<int64_t>().swap(gptr);
 
     // leaf sequence: roots by ascending id; a root, then its children's subtrees in merge
     // order; each tree's sequence is cut into segments of at most seg_len leaves

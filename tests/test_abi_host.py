@@ -89,9 +89,24 @@ def test_no_gpu_means_a_loud_error_not_a_fallback():
 
 
 # --------------------------------------------------------------- host stage: dendrogram
+def _pattern_graph(rowptr, colidx):
+    """Symmetric adjacency of A + A^T without the diagonal, built with scipy (independent of
+    both the library and the oracle)."""
+    import scipy.sparse as sp
+    M = len(rowptr) - 1
+    A = sp.csr_matrix((np.ones(len(colidx), np.int8), colidx, rowptr), shape=(M, M))
+    G = ((A + A.T) != 0).astype(np.int8).tolil()
+    G.setdiag(0)
+    G = G.tocsr()
+    G.eliminate_zeros()
+    G.sort_indices()
+    return G.indptr.astype(np.int64), G.indices.astype(np.int32)
+
+
 def _check_dendrogram(rowptr, colidx, seg):
     M = len(rowptr) - 1
-    parent, seq, seg_start, work = acc.acc_spmm_dendrogram_host(M, len(colidx), rowptr, colidx, seg)
+    gptr, gadj = _pattern_graph(rowptr, colidx)
+    parent, seq, seg_start, work = acc.acc_spmm_dendrogram_host(M, gptr, gadj, seg)
     oparent, ochild = oracle.dendrogram(rowptr, colidx)
     np.testing.assert_array_equal(parent, oparent)
     _, _, oseq, oseg = oracle.ordering(rowptr, colidx, oparent, ochild, seg, details=True)
@@ -119,14 +134,16 @@ def test_dendrogram_host_equals_oracle_on_the_workloads(cfg, shrink):
     _check_dendrogram(w.rowptr, w.colidx, 1024)
 
 
-def test_dendrogram_host_accepts_unsorted_rows_and_special_graphs():
-    rowptr, colidx, _ = csr_from_rows([[3, 1], [0], [], [0, 2]])
-    parent, _, _, _ = acc.acc_spmm_dendrogram_host(4, 5, rowptr, colidx)
-    srp, sci, _ = csr_from_rows([[1, 3], [0], [], [0, 2]])
-    np.testing.assert_array_equal(parent, oracle.dendrogram(srp, sci)[0])
+def test_dendrogram_host_special_graphs_and_bad_input():
     for M, edges in ((12, [(0, i) for i in range(1, 12)]), (5, []), (9, [(i, i + 1) for i in range(8)])):
         rowptr, colidx, _ = csr_from_edges(M, edges)
         _check_dendrogram(rowptr, colidx, 4)
+    for gptr, gadj in (([0, 1, 2], [0, 0]),       # self loop
+                       ([0, 2, 2], [1, 1]),       # not ascending
+                       ([0, 1, 2], [1, 5])):      # out of range
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_dendrogram_host(2, gptr, gadj)
+        assert e.value.code == -2
 
 
 # ----------------------------------------------------------------- host stage: schedule

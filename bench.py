@@ -169,7 +169,7 @@ def main() -> int:
 
     acc.acc_spmm_destroy(plan)
     out = {
-        "metric": "SpMM effective GFLOP/s (2*nnz*N/t)",
+        "metric": "SpMM effective GFLOP/s (2·nnz·N/t) + achieved HBM GB/s vs roofline, 1 MI355X",
         "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",

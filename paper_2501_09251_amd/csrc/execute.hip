@@ -404,9 +404,16 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     if ((reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
         fail(ACC_SPMM_ERR_INVALID_ARG, "B and C must be 16-byte aligned");
     if (f.M == 0) return;
-    if (plan.n_slots > 0 && plan.workspace_N < N) {
-        plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
-        plan.workspace_N = N;
+    int dev = -1;
+    ACC_HIP(hipGetDevice(&dev));
+    if (dev != plan.device) fail(ACC_SPMM_ERR_INVALID_ARG, "the plan lives on another device than the current one");
+    if (plan.n_slots > 0) {
+        // grown only when a wider N arrives; hipFree inside alloc() waits for kernels still using the old buffer
+        std::lock_guard<std::mutex> lock(plan.workspace_mutex);
+        if (plan.workspace_N < N) {
+            plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
+            plan.workspace_N = N;
+        }
     }
     ExecParams p;
     p.rwo = f.row_window_offset.p;

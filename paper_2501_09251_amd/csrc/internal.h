@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -127,6 +128,7 @@ struct Plan {
     DevBuf<SplitWindow> d_splits;
     int64_t n_slots = 0;
     // partial-sum workspace, grown on demand by execute
+    mutable std::mutex workspace_mutex;
     mutable DevBuf<float> workspace;
     mutable int32_t workspace_N = 0;
     // optional CSR copy for the naive baseline

@@ -47,6 +47,7 @@ struct ExecParams {
     int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
     int32_t N;
     bool wide;         // B needs 64-bit row offsets
+    int32_t waves_per_block;
 };
 
 template <int FPL>
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int per_xcd = (p.n_blocks + 7) >> 3;
     const int lblock = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (lblock >= p.n_blocks) return;
-    const int item_id = __builtin_amdgcn_readfirstlane(lblock * kWavesPerBlock + (int)(threadIdx.x >> 6));
+    const int item_id = __builtin_amdgcn_readfirstlane(lblock * (int)(blockDim.x >> 6) + (int)(threadIdx.x >> 6));
     if (item_id >= p.n_items) return;
     const WorkItem it = p.items[item_id];
     const int w_begin = __builtin_amdgcn_readfirstlane(it.w_begin);
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
 template <int FPL, int NS, int DEPTH, bool NT, bool WIDE>
 void launch_one(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
-    dim3 grid(blocks, n_slab_launches), block(kWavesPerBlock * 64);
+    dim3 grid(blocks, n_slab_launches), block(p.waves_per_block * 64);
     hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, NT, WIDE>), grid, block, 0, stream, p.rwo, p.tco, p.a2b, p.bits,
                        p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N);
 }
@@ -427,7 +428,8 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.C = static_cast<float*>(C);
     p.ws = plan.workspace.p;
     p.n_items = (int32_t)plan.items.size();
-    p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    p.waves_per_block = kWavesPerBlock;
+    p.n_blocks = (p.n_items + p.waves_per_block - 1) / p.waves_per_block;
     p.N = N;
     p.wide = plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32);
     const int default_depth = N == 128 ? 3 : (N >= 256 ? 2 : 1);

@@ -248,6 +248,28 @@ def test_edge_cases():
     acc.acc_spmm_destroy(plan)
 
 
+def test_wide_matrix_uses_64bit_row_offsets():
+    """K >= 2^24 switches the kernel to 64-bit B row offsets; columns at both ends of the range."""
+    rng = np.random.default_rng(3)
+    M, K, N = 100, (1 << 24) + 64, 16
+    rows = []
+    for i in range(M):
+        cols = set(rng.integers(0, K, 20).tolist()) | {K - 1 - i, i}
+        rows.append(sorted(cols))
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    B = wl.dense(K, N, 5, "normal", 0.0, 1.0)
+    for lb in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON):
+        plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                    acc.make_options(load_balance=lb, max_tiles_per_item=4))
+        try:
+            check_format(plan, rowptr, colidx, vals)
+            C = run_spmm(plan, B, M, N)
+            check_against_oracle(rowptr, colidx, vals, B, C)
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+
 def test_paper_geometry_8x8_format_and_closed_form_size():
     w = wl.config(2, 7)
     plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,

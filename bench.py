@@ -53,6 +53,8 @@ def main() -> int:
     ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
     ap.add_argument("--no-prefetch", action="store_true")
     ap.add_argument("--streaming-stores", action="store_true")
+    ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2),
+                    help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-naive", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,7 +85,8 @@ def main() -> int:
     t0 = time.time()
     opt = acc.make_options(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
                            max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
-                           no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores))
+                           no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores),
+                           value_fetch=args.value_fetch)
     plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
     t_plan = time.time() - t0
     st = acc.acc_spmm_plan_stats(plan)

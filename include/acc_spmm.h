@@ -88,6 +88,11 @@ typedef struct {
      * 0 = default (3 for N = 128, 2 for N >= 256, 1 for N <= 64).  Ignored when no_prefetch
      * is set. */
     int32_t pipeline_depth;
+    /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its
+     * own up-to-four values; 2 = the wavefront loads the tile's values once and the lanes
+     * exchange them across registers; 0 = default: 2 when the plan has at least 24 entries
+     * per tile on average, else 1. */
+    int32_t value_fetch;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */

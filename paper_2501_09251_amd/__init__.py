@@ -43,6 +43,7 @@ class acc_spmm_options(ctypes.Structure):
         ("max_tiles_per_item", ctypes.c_int32), ("window_height", ctypes.c_int32), ("tile_width", ctypes.c_int32),
         ("segment_length", ctypes.c_int32), ("ibd_threshold", ctypes.c_float), ("keep_csr", ctypes.c_int32),
         ("no_prefetch", ctypes.c_int32), ("streaming_stores", ctypes.c_int32), ("pipeline_depth", ctypes.c_int32),
+        ("value_fetch", ctypes.c_int32),
     ]
 
 

@@ -14,6 +14,13 @@
 // position inside an MFMA is a free choice and no transpose through LDS is needed: the
 // four k-values of one feature come from four registers and are packed with v_perm_b32.
 //
+// The packed values of a tile reach the lanes in one of two ways (template COOP).  Per-lane:
+// each lane reads its up-to-four values itself (four 2-byte loads).  Cooperative: the wave
+// reads the tile's contiguous values once, one dword per lane, and every lane then picks its
+// values out of the other lanes' registers with ds_bpermute.  The second way issues a
+// quarter of the memory instructions and wins when tiles are dense; the first wins on the
+// sparse tiles of power-law inputs.  The plan's mean entries per tile selects the way.
+//
 // Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
 // values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
 // words of tile t+DEPTH+1 are requested one step before they are needed for addresses.
@@ -47,7 +54,7 @@ struct ExecParams {
     int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
     int32_t N;
     bool wide;         // B needs 64-bit row offsets
-    int32_t waves_per_block;
+    bool coop;         // cooperative value fetch
 };
 
 template <int FPL>
@@ -80,8 +87,12 @@ struct TileMeta {       // index words of one tile
 template <int FPL, int NS>
 struct TileData {       // what the multiply needs
     Chunk<FPL> b[NS][4];
-    uint32_t h[4];      // up to four packed values (fp16 bits)
+    // per-lane fetch: v[0..3] = up to four packed values (fp16 bits).
+    // cooperative fetch: v[0..2] = the tile's packed values, chunk k's dword L in lane L;
+    //                    v[3] = index of this lane's first value relative to the first loaded half
+    uint32_t v[4];
     uint32_t nib;       // this lane's four bitmap bits
+    uint32_t nchunk;    // cooperative fetch: 64-dword chunks that hold values (wave-uniform)
 };
 
 // The index arrays are passed as separate const __restrict__ kernel arguments (not inside a
@@ -89,7 +100,7 @@ struct TileData {       // what the multiply needs
 // become scalar loads.
 // WIDE = false: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
 // with one 24-bit multiply in 32 bits and added to the uniform base by the load itself.
-template <int FPL, int NS, int DEPTH, bool NT, bool WIDE>
+template <int FPL, int NS, int DEPTH, bool NT, bool WIDE, bool COOP>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
@@ -109,7 +120,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int per_xcd = (p.n_blocks + 7) >> 3;
     const int lblock = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (lblock >= p.n_blocks) return;
-    const int item_id = __builtin_amdgcn_readfirstlane(lblock * (int)(blockDim.x >> 6) + (int)(threadIdx.x >> 6));
+    const int item_id = __builtin_amdgcn_readfirstlane(lblock * kWavesPerBlock + (int)(threadIdx.x >> 6));
     if (item_id >= p.n_items) return;
     const WorkItem it = p.items[item_id];
     const int w_begin = __builtin_amdgcn_readfirstlane(it.w_begin);
@@ -204,23 +215,69 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         const int pre = (w1 ? c0 : 0) + (w2 ? c1 : 0) + (w3 ? c2 : 0);
         const uint32_t nib = (uint32_t)(word >> sh) & 15u;
         const uint32_t i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
-        const uint32_t i1 = i0 + (nib & 1u);
-        const uint32_t i2 = i1 + ((nib >> 1) & 1u);
-        const uint32_t i3 = i2 + ((nib >> 2) & 1u);
-        const char* vb = reinterpret_cast<const char*>(p.vals);
-        d.h[0] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i0 << 1));
-        d.h[1] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i1 << 1));
-        d.h[2] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i2 << 1));
-        d.h[3] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i3 << 1));
+        if constexpr (COOP) {
+            const uint32_t cnt = (uint32_t)(c0 + c1 + c2 + __builtin_popcountll(m.bm[3]));
+            const uint32_t first_half = (uint32_t)m.tco & ~1u;        // first loaded value (dword aligned)
+            const uint32_t span = ((uint32_t)m.tco & 1u) + cnt;       // halves from there to the tile's end
+            const uint32_t nchunk = (span + 127u) >> 7;               // 0..3
+            const uint32_t* v32 = reinterpret_cast<const uint32_t*>(p.vals) + (first_half >> 1);
+            d.v[0] = 0; d.v[1] = 0; d.v[2] = 0;
+            // only the lanes whose dword holds values of this tile read (so nothing is read past the tile)
+            if ((uint32_t)lane * 2u < span) d.v[0] = v32[lane];
+            if (nchunk > 1 && (uint32_t)(64 + lane) * 2u < span) d.v[1] = v32[64 + lane];
+            if (nchunk > 2 && (uint32_t)(128 + lane) * 2u < span) d.v[2] = v32[128 + lane];
+            d.v[3] = i0 - first_half;
+            d.nchunk = nchunk;
+        } else {
+            const uint32_t i1 = i0 + (nib & 1u);
+            const uint32_t i2 = i1 + ((nib >> 1) & 1u);
+            const uint32_t i3 = i2 + ((nib >> 2) & 1u);
+            const char* vb = reinterpret_cast<const char*>(p.vals);
+            d.v[0] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i0 << 1));
+            d.v[1] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i1 << 1));
+            d.v[2] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i2 << 1));
+            d.v[3] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i3 << 1));
+            d.nchunk = 0;
+        }
         d.nib = nib;
     };
 
-    auto multiply = [&](const TileData<FPL, NS>& d) {
-        const uint32_t a0 = (d.nib & 1u) ? d.h[0] : 0u;
-        const uint32_t a1 = (d.nib & 2u) ? d.h[1] : 0u;
-        const uint32_t a2 = (d.nib & 4u) ? d.h[2] : 0u;
-        const uint32_t a3 = (d.nib & 8u) ? d.h[3] : 0u;
-        const uintx2 au{a0 | (a1 << 16), a2 | (a3 << 16)};
+    // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
+    auto operand_a = [&](const TileData<FPL, NS>& d) -> uintx2 {
+        const uint32_t nib = d.nib;
+        uint32_t h[4];
+        if constexpr (COOP) {
+            uint32_t r[4];
+            r[0] = d.v[3];
+            r[1] = r[0] + (nib & 1u);
+            r[2] = r[1] + ((nib >> 1) & 1u);
+            r[3] = r[2] + ((nib >> 2) & 1u);
+            const int nchunk = __builtin_amdgcn_readfirstlane((int)d.nchunk);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int addr = (int)((r[q] >> 1) << 2);  // source lane * 4; the hardware uses it modulo 64 lanes
+                uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[0]);
+                if (nchunk > 1) {
+                    const uint32_t x1 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[1]);
+                    x = ((r[q] >> 7) == 1u) ? x1 : x;
+                }
+                if (nchunk > 2) {
+                    const uint32_t x2 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[2]);
+                    x = ((r[q] >> 7) == 2u) ? x2 : x;
+                }
+                h[q] = (r[q] & 1u) ? (x >> 16) : (x & 0xFFFFu);
+            }
+        } else {
+            h[0] = d.v[0]; h[1] = d.v[1]; h[2] = d.v[2]; h[3] = d.v[3];
+        }
+        const uint32_t a0 = (nib & 1u) ? h[0] : 0u;
+        const uint32_t a1 = (nib & 2u) ? h[1] : 0u;
+        const uint32_t a2 = (nib & 4u) ? h[2] : 0u;
+        const uint32_t a3 = (nib & 8u) ? h[3] : 0u;
+        return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
+    };
+
+    auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) {
         const half4 a = __builtin_bit_cast(half4, au);
 #pragma unroll
         for (int s = 0; s < NS; ++s)
@@ -273,7 +330,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             TileData<FPL, NS> d;
             load_meta(tt, m);
             issue(m, d);
-            multiply(d);
+            multiply(d, operand_a(d));
             after_tile(tt);
         }
     } else {
@@ -292,11 +349,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             for (int r = 0; r < R; ++r) {
                 const int tt = t + r;
                 if (tt >= te) break;
+                // tile tt's sparse operand first: its cross-lane fetch (if any) shares a wait counter
+                // with the scalar index loads issued next
+                const uintx2 au = operand_a(data[r]);
+                if constexpr (COOP) __builtin_amdgcn_sched_barrier(0);
                 TileMeta next_meta;
                 load_meta(tt + DEPTH + 1, next_meta);                     // slot r, free since tile tt was issued
                 issue(meta[(r + DEPTH) % R], data[(r + DEPTH) % R]);     // tile tt+DEPTH
                 meta[r] = next_meta;
-                multiply(data[r]);
+                multiply(data[r], au);
                 after_tile(tt);
             }
         }
@@ -352,23 +413,29 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
         dst[i] = src[i];
 }
 
-template <int FPL, int NS, int DEPTH, bool NT, bool WIDE>
+template <int FPL, int NS, int DEPTH, bool NT, bool WIDE, bool COOP>
 void launch_one(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
-    dim3 grid(blocks, n_slab_launches), block(p.waves_per_block * 64);
-    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, NT, WIDE>), grid, block, 0, stream, p.rwo, p.tco, p.a2b, p.bits,
-                       p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N);
+    dim3 grid(blocks, n_slab_launches), block(kWavesPerBlock * 64);
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, NT, WIDE, COOP>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
+                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N);
+}
+
+template <int FPL, int NS, int DEPTH, bool NT>
+void launch_nt(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
+    if (p.wide) {
+        if (p.coop) launch_one<FPL, NS, DEPTH, NT, true, true>(p, n_slab_launches, stream);
+        else launch_one<FPL, NS, DEPTH, NT, true, false>(p, n_slab_launches, stream);
+    } else {
+        if (p.coop) launch_one<FPL, NS, DEPTH, NT, false, true>(p, n_slab_launches, stream);
+        else launch_one<FPL, NS, DEPTH, NT, false, false>(p, n_slab_launches, stream);
+    }
 }
 
 template <int FPL, int NS, int DEPTH>
 void launch_depth(const ExecParams& p, int n_slab_launches, bool plain_stores, hipStream_t stream) {
-    if (p.wide) {
-        if (plain_stores) launch_one<FPL, NS, DEPTH, false, true>(p, n_slab_launches, stream);
-        else launch_one<FPL, NS, DEPTH, true, true>(p, n_slab_launches, stream);
-    } else {
-        if (plain_stores) launch_one<FPL, NS, DEPTH, false, false>(p, n_slab_launches, stream);
-        else launch_one<FPL, NS, DEPTH, true, false>(p, n_slab_launches, stream);
-    }
+    if (plain_stores) launch_nt<FPL, NS, DEPTH, false>(p, n_slab_launches, stream);
+    else launch_nt<FPL, NS, DEPTH, true>(p, n_slab_launches, stream);
 }
 
 template <int FPL, int NS>
@@ -428,8 +495,10 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.C = static_cast<float*>(C);
     p.ws = plan.workspace.p;
     p.n_items = (int32_t)plan.items.size();
-    p.waves_per_block = kWavesPerBlock;
-    p.n_blocks = (p.n_items + p.waves_per_block - 1) / p.waves_per_block;
+    p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
+    // dense tiles: fetch the values cooperatively (see the file header); measured break-even is
+    // between 18 (power-law inputs, per-lane wins) and 35 (block / stencil inputs) entries per tile
+    p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && plan.stats.mean_nnz_per_tile >= 24.0);
     p.N = N;
     p.wide = plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32);
     const int default_depth = N == 128 ? 3 : (N >= 256 ? 2 : 1);

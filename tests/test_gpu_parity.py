@@ -116,14 +116,15 @@ def test_all_widths_with_and_without_load_balancing(N, lb):
 
 @pytest.mark.parametrize("N", [32, 128, 256])
 def test_every_kernel_variant(N):
-    """All pipeline depths (0 = no prefetch) and both store policies give the same, correct C."""
+    """All pipeline depths (0 = no prefetch), both store policies and both ways of fetching
+    the packed values give the same, correct C."""
     w = wl.config(5, 9)
     B = wl.dense(w.K, N, 77, "normal", 0.0, 1.0)
     ref = None
     for depth in (0, 1, 2, 3):
-        for streaming in (0, 1):
+        for streaming, fetch in ((0, 1), (1, 1), (0, 2), (1, 2)):
             opt = acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16, streaming_stores=streaming,
-                                   no_prefetch=int(depth == 0), pipeline_depth=depth)
+                                   no_prefetch=int(depth == 0), pipeline_depth=depth, value_fetch=fetch)
             plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
             try:
                 C = run_spmm(plan, B, w.M, N)
@@ -134,6 +135,29 @@ def test_every_kernel_variant(N):
                 check_against_oracle(w.rowptr, w.colidx, w.vals, B, C)
             else:
                 np.testing.assert_array_equal(C, ref)      # same summation order in every variant
+
+
+@pytest.mark.parametrize("fetch", [0, 1, 2])
+@pytest.mark.parametrize("N", [16, 64, 128, 512])
+def test_dense_tiles_at_odd_value_offsets(fetch, N):
+    """Full 16x16 tiles whose packed values start at an odd index (a one-entry first tile),
+    tiles with more than 128 and more than 254 values, and a ragged last tile: the cases that
+    decide how many 64-dword chunks the cooperative value fetch reads."""
+    rng = np.random.default_rng(N)
+    rows = [[0]] + [list(range(40)) for _ in range(15)]           # window 0: 1 + 15*16, 240, 120 entries
+    rows += [list(range(40)) for _ in range(16)]                  # window 1: 256, 256, 128
+    rows += [list(range(0, 40, 3)) for _ in range(9)]             # window 2: ragged, sparse
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    B = f16(rng.standard_normal((40, N)))
+    plan = acc.acc_spmm_plan_ex(len(rows), 40, len(colidx), rowptr, colidx, vals,
+                                acc.make_options(reorder=acc.ACC_SPMM_OFF, value_fetch=fetch, keep_csr=1))
+    try:
+        check_format(plan, rowptr, colidx, vals)
+        C = run_spmm(plan, B, len(rows), N)
+        check_against_oracle(rowptr, colidx, vals, B, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
 
 
 def test_identity_and_permutation_matrices_are_exact():

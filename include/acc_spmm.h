@@ -91,7 +91,7 @@ typedef struct {
     /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its
      * own up-to-four values; 2 = the wavefront loads the tile's values once and the lanes
      * exchange them across registers; 0 = default: 2 when the plan has at least 24 entries
-     * per tile on average, else 1. */
+     * per tile on average, or when N is 32 or 64 and the plan has at least 16384 tiles; else 1. */
     int32_t value_fetch;
 } acc_spmm_options;
 
@@ -153,7 +153,10 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz
  * Enqueue C = A.B on `stream` (Algorithm 2's runtime kernel; Section 3.5's split row
  * windows are combined by a second small kernel on the same stream).
  *   B       DEVICE fp16, row-major K x N, leading dimension N, 16-byte aligned
- *   N       16, 32, 64, 128, or a multiple of 128 up to 512
+ *   N       1 .. 65536.  A lane of the kernel handles the largest power of two of features,
+ *           up to 8, that divides N, so multiples of 8 run at full speed (each lane reads 16
+ *           bytes of a B row at once), other even N slower, odd N slowest; 16, 32, 64 and
+ *           multiples of 128 leave no lane idle
  *   C       DEVICE fp32, row-major M x N, leading dimension N, 16-byte aligned; every
  *           element is overwritten (rows without entries become 0); rows are in the
  *           caller's original order whatever the plan's internal reordering

@@ -38,6 +38,7 @@ typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef int32_t intx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerBlock = 4;
+constexpr int kMaxN = 65536;
 
 struct ExecParams {
     const int32_t* __restrict__ rwo;
@@ -55,6 +56,8 @@ struct ExecParams {
     int32_t N;
     bool wide;         // B needs 64-bit row offsets
     bool coop;         // cooperative value fetch
+    bool tail;         // N is not a whole number of slabs
+    int32_t fpl, ns, grid_y, depth, streaming_stores;
 };
 
 template <int FPL>
@@ -100,13 +103,17 @@ struct TileData {       // what the multiply needs
 // become scalar loads.
 // WIDE = false: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
 // with one 24-bit multiply in 32 bits and added to the uniform base by the load itself.
-template <int FPL, int NS, int DEPTH, bool NT, bool WIDE, bool COOP>
+// TAIL = true: N is not a whole number of this kernel's feature slabs (16*FPL features per slab,
+// NS slabs per wave, gridDim.y waves per item); lanes whose features lie at or beyond N neither
+// load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
+template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
     const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, float* __restrict__ g_C,
-    float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg) {
+    float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg, int32_t streaming_stores) {
     constexpr int R = DEPTH + 1;
+    constexpr int SW = 16 * FPL;  // features per slab
     struct {
         const int32_t* __restrict__ rwo; const int32_t* __restrict__ tco; const int32_t* __restrict__ a2b;
         const uint64_t* __restrict__ bits; const uint16_t* __restrict__ vals; const int32_t* __restrict__ perm_pad;
@@ -130,8 +137,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const bool partial = w_end_raw < 0;
     const int w_end = partial ? w_begin + 1 : w_end_raw;
     const int N = p.N;
-    const int slab_base = (int)(blockIdx.y * NS) * 128;  // first feature of this launch's slabs (NS>1 or grid.y>1 only when FPL==8)
-    const int f0 = slab_base + c * FPL;
+    const int f0 = (int)(blockIdx.y * NS) * SW + c * FPL;  // this lane's first feature in slab 0 of this wave
+    bool act[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) act[s] = !TAIL || (f0 + s * SW < N);
+    const bool nt = streaming_stores != 0;
 
     // lane constants of the bitmap decode: bit index of (row c, k 4g) is c*16 + 4g
     const int wq = c >> 2;
@@ -148,32 +158,31 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     // Rows of C owned by this lane for the window being accumulated (requested when the window
     // starts, so that closing the window does not wait on a fresh load).
     intx4 rows_cur = intx4{4 * g, 4 * g + 1, 4 * g + 2, 4 * g + 3};
-    auto load_rows = [&](int w) {
+    auto load_rows = [&](int w) __attribute__((always_inline)) {
         rows_cur = *reinterpret_cast<const intx4*>(p.perm_pad + (size_t)w * 16 + 4 * g);
     };
     float* const out_base = partial ? p.ws + (size_t)(-w_end_raw - 1) * 16 * (size_t)N : p.C;
 
-    auto flush = [&]() {  // store the accumulators to rows_cur and clear them
+    auto flush = [&]() __attribute__((always_inline)) {  // store the accumulators to rows_cur and clear them
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const int row = rows_cur[r];
-            if (row >= 0) {
 #pragma unroll
-                for (int s = 0; s < NS; ++s) {
-                    float* dst = out_base + (size_t)row * (size_t)N + f0 + s * 128;
-                    if constexpr (FPL >= 4) {
+            for (int s = 0; s < NS; ++s) {
+                if (row < 0 || !act[s]) continue;
+                float* dst = out_base + (size_t)row * (size_t)N + f0 + s * SW;
+                if constexpr (FPL >= 4) {
 #pragma unroll
-                        for (int m = 0; m < FPL; m += 4) {
-                            floatx4 v{acc[s][m][r], acc[s][m + 1][r], acc[s][m + 2][r], acc[s][m + 3][r]};
-                            if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(dst + m));
-                            else *reinterpret_cast<floatx4*>(dst + m) = v;
-                        }
-                    } else {
+                    for (int m = 0; m < FPL; m += 4) {
+                        floatx4 v{acc[s][m][r], acc[s][m + 1][r], acc[s][m + 2][r], acc[s][m + 3][r]};
+                        if (nt) __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(dst + m));
+                        else *reinterpret_cast<floatx4*>(dst + m) = v;
+                    }
+                } else {
 #pragma unroll
-                        for (int m = 0; m < FPL; ++m) {
-                            if constexpr (NT) __builtin_nontemporal_store(acc[s][m][r], dst + m);
-                            else dst[m] = acc[s][m][r];
-                        }
+                    for (int m = 0; m < FPL; ++m) {
+                        if (nt) __builtin_nontemporal_store(acc[s][m][r], dst + m);
+                        else dst[m] = acc[s][m][r];
                     }
                 }
             }
@@ -184,7 +193,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
     };
 
-    auto load_meta = [&](int t, TileMeta& m) {
+    auto load_meta = [&](int t, TileMeta& m) __attribute__((always_inline)) {
         t = t < te ? t : te - 1;  // past the end: re-read the last tile (always in bounds)
         m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 16 + 4 * g);
         const uint64_t* bm = p.bits + (size_t)t * 4;
@@ -192,7 +201,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         m.tco = p.tco[t];
     };
 
-    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) {
+    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint16_t* row;
@@ -203,7 +212,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
             }
 #pragma unroll
-            for (int s = 0; s < NS; ++s) load_chunk<FPL>(row + s * 128, d.b[s][q]);
+            for (int s = 0; s < NS; ++s) {
+                if constexpr (TAIL) {
+#pragma unroll
+                    for (int k = 0; k < Chunk<FPL>::DW; ++k) d.b[s][q].d[k] = 0;
+                    if (act[s]) load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                } else {
+                    load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                }
+            }
         }
         // this lane's bitmap word and the popcount of the words below it, by plain selects
         const int c0 = __builtin_popcountll(m.bm[0]), c1 = __builtin_popcountll(m.bm[1]),
@@ -243,7 +260,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     };
 
     // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
-    auto operand_a = [&](const TileData<FPL, NS>& d) -> uintx2 {
+    auto operand_a = [&](const TileData<FPL, NS>& d) __attribute__((always_inline)) -> uintx2 {
         const uint32_t nib = d.nib;
         uint32_t h[4];
         if constexpr (COOP) {
@@ -277,7 +294,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
     };
 
-    auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) {
+    auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) __attribute__((always_inline)) {
         const half4 a = __builtin_bit_cast(half4, au);
 #pragma unroll
         for (int s = 0; s < NS; ++s)
@@ -295,7 +312,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     int w = w_begin;
     int wend = partial ? te : p.rwo[w + 1];
     int wend_next = partial ? te : p.rwo[(w + 2 < w_end) ? w + 2 : w_end];
-    auto next_window = [&]() {
+    auto next_window = [&]() __attribute__((always_inline)) {
         ++w;
         wend = wend_next;
         if (w < w_end) {
@@ -312,7 +329,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     }
     if (tb >= te) return;
 
-    auto after_tile = [&](int tt) {  // tile tt has been multiplied: close the window(s) ending there
+    auto after_tile = [&](int tt) __attribute__((always_inline)) {  // tile tt has been multiplied: close the window(s) ending there
         if (__builtin_expect(tt + 1 != wend, 1)) return;
         flush();
         if (partial) return;
@@ -325,9 +342,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
 
     if constexpr (DEPTH == 0) {
         // ablation: every tile's loads are issued only when the tile is computed
+        TileMeta m;
+        TileData<FPL, NS> d;
         for (int tt = tb; tt < te; ++tt) {
-            TileMeta m;
-            TileData<FPL, NS> d;
             load_meta(tt, m);
             issue(m, d);
             multiply(d, operand_a(d));
@@ -371,6 +388,17 @@ __global__ __launch_bounds__(256) void combine_split_kernel(const SplitWindow* _
                                                             const int32_t* __restrict__ perm_pad,
                                                             float* __restrict__ C, int32_t N) {
     const SplitWindow sw = splits[blockIdx.x];
+    if (N & 3) {  // rows of C are not 16-byte aligned: one float at a time
+        for (int e = threadIdx.x; e < 16 * N; e += blockDim.x) {
+            const int r = e / N, j = e - r * N;
+            const int row = perm_pad[(size_t)sw.window * 16 + r];
+            if (row < 0) continue;
+            float s = 0.f;
+            for (int slot = sw.slot_begin; slot < sw.slot_end; ++slot) s += ws[((size_t)slot * 16 + r) * (size_t)N + j];
+            __builtin_nontemporal_store(s, C + (size_t)row * (size_t)N + j);
+        }
+        return;
+    }
     const int n4 = N >> 2;
     for (int e = threadIdx.x; e < 16 * n4; e += blockDim.x) {
         const int r = e / n4, j = (e - r * n4) << 2;
@@ -413,38 +441,47 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
         dst[i] = src[i];
 }
 
-template <int FPL, int NS, int DEPTH, bool NT, bool WIDE, bool COOP>
-void launch_one(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
+template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL>
+void launch_one(const ExecParams& p, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
-    dim3 grid(blocks, n_slab_launches), block(kWavesPerBlock * 64);
-    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, NT, WIDE, COOP>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
-                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N);
+    dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, WIDE, COOP, TAIL>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
+                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N,
+                       p.streaming_stores);
 }
 
-template <int FPL, int NS, int DEPTH, bool NT>
-void launch_nt(const ExecParams& p, int n_slab_launches, hipStream_t stream) {
+template <int FPL, int NS, int DEPTH, bool TAIL>
+void launch_depth(const ExecParams& p, hipStream_t stream) {
     if (p.wide) {
-        if (p.coop) launch_one<FPL, NS, DEPTH, NT, true, true>(p, n_slab_launches, stream);
-        else launch_one<FPL, NS, DEPTH, NT, true, false>(p, n_slab_launches, stream);
+        if (p.coop) launch_one<FPL, NS, DEPTH, true, true, TAIL>(p, stream);
+        else launch_one<FPL, NS, DEPTH, true, false, TAIL>(p, stream);
     } else {
-        if (p.coop) launch_one<FPL, NS, DEPTH, NT, false, true>(p, n_slab_launches, stream);
-        else launch_one<FPL, NS, DEPTH, NT, false, false>(p, n_slab_launches, stream);
+        if (p.coop) launch_one<FPL, NS, DEPTH, false, true, TAIL>(p, stream);
+        else launch_one<FPL, NS, DEPTH, false, false, TAIL>(p, stream);
     }
 }
 
-template <int FPL, int NS, int DEPTH>
-void launch_depth(const ExecParams& p, int n_slab_launches, bool plain_stores, hipStream_t stream) {
-    if (plain_stores) launch_nt<FPL, NS, DEPTH, false>(p, n_slab_launches, stream);
-    else launch_nt<FPL, NS, DEPTH, true>(p, n_slab_launches, stream);
+template <int FPL, int NS, bool TAIL>
+void launch_variant(const ExecParams& p, hipStream_t stream) {
+    switch (p.depth) {
+        case 0: launch_depth<FPL, NS, 0, TAIL>(p, stream); break;
+        case 1: launch_depth<FPL, NS, 1, TAIL>(p, stream); break;
+        case 3: launch_depth<FPL, NS, 3, TAIL>(p, stream); break;
+        default: launch_depth<FPL, NS, 2, TAIL>(p, stream); break;
+    }
 }
 
-template <int FPL, int NS>
-void launch_variant(const ExecParams& p, int n_slab_launches, int depth, bool plain_stores, hipStream_t stream) {
-    switch (depth) {
-        case 0: launch_depth<FPL, NS, 0>(p, n_slab_launches, plain_stores, stream); break;
-        case 1: launch_depth<FPL, NS, 1>(p, n_slab_launches, plain_stores, stream); break;
-        case 3: launch_depth<FPL, NS, 3>(p, n_slab_launches, plain_stores, stream); break;
-        default: launch_depth<FPL, NS, 2>(p, n_slab_launches, plain_stores, stream); break;
+// Without a tail only the slab shapes that a power-of-two or 128-multiple N produces exist.
+template <int FPL>
+void launch_shape(const ExecParams& p, hipStream_t stream) {
+    if (p.tail) {
+        if (p.ns == 2) launch_variant<FPL, 2, true>(p, stream);
+        else launch_variant<FPL, 1, true>(p, stream);
+    } else {
+        if constexpr (FPL == 8) {
+            if (p.ns == 2) { launch_variant<8, 2, false>(p, stream); return; }
+        }
+        launch_variant<FPL, 1, false>(p, stream);
     }
 }
 
@@ -466,9 +503,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     const DeviceFormat& f = plan.fmt;
     if (f.WH != 16 || f.TW != 16)
         fail(ACC_SPMM_ERR_UNSUPPORTED, "execute needs a plan with 16x16 tiles");
-    const bool small = (N == 16 || N == 32 || N == 64 || N == 128);
-    if (!(small || (N > 0 && N <= 512 && N % 128 == 0)))
-        fail(ACC_SPMM_ERR_UNSUPPORTED, "N must be 16, 32, 64, 128, 256, 384 or 512");
+    if (N <= 0 || N > kMaxN) fail(ACC_SPMM_ERR_UNSUPPORTED, "N must be between 1 and 65536");
     if ((reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
         fail(ACC_SPMM_ERR_INVALID_ARG, "B and C must be 16-byte aligned");
     if (f.M == 0) return;
@@ -496,24 +531,37 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.ws = plan.workspace.p;
     p.n_items = (int32_t)plan.items.size();
     p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-    // dense tiles: fetch the values cooperatively (see the file header); measured break-even is
-    // between 18 (power-law inputs, per-lane wins) and 35 (block / stencil inputs) entries per tile
-    p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && plan.stats.mean_nnz_per_tile >= 24.0);
+    // Cooperative value fetch (see the file header) where it measured faster: dense tiles at any
+    // N (break-even between 18 entries per tile, power-law inputs, and 35, block / stencil
+    // inputs), and N of 32 or 64 at any density once there are enough tiles to be bound by
+    // throughput rather than by the latency of one wave's chain of tiles.
+    const bool dense_tiles = plan.stats.mean_nnz_per_tile >= 24.0;
+    const bool narrow_rows = N >= 32 && N <= 64 && plan.stats.num_tiles >= 16384;
+    p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && (dense_tiles || narrow_rows));
     p.N = N;
     p.wide = plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32);
-    const int default_depth = N == 128 ? 3 : (N >= 256 ? 2 : 1);
-    const int np = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
-    const bool ps = plan.opt.streaming_stores == 0;
+    // Shape of the launch: FPL features per lane (a divisor of N, so that vector loads stay
+    // aligned and no lane straddles N, and no wider than N needs), 16*FPL features per slab,
+    // one or two slabs per wave, the rest of N over gridDim.y.
+    const int fpl_fit = N > 64 ? 8 : (N > 32 ? 4 : (N > 16 ? 2 : 1));
+    const int fpl_div = (N % 8 == 0) ? 8 : ((N % 4 == 0) ? 4 : ((N % 2 == 0) ? 2 : 1));
+    p.fpl = std::min(fpl_fit, fpl_div);
+    const int slab_width = 16 * p.fpl;
+    const int slabs = (N + slab_width - 1) / slab_width;
+    p.ns = (slabs % 2 == 0 || slabs > 3) ? 2 : 1;
+    p.grid_y = (slabs + p.ns - 1) / p.ns;
+    p.tail = (int64_t)p.grid_y * p.ns * slab_width != N;
+    if (!p.tail && p.ns == 2 && p.fpl != 8) p.tail = true;  // shape compiled only in its general form
+    const int default_depth = (p.fpl == 8 && p.ns == 1) ? 3 : (p.fpl == 8 ? 2 : 1);
+    p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
+    p.streaming_stores = plan.opt.streaming_stores != 0;
     if (timed) ACC_HIP(hipEventRecord(ev[0], stream));
     if (p.n_items > 0) {
-        switch (N) {
-            case 16: launch_variant<1, 1>(p, 1, np, ps, stream); break;
-            case 32: launch_variant<2, 1>(p, 1, np, ps, stream); break;
-            case 64: launch_variant<4, 1>(p, 1, np, ps, stream); break;
-            case 128: launch_variant<8, 1>(p, 1, np, ps, stream); break;
-            case 256: launch_variant<8, 2>(p, 1, np, ps, stream); break;
-            case 384: launch_variant<8, 1>(p, 3, np, ps, stream); break;
-            case 512: launch_variant<8, 2>(p, 2, np, ps, stream); break;
+        switch (p.fpl) {
+            case 1: launch_shape<1>(p, stream); break;
+            case 2: launch_shape<2>(p, stream); break;
+            case 4: launch_shape<4>(p, stream); break;
+            default: launch_shape<8>(p, stream); break;
         }
         ACC_HIP(hipGetLastError());
     }

@@ -27,11 +27,15 @@ def _need_gpu():
 def run_spmm(plan, B_u16, M, N, naive=False):
     dev = torch.device("cuda:0")
     Bd = torch.from_numpy(B_u16.view(np.int16)).to(dev)
-    # poison C: every element must be overwritten
-    C = torch.full((max(M, 1), N), float("nan"), dtype=torch.float32, device=dev)
+    # poison C: every element must be overwritten; nothing behind its last row may be
+    rows, guard = max(M, 1), 4096
+    buf = torch.full((rows * N + guard,), float("nan"), dtype=torch.float32, device=dev)
+    buf[rows * N:] = 12345.0
+    C = buf[:rows * N].view(rows, N)
     stream = torch.cuda.current_stream().cuda_stream
     (acc.acc_spmm_execute_csr_naive if naive else acc.acc_spmm_execute)(plan, Bd, N, C, stream)
     torch.cuda.synchronize()
+    assert bool((buf[rows * N:] == 12345.0).all()), "wrote past the end of C"
     return C[:M].cpu().numpy()
 
 
@@ -85,7 +89,11 @@ def test_workloads_small_full_comparison(cfg, shrink, mode):
         acc.acc_spmm_destroy(plan)
 
 
-@pytest.mark.parametrize("N", [16, 32, 64, 128, 256, 384, 512])
+# powers of two and multiples of 128 fill whole feature slabs; the others exercise the masked
+# tail with every lane width (N odd, N = 2, 4, 8 mod 16), one and two slabs per wave, and
+# several waves per item
+@pytest.mark.parametrize("N", [16, 32, 64, 128, 256, 384, 512, 1024,
+                               1, 7, 17, 2, 30, 602, 4, 36, 100, 500, 8, 24, 40, 48, 96, 136, 200, 640])
 @pytest.mark.parametrize("lb", [acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON])
 def test_all_widths_with_and_without_load_balancing(N, lb):
     rng = np.random.default_rng(N + lb)
@@ -114,7 +122,7 @@ def test_all_widths_with_and_without_load_balancing(N, lb):
         acc.acc_spmm_destroy(plan)
 
 
-@pytest.mark.parametrize("N", [32, 128, 256])
+@pytest.mark.parametrize("N", [32, 128, 256, 36, 200])
 def test_every_kernel_variant(N):
     """All pipeline depths (0 = no prefetch), both store policies and both ways of fetching
     the packed values give the same, correct C."""
@@ -317,9 +325,10 @@ def test_execute_argument_errors():
     try:
         B = torch.zeros(1, 48, dtype=torch.float16, device="cuda")
         C = torch.zeros(1, 48, device="cuda")
-        with pytest.raises(acc.AccSpmmError) as e:
-            acc.acc_spmm_execute(plan, B, 48, C, None)
-        assert e.value.code == -3
+        for bad_N in (0, -16, 65537):
+            with pytest.raises(acc.AccSpmmError) as e:
+                acc.acc_spmm_execute(plan, B, bad_N, C, None)
+            assert e.value.code == -3
         with pytest.raises(acc.AccSpmmError) as e:
             acc.acc_spmm_execute(plan, B, 32, None, None)
         assert e.value.code == -1

@@ -43,6 +43,9 @@ typedef struct acc_spmm_plan_s acc_spmm_plan_t;
 /* Values for acc_spmm_options.reorder and .load_balance */
 enum { ACC_SPMM_OFF = 0, ACC_SPMM_ON = 1, ACC_SPMM_AUTO = 2 };
 
+/* acc_spmm_options.value_type */
+enum { ACC_SPMM_FP16 = 0, ACC_SPMM_BF16 = 1 };
+
 /*
  * Plan options.  Zero-initialise, set struct_size = sizeof(acc_spmm_options), then
  * change what you need; a field left 0 takes its default where "0 = default" is stated.
@@ -93,6 +96,10 @@ typedef struct {
      * exchange them across registers; 0 = default: 2 when the plan has at least 24 entries
      * per tile on average, or when N is 32 or 64 and the plan has at least 16384 tiles; else 1. */
     int32_t value_fetch;
+    /* The 16-bit floating-point type of csr_vals and of B: ACC_SPMM_FP16 (0, default) = IEEE
+     * binary16, ACC_SPMM_BF16 (1) = bfloat16.  C is fp32 and products are accumulated in fp32
+     * either way. */
+    int32_t value_type;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */

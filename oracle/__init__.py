@@ -36,8 +36,12 @@ def _load():
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
         L.orc_f16_to_f64.restype = ctypes.c_double
         L.orc_f16_to_f64.argtypes = [ctypes.c_uint16]
+        L.orc_bf16_to_f64.restype = ctypes.c_double
+        L.orc_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.orc_spmm_rows.restype = None
         L.orc_spmm_rows.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp]
+        L.orc_spmm_rows_typed.restype = None
+        L.orc_spmm_rows_typed.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp, ctypes.c_int]
         L.orc_encode.restype = i64
         L.orc_encode.argtypes = [i64, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp]
         L.orc_decode.restype = None
@@ -64,8 +68,9 @@ def _u16(a):
     return np.ascontiguousarray(a, dtype=np.uint16)
 
 
-def spmm(rowptr, colidx, vals, B, rows=None, want_bound=True):
-    """fp64 C = A.B and bound = |A|.|B| for all rows, or for the given row indices."""
+def spmm(rowptr, colidx, vals, B, rows=None, want_bound=True, value_type="f16"):
+    """fp64 C = A.B and bound = |A|.|B| for all rows, or for the given row indices.
+    `vals` and `B` are 16-bit patterns of `value_type` ("f16" = IEEE binary16, "bf16")."""
     rowptr, colidx, vals, B = _i32(rowptr), _i32(colidx), _u16(vals), _u16(B)
     N = B.shape[1]
     if rows is None:
@@ -75,7 +80,8 @@ def spmm(rowptr, colidx, vals, B, rows=None, want_bound=True):
         n, rp = len(rows), rows.ctypes.data
     C = np.empty((n, N), np.float64)
     bound = np.empty((n, N), np.float64) if want_bound else None
-    _load().orc_spmm_rows(n, rp, N, _p(rowptr), _p(colidx), _p(vals), _p(B), _p(C), _p(bound))
+    _load().orc_spmm_rows_typed(n, rp, N, _p(rowptr), _p(colidx), _p(vals), _p(B), _p(C), _p(bound),
+                                {"f16": 0, "bf16": 1}[value_type])
     return C, bound
 
 

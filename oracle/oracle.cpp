@@ -51,19 +51,36 @@ inline double h2d(uint16_t h) {
     return s ? -v : v;
 }
 
+// bfloat16 bit pattern -> double (exact): sign, 8 exponent bits (bias 127), 7 fraction bits,
+// i.e. the upper half of an IEEE binary32.
+inline double bf2d(uint16_t h) {
+    int s = h >> 15, e = (h >> 7) & 255, f = h & 127;
+    double v;
+    if (e == 0) v = std::ldexp((double)f, -133);            // subnormal: f * 2^-7 * 2^-126
+    else if (e == 255) v = f ? NAN : INFINITY;
+    else v = std::ldexp((double)(f + 128), e - 134);        // (1 + f/128) * 2^(e-127)
+    return s ? -v : v;
+}
+
+// value_type: 0 = IEEE binary16, 1 = bfloat16
+inline double widen(uint16_t h, int value_type) { return value_type == 1 ? bf2d(h) : h2d(h); }
+
 }  // namespace
 
 extern "C" {
 
 double orc_f16_to_f64(uint16_t h) { return h2d(h); }
+double orc_bf16_to_f64(uint16_t h) { return bf2d(h); }
 
 // C[i][j] = sum_p A.val[p] * B[A.col[p]][j] over the stored entries p of row i, in fp64
 // (definition of SpMM).  bound[i][j] = sum_p |A.val[p]| * |B[A.col[p]][j]| (may be null).
 // `rows` selects which rows to compute (null = rows 0..nrows-1); output row r of C/bound
 // corresponds to rows[r].
-void orc_spmm_rows(int64_t nrows, const int64_t* rows, int64_t N, const int32_t* rowptr,
-                   const int32_t* colidx, const uint16_t* vals, const uint16_t* B, double* C,
-                   double* bound) {
+// `value_type` names the 16-bit type of vals and B (0 = binary16, the type of the benchmark
+// workloads; 1 = bfloat16).
+void orc_spmm_rows_typed(int64_t nrows, const int64_t* rows, int64_t N, const int32_t* rowptr,
+                         const int32_t* colidx, const uint16_t* vals, const uint16_t* B, double* C,
+                         double* bound, int value_type) {
 #pragma omp parallel for schedule(dynamic, 256)
     for (int64_t r = 0; r < nrows; ++r) {
         int64_t i = rows ? rows[r] : r;
@@ -72,15 +89,21 @@ void orc_spmm_rows(int64_t nrows, const int64_t* rows, int64_t N, const int32_t*
         for (int64_t j = 0; j < N; ++j) c[j] = 0.0;
         if (bd) for (int64_t j = 0; j < N; ++j) bd[j] = 0.0;
         for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
-            double a = h2d(vals[p]);
+            double a = widen(vals[p], value_type);
             const uint16_t* brow = B + (int64_t)colidx[p] * N;
             for (int64_t j = 0; j < N; ++j) {
-                double b = h2d(brow[j]);
+                double b = widen(brow[j], value_type);
                 c[j] += a * b;
                 if (bd) bd[j] += std::fabs(a) * std::fabs(b);
             }
         }
     }
+}
+
+void orc_spmm_rows(int64_t nrows, const int64_t* rows, int64_t N, const int32_t* rowptr,
+                   const int32_t* colidx, const uint16_t* vals, const uint16_t* B, double* C,
+                   double* bound) {
+    orc_spmm_rows_typed(nrows, rows, N, rowptr, colidx, vals, B, C, bound, 0);
 }
 
 void orc_spmm(int64_t M, int64_t N, const int32_t* rowptr, const int32_t* colidx, const uint16_t* vals,

@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libaccspmm.so")
 _lib = None
 
 ACC_SPMM_OFF, ACC_SPMM_ON, ACC_SPMM_AUTO = 0, 1, 2
+ACC_SPMM_FP16, ACC_SPMM_BF16 = 0, 1
 
 (ACC_SPMM_ARR_PERM, ACC_SPMM_ARR_IPERM, ACC_SPMM_ARR_ROW_WINDOW_OFFSET, ACC_SPMM_ARR_TC_OFFSET,
  ACC_SPMM_ARR_SPARSE_A_TO_B, ACC_SPMM_ARR_TC_LOCAL_BIT, ACC_SPMM_ARR_VALUES, ACC_SPMM_ARR_WORK_ITEMS,
@@ -44,6 +45,7 @@ class acc_spmm_options(ctypes.Structure):
         ("segment_length", ctypes.c_int32), ("ibd_threshold", ctypes.c_float), ("keep_csr", ctypes.c_int32),
         ("no_prefetch", ctypes.c_int32), ("streaming_stores", ctypes.c_int32), ("pipeline_depth", ctypes.c_int32),
         ("value_fetch", ctypes.c_int32),
+        ("value_type", ctypes.c_int32),
     ]
 
 

@@ -16,6 +16,8 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OUT = os.path.join(HERE, "libaccspmm.so")
 SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "encode.hip", "graph.hip", "ordering.hip", "execute.hip"]
+# tile_kernel.hip is compiled once per (features per lane, value type) into its own object
+TILE_VARIANTS = [(fpl, bf16) for bf16 in (0, 1) for fpl in (8, 4, 2, 1)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -38,17 +40,20 @@ def _stale(target: str, deps: list[str]) -> bool:
 def build(force: bool = False, verbose: bool = False) -> str:
     bdir = os.path.join(CSRC, "_build")
     os.makedirs(bdir, exist_ok=True)
-    headers = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device_util.h"), os.path.join(INCLUDE, "acc_spmm.h")]
-    jobs = []
-    for src in SOURCES:
-        s = os.path.join(CSRC, src)
-        o = os.path.join(bdir, src + ".o")
+    headers = [os.path.join(CSRC, h) for h in ("internal.h", "device_util.h", "execute.h")]
+    headers.append(os.path.join(INCLUDE, "acc_spmm.h"))
+    jobs, objs = [], []
+    units = [(os.path.join(CSRC, "tile_kernel.hip"), os.path.join(bdir, f"tile_kernel_f{fpl}_t{bf16}.o"),
+              [f"-DACC_TILE_FPL={fpl}", f"-DACC_TILE_BF16={bf16}"]) for fpl, bf16 in TILE_VARIANTS]
+    units += [(os.path.join(CSRC, src), os.path.join(bdir, src + ".o"), []) for src in SOURCES]
+    for s, o, defs in units:
+        objs.append(o)
         if force or _stale(o, [s] + headers):
-            jobs.append((s, o))
+            jobs.append((s, o, defs))
 
     def compile_one(job):
-        s, o = job
-        cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
+        s, o, defs = job
+        cmd = [HIPCC] + FLAGS + defs + ["-c", s, "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
@@ -56,11 +61,11 @@ def build(force: bool = False, verbose: bool = False) -> str:
             raise RuntimeError(f"hipcc failed on {s}:\n{r.stderr}")
         return r.stderr
 
-    with ThreadPoolExecutor(max_workers=min(4, max(1, len(jobs)))) as ex:
+    workers = min(8, os.cpu_count() or 4, max(1, len(jobs)))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
         for err in ex.map(compile_one, jobs):
             if verbose and err:
                 sys.stderr.write(err)
-    objs = [os.path.join(bdir, s + ".o") for s in SOURCES]
     if force or jobs or _stale(OUT, objs):
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -98,6 +98,8 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.ibd_threshold == 0.f) opt.ibd_threshold = kDefaultIbdThreshold;
     if (opt.pipeline_depth < 0 || opt.pipeline_depth > 3) fail(ACC_SPMM_ERR_INVALID_ARG, "pipeline_depth must be 0..3");
     if (opt.value_fetch < 0 || opt.value_fetch > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "value_fetch must be 0, 1 or 2");
+    if (opt.value_type != ACC_SPMM_FP16 && opt.value_type != ACC_SPMM_BF16)
+        fail(ACC_SPMM_ERR_INVALID_ARG, "value_type must be ACC_SPMM_FP16 or ACC_SPMM_BF16");
 
     std::vector<int32_t> fixed_col;
     std::vector<uint16_t> fixed_val;

@@ -1,0 +1,38 @@
+// Shared between the tile-kernel translation units and the execute dispatcher.
+#pragma once
+#include "internal.h"
+
+namespace accspmm {
+
+constexpr int kWavesPerBlock = 4;   // wavefronts (work items) per thread block of the tile kernel
+constexpr int kMaxN = 65536;
+
+struct ExecParams {
+    const int32_t* __restrict__ rwo;
+    const int32_t* __restrict__ tco;
+    const int32_t* __restrict__ a2b;
+    const uint64_t* __restrict__ bits;
+    const uint16_t* __restrict__ vals;
+    const int32_t* __restrict__ perm_pad;
+    const WorkItem* __restrict__ items;
+    const uint16_t* __restrict__ B;
+    float* __restrict__ C;
+    float* __restrict__ ws;
+    int32_t n_items;
+    int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
+    int32_t N;
+    bool wide;         // B needs 64-bit row offsets
+    bool coop;         // cooperative value fetch
+    bool tail;         // N is not a whole number of slabs
+    bool bf16;         // values are bfloat16
+    int32_t fpl, ns, grid_y, depth, streaming_stores;
+};
+
+// One function per (features per lane, value type); each lives in its own object file,
+// compiled from tile_kernel.hip with ACC_TILE_FPL and ACC_TILE_BF16 defined.
+#define ACC_DECLARE_TILE_LAUNCHER(FPL, T) void launch_tiles_f##FPL##_t##T(const ExecParams& p, hipStream_t stream);
+ACC_DECLARE_TILE_LAUNCHER(1, 0) ACC_DECLARE_TILE_LAUNCHER(2, 0) ACC_DECLARE_TILE_LAUNCHER(4, 0) ACC_DECLARE_TILE_LAUNCHER(8, 0)
+ACC_DECLARE_TILE_LAUNCHER(1, 1) ACC_DECLARE_TILE_LAUNCHER(2, 1) ACC_DECLARE_TILE_LAUNCHER(4, 1) ACC_DECLARE_TILE_LAUNCHER(8, 1)
+#undef ACC_DECLARE_TILE_LAUNCHER
+
+}  // namespace accspmm

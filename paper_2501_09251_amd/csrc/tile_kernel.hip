@@ -1,0 +1,431 @@
+// Runtime kernels: C = A.B from the bitmap tile format (paper Section 3.4, Algorithm 2,
+// re-designed for gfx950).
+//
+// One wavefront owns one work item: a run of whole row windows, or a slice of the tiles of
+// one heavy window (Section 3.5).  For every 16x16 tile the wavefront
+//   - reads the tile's 16 SparseAToB entries and gathers those 16 rows of B straight into
+//     registers (as in the paper's Fig. 5, B goes global -> registers): each 16-lane group
+//     reads four whole rows with 16-byte loads per lane,
+//   - decodes its own four positions of the tile from the bitmap (popcount of the lower
+//     bits gives the value offset, Section 3.3) and reads up to four packed values,
+//   - issues v_mfma_f32_16x16x16_f16 with the sparse tile as the 16x16 left operand and
+//     sixteen feature columns of the gathered rows as the right operand.
+// Lane c of a group owns features [FPL*c, FPL*c+FPL) of a 16*FPL-wide slab, so a feature's
+// position inside an MFMA is a free choice and no transpose through LDS is needed: the
+// four k-values of one feature come from four registers and are packed with v_perm_b32.
+//
+// The packed values of a tile reach the lanes in one of two ways (template COOP).  Per-lane:
+// each lane reads its up-to-four values itself (four 2-byte loads).  Cooperative: the wave
+// reads the tile's contiguous values once, one dword per lane, and every lane then picks its
+// values out of the other lanes' registers with ds_bpermute.  The second way issues a
+// quarter of the memory instructions and wins when tiles are dense; the first wins on the
+// sparse tiles of power-law inputs.  The plan's mean entries per tile selects the way.
+//
+// Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
+// values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
+// words of tile t+DEPTH+1 are requested one step before they are needed for addresses.
+//
+// This file is compiled once per (features per lane, value type): ACC_TILE_FPL in {1, 2, 4, 8}
+// and ACC_TILE_BF16 in {0, 1} come from the command line, so that the many instantiations
+// build in parallel.
+#include "execute.h"
+
+#if !defined(ACC_TILE_FPL) || !defined(ACC_TILE_BF16)
+#error "compile with -DACC_TILE_FPL=<1|2|4|8> -DACC_TILE_BF16=<0|1>"
+#endif
+
+namespace accspmm {
+namespace {
+
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef int32_t intx4 __attribute__((ext_vector_type(4)));
+
+template <int FPL>
+struct Chunk {  // FPL consecutive fp16 features of one B row, as dwords
+    static constexpr int DW = (FPL + 1) / 2;
+    uint32_t d[DW];
+};
+
+template <int FPL>
+__device__ __forceinline__ void load_chunk(const uint16_t* p, Chunk<FPL>& c) {
+    if constexpr (FPL == 8) {
+        uintx4 v = *reinterpret_cast<const uintx4*>(p);
+        c.d[0] = v.x; c.d[1] = v.y; c.d[2] = v.z; c.d[3] = v.w;
+    } else if constexpr (FPL == 4) {
+        uintx2 v = *reinterpret_cast<const uintx2*>(p);
+        c.d[0] = v.x; c.d[1] = v.y;
+    } else if constexpr (FPL == 2) {
+        c.d[0] = *reinterpret_cast<const uint32_t*>(p);
+    } else {
+        c.d[0] = *p;
+    }
+}
+
+struct TileMeta {       // index words of one tile
+    intx4 cols;         // this lane group's four SparseAToB entries
+    uint64_t bm[4];     // TCLocalBit (wave-uniform)
+    int32_t tco;        // TCOffset (wave-uniform)
+};
+
+template <int FPL, int NS>
+struct TileData {       // what the multiply needs
+    Chunk<FPL> b[NS][4];
+    // per-lane fetch: v[0..3] = up to four packed values (fp16 bits).
+    // cooperative fetch: v[0..2] = the tile's packed values, chunk k's dword L in lane L;
+    //                    v[3] = index of this lane's first value relative to the first loaded half
+    uint32_t v[4];
+    uint32_t nib;       // this lane's four bitmap bits
+    uint32_t nchunk;    // cooperative fetch: 64-dword chunks that hold values (wave-uniform)
+};
+
+// The index arrays are passed as separate const __restrict__ kernel arguments (not inside a
+// struct) so that the compiler knows they are read-only and wave-uniform accesses to them
+// become scalar loads.
+// WIDE = false: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
+// with one 24-bit multiply in 32 bits and added to the uniform base by the load itself.
+// TAIL = true: N is not a whole number of this kernel's feature slabs (16*FPL features per slab,
+// NS slabs per wave, gridDim.y waves per item); lanes whose features lie at or beyond N neither
+// load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
+// BF16 = true: the 16-bit values of A and B are bfloat16 instead of IEEE half; only the MFMA
+// instruction differs, the data movement is the same.
+template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL, bool BF16>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
+    const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
+    const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
+    const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, float* __restrict__ g_C,
+    float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg, int32_t streaming_stores) {
+    constexpr int R = DEPTH + 1;
+    constexpr int SW = 16 * FPL;  // features per slab
+    struct {
+        const int32_t* __restrict__ rwo; const int32_t* __restrict__ tco; const int32_t* __restrict__ a2b;
+        const uint64_t* __restrict__ bits; const uint16_t* __restrict__ vals; const int32_t* __restrict__ perm_pad;
+        const WorkItem* __restrict__ items; const uint16_t* __restrict__ B; float* __restrict__ C; float* __restrict__ ws;
+        int32_t n_items, n_blocks, N;
+    } p{g_rwo, g_tco, g_a2b, g_bits, g_vals, g_perm_pad, g_items, g_B, g_C, g_ws, n_items, n_blocks, N_arg};
+    const int lane = threadIdx.x & 63;
+    const int g = lane >> 4, c = lane & 15;
+    // Consecutive blocks go to different XCDs (round-robin over 8); give each XCD one
+    // contiguous eighth of the items so that neighbouring windows share an L2.
+    const int per_xcd = (p.n_blocks + 7) >> 3;
+    const int lblock = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (lblock >= p.n_blocks) return;
+    const int item_id = __builtin_amdgcn_readfirstlane(lblock * kWavesPerBlock + (int)(threadIdx.x >> 6));
+    if (item_id >= p.n_items) return;
+    const WorkItem it = p.items[item_id];
+    const int w_begin = __builtin_amdgcn_readfirstlane(it.w_begin);
+    const int w_end_raw = __builtin_amdgcn_readfirstlane(it.w_end);
+    const int tb = __builtin_amdgcn_readfirstlane(it.t_begin);
+    const int te = __builtin_amdgcn_readfirstlane(it.t_end);
+    const bool partial = w_end_raw < 0;
+    const int w_end = partial ? w_begin + 1 : w_end_raw;
+    const int N = p.N;
+    const int f0 = (int)(blockIdx.y * NS) * SW + c * FPL;  // this lane's first feature in slab 0 of this wave
+    bool act[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) act[s] = !TAIL || (f0 + s * SW < N);
+    const bool nt = streaming_stores != 0;
+
+    // lane constants of the bitmap decode: bit index of (row c, k 4g) is c*16 + 4g
+    const int wq = c >> 2;
+    const int sh = ((c & 3) << 4) | (g << 2);
+    const uint64_t below_mask = (1ull << sh) - 1ull;
+    const bool w1 = wq >= 1, w2 = wq >= 2, w3 = wq >= 3;
+
+    floatx4 acc[NS][FPL];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // Rows of C owned by this lane for the window being accumulated (requested when the window
+    // starts, so that closing the window does not wait on a fresh load).
+    intx4 rows_cur = intx4{4 * g, 4 * g + 1, 4 * g + 2, 4 * g + 3};
+    auto load_rows = [&](int w) __attribute__((always_inline)) {
+        rows_cur = *reinterpret_cast<const intx4*>(p.perm_pad + (size_t)w * 16 + 4 * g);
+    };
+    float* const out_base = partial ? p.ws + (size_t)(-w_end_raw - 1) * 16 * (size_t)N : p.C;
+
+    auto flush = [&]() __attribute__((always_inline)) {  // store the accumulators to rows_cur and clear them
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = rows_cur[r];
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (row < 0 || !act[s]) continue;
+                float* dst = out_base + (size_t)row * (size_t)N + f0 + s * SW;
+                if constexpr (FPL >= 4) {
+#pragma unroll
+                    for (int m = 0; m < FPL; m += 4) {
+                        floatx4 v{acc[s][m][r], acc[s][m + 1][r], acc[s][m + 2][r], acc[s][m + 3][r]};
+                        if (nt) __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(dst + m));
+                        else *reinterpret_cast<floatx4*>(dst + m) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int m = 0; m < FPL; ++m) {
+                        if (nt) __builtin_nontemporal_store(acc[s][m][r], dst + m);
+                        else dst[m] = acc[s][m][r];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
+    };
+
+    auto load_meta = [&](int t, TileMeta& m) __attribute__((always_inline)) {
+        t = t < te ? t : te - 1;  // past the end: re-read the last tile (always in bounds)
+        m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 16 + 4 * g);
+        const uint64_t* bm = p.bits + (size_t)t * 4;
+        m.bm[0] = bm[0]; m.bm[1] = bm[1]; m.bm[2] = bm[2]; m.bm[3] = bm[3];
+        m.tco = p.tco[t];
+    };
+
+    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint16_t* row;
+            if constexpr (WIDE) {
+                row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
+            } else {
+                const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
+                row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
+            }
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if constexpr (TAIL) {
+#pragma unroll
+                    for (int k = 0; k < Chunk<FPL>::DW; ++k) d.b[s][q].d[k] = 0;
+                    if (act[s]) load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                } else {
+                    load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                }
+            }
+        }
+        // this lane's bitmap word and the popcount of the words below it, by plain selects
+        const int c0 = __builtin_popcountll(m.bm[0]), c1 = __builtin_popcountll(m.bm[1]),
+                  c2 = __builtin_popcountll(m.bm[2]);
+        uint64_t word = m.bm[0];
+        word = w1 ? m.bm[1] : word;
+        word = w2 ? m.bm[2] : word;
+        word = w3 ? m.bm[3] : word;
+        const int pre = (w1 ? c0 : 0) + (w2 ? c1 : 0) + (w3 ? c2 : 0);
+        const uint32_t nib = (uint32_t)(word >> sh) & 15u;
+        const uint32_t i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
+        if constexpr (COOP) {
+            const uint32_t cnt = (uint32_t)(c0 + c1 + c2 + __builtin_popcountll(m.bm[3]));
+            const uint32_t first_half = (uint32_t)m.tco & ~1u;        // first loaded value (dword aligned)
+            const uint32_t span = ((uint32_t)m.tco & 1u) + cnt;       // halves from there to the tile's end
+            const uint32_t nchunk = (span + 127u) >> 7;               // 0..3
+            const uint32_t* v32 = reinterpret_cast<const uint32_t*>(p.vals) + (first_half >> 1);
+            d.v[0] = 0; d.v[1] = 0; d.v[2] = 0;
+            // only the lanes whose dword holds values of this tile read (so nothing is read past the tile)
+            if ((uint32_t)lane * 2u < span) d.v[0] = v32[lane];
+            if (nchunk > 1 && (uint32_t)(64 + lane) * 2u < span) d.v[1] = v32[64 + lane];
+            if (nchunk > 2 && (uint32_t)(128 + lane) * 2u < span) d.v[2] = v32[128 + lane];
+            d.v[3] = i0 - first_half;
+            d.nchunk = nchunk;
+        } else {
+            const uint32_t i1 = i0 + (nib & 1u);
+            const uint32_t i2 = i1 + ((nib >> 1) & 1u);
+            const uint32_t i3 = i2 + ((nib >> 2) & 1u);
+            const char* vb = reinterpret_cast<const char*>(p.vals);
+            d.v[0] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i0 << 1));
+            d.v[1] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i1 << 1));
+            d.v[2] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i2 << 1));
+            d.v[3] = *reinterpret_cast<const uint16_t*>(vb + (size_t)(uint32_t)(i3 << 1));
+            d.nchunk = 0;
+        }
+        d.nib = nib;
+    };
+
+    // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
+    auto operand_a = [&](const TileData<FPL, NS>& d) __attribute__((always_inline)) -> uintx2 {
+        const uint32_t nib = d.nib;
+        uint32_t h[4];
+        if constexpr (COOP) {
+            uint32_t r[4];
+            r[0] = d.v[3];
+            r[1] = r[0] + (nib & 1u);
+            r[2] = r[1] + ((nib >> 1) & 1u);
+            r[3] = r[2] + ((nib >> 2) & 1u);
+            const int nchunk = __builtin_amdgcn_readfirstlane((int)d.nchunk);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int addr = (int)((r[q] >> 1) << 2);  // source lane * 4; the hardware uses it modulo 64 lanes
+                uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[0]);
+                if (nchunk > 1) {
+                    const uint32_t x1 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[1]);
+                    x = ((r[q] >> 7) == 1u) ? x1 : x;
+                }
+                if (nchunk > 2) {
+                    const uint32_t x2 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[2]);
+                    x = ((r[q] >> 7) == 2u) ? x2 : x;
+                }
+                h[q] = (r[q] & 1u) ? (x >> 16) : (x & 0xFFFFu);
+            }
+        } else {
+            h[0] = d.v[0]; h[1] = d.v[1]; h[2] = d.v[2]; h[3] = d.v[3];
+        }
+        const uint32_t a0 = (nib & 1u) ? h[0] : 0u;
+        const uint32_t a1 = (nib & 2u) ? h[1] : 0u;
+        const uint32_t a2 = (nib & 4u) ? h[2] : 0u;
+        const uint32_t a3 = (nib & 8u) ? h[3] : 0u;
+        return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
+    };
+
+    auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int m = 0; m < FPL; ++m) {
+                const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
+                const uintx2 bu{__builtin_amdgcn_perm(d.b[s][1].d[m >> 1], d.b[s][0].d[m >> 1], sel),
+                                __builtin_amdgcn_perm(d.b[s][3].d[m >> 1], d.b[s][2].d[m >> 1], sel)};
+                if constexpr (BF16)
+                    acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, au),
+                                                                          __builtin_bit_cast(shortx4, bu), acc[s][m], 0, 0, 0);
+                else
+                    acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, au),
+                                                                      __builtin_bit_cast(half4, bu), acc[s][m], 0, 0, 0);
+            }
+    };
+
+    // window bookkeeping (all wave-uniform): w is the window being accumulated, wend its
+    // one-past-last tile, wend_next that of window w+1 (requested one window ahead)
+    int w = w_begin;
+    int wend = partial ? te : p.rwo[w + 1];
+    int wend_next = partial ? te : p.rwo[(w + 2 < w_end) ? w + 2 : w_end];
+    auto next_window = [&]() __attribute__((always_inline)) {
+        ++w;
+        wend = wend_next;
+        if (w < w_end) {
+            load_rows(w);
+            wend_next = p.rwo[(w + 2 < w_end) ? w + 2 : w_end];
+        }
+    };
+    if (!partial) {
+        load_rows(w);
+        while (w < w_end && wend == tb) {  // leading empty windows: rows of zeros
+            flush();
+            next_window();
+        }
+    }
+    if (tb >= te) return;
+
+    auto after_tile = [&](int tt) __attribute__((always_inline)) {  // tile tt has been multiplied: close the window(s) ending there
+        if (__builtin_expect(tt + 1 != wend, 1)) return;
+        flush();
+        if (partial) return;
+        next_window();
+        while (w < w_end && wend == tt + 1) {  // empty windows inside the run
+            flush();
+            next_window();
+        }
+    };
+
+    if constexpr (DEPTH == 0) {
+        // ablation: every tile's loads are issued only when the tile is computed
+        TileMeta m;
+        TileData<FPL, NS> d;
+        for (int tt = tb; tt < te; ++tt) {
+            load_meta(tt, m);
+            issue(m, d);
+            multiply(d, operand_a(d));
+            after_tile(tt);
+        }
+    } else {
+        // Ring of R = DEPTH+1 buffers; tile x uses slot (x - tb) % R.  vmcnt retires loads in
+        // issue order, so the index words of tile tt+DEPTH+1 are requested *before* the data
+        // of tile tt+DEPTH: waiting for index words then never drains the data behind them,
+        // and DEPTH tiles of B rows stay in flight while tile tt is multiplied.
+        TileMeta meta[R];
+        TileData<FPL, NS> data[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_meta(tb + r, meta[r]);
+#pragma unroll
+        for (int r = 0; r < DEPTH; ++r) issue(meta[r], data[r]);
+        for (int t = tb; t < te; t += R) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int tt = t + r;
+                if (tt >= te) break;
+                // tile tt's sparse operand first: its cross-lane fetch (if any) shares a wait counter
+                // with the scalar index loads issued next
+                const uintx2 au = operand_a(data[r]);
+                if constexpr (COOP) __builtin_amdgcn_sched_barrier(0);
+                TileMeta next_meta;
+                load_meta(tt + DEPTH + 1, next_meta);                     // slot r, free since tile tt was issued
+                issue(meta[(r + DEPTH) % R], data[(r + DEPTH) % R]);     // tile tt+DEPTH
+                meta[r] = next_meta;
+                multiply(data[r], au);
+                after_tile(tt);
+            }
+        }
+    }
+}
+
+template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL, bool BF16>
+void launch_one(const ExecParams& p, hipStream_t stream) {
+    const int blocks = ((p.n_blocks + 7) / 8) * 8;
+    dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, WIDE, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
+                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N,
+                       p.streaming_stores);
+}
+
+template <int FPL, int NS, int DEPTH, bool TAIL, bool BF16>
+void launch_type(const ExecParams& p, hipStream_t stream) {
+    if (p.wide) {
+        if (p.coop) launch_one<FPL, NS, DEPTH, true, true, TAIL, BF16>(p, stream);
+        else launch_one<FPL, NS, DEPTH, true, false, TAIL, BF16>(p, stream);
+    } else {
+        if (p.coop) launch_one<FPL, NS, DEPTH, false, true, TAIL, BF16>(p, stream);
+        else launch_one<FPL, NS, DEPTH, false, false, TAIL, BF16>(p, stream);
+    }
+}
+
+template <int FPL, int NS, int DEPTH, bool TAIL>
+void launch_depth(const ExecParams& p, hipStream_t stream) {
+    launch_type<FPL, NS, DEPTH, TAIL, ACC_TILE_BF16 != 0>(p, stream);
+}
+
+template <int FPL, int NS, bool TAIL>
+void launch_variant(const ExecParams& p, hipStream_t stream) {
+    switch (p.depth) {
+        case 0: launch_depth<FPL, NS, 0, TAIL>(p, stream); break;
+        case 1: launch_depth<FPL, NS, 1, TAIL>(p, stream); break;
+        case 3: launch_depth<FPL, NS, 3, TAIL>(p, stream); break;
+        default: launch_depth<FPL, NS, 2, TAIL>(p, stream); break;
+    }
+}
+
+// Without a tail only the slab shapes that a power-of-two or 128-multiple N produces exist.
+template <int FPL>
+void launch_shape(const ExecParams& p, hipStream_t stream) {
+    if (p.tail) {
+        if (p.ns == 2) launch_variant<FPL, 2, true>(p, stream);
+        else launch_variant<FPL, 1, true>(p, stream);
+    } else {
+        if constexpr (FPL == 8) {
+            if (p.ns == 2) { launch_variant<8, 2, false>(p, stream); return; }
+        }
+        launch_variant<FPL, 1, false>(p, stream);
+    }
+}
+
+}  // namespace
+
+#define ACC_TILE_LAUNCHER_NAME2(FPL, T) launch_tiles_f##FPL##_t##T
+#define ACC_TILE_LAUNCHER_NAME(FPL, T) ACC_TILE_LAUNCHER_NAME2(FPL, T)
+void ACC_TILE_LAUNCHER_NAME(ACC_TILE_FPL, ACC_TILE_BF16)(const ExecParams& p, hipStream_t stream) {
+    launch_shape<ACC_TILE_FPL>(p, stream);
+}
+
+}  // namespace accspmm

@@ -53,3 +53,13 @@ def load_golden(name):
 
 def f16(a):
     return np.asarray(a, np.float16).view(np.uint16).copy()
+
+
+def bf16(a):
+    """float -> bfloat16 bit patterns, round to nearest even (finite inputs)."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
+def bf16_to_f64(bits):
+    return (np.asarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)

@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2501_09251_amd as acc
 import workloads as wl
-from _util import csr_from_rows, random_csr, f16
+from _util import csr_from_rows, random_csr, f16, bf16
 
 pytestmark = pytest.mark.gpu
 
@@ -39,8 +39,8 @@ def run_spmm(plan, B_u16, M, N, naive=False):
     return C[:M].cpu().numpy()
 
 
-def check_against_oracle(rowptr, colidx, vals, B, C, rows=None):
-    C_ref, bound = oracle.spmm(rowptr, colidx, vals, B, rows=rows)
+def check_against_oracle(rowptr, colidx, vals, B, C, rows=None, value_type="f16"):
+    C_ref, bound = oracle.spmm(rowptr, colidx, vals, B, rows=rows, value_type=value_type)
     got = C if rows is None else C[rows]
     ok, ratio = oracle.within_bound(got, C_ref, bound)
     assert ok, f"outside tolerance, worst error/limit = {ratio}"
@@ -164,6 +164,33 @@ def test_dense_tiles_at_odd_value_offsets(fetch, N):
         check_format(plan, rowptr, colidx, vals)
         C = run_spmm(plan, B, len(rows), N)
         check_against_oracle(rowptr, colidx, vals, B, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("N", [16, 64, 128, 256, 100, 7])
+@pytest.mark.parametrize("fetch", [1, 2])
+def test_bfloat16_values(N, fetch):
+    """value_type = bfloat16: same bits-in, fp32-out contract, wide-exponent inputs that binary16
+    could not hold, split windows, and the one-row-per-wave comparison kernel."""
+    rng = np.random.default_rng(1000 + N)
+    M, K = 333, 500
+    rowptr, colidx, _ = random_csr(rng, M, K, 0.04)
+    rows = [colidx[rowptr[i]:rowptr[i + 1]].tolist() for i in range(M)]
+    rows[40] = np.sort(rng.choice(K, 450, replace=False)).tolist()
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = bf16(rng.uniform(-1, 1, len(colidx)) * 10.0 ** rng.integers(-8, 9, len(colidx)))
+    B = bf16(rng.standard_normal((K, N)) * 1e6)
+    plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=8, keep_csr=1,
+                                                 value_type=acc.ACC_SPMM_BF16, value_fetch=fetch))
+    try:
+        C = run_spmm(plan, B, M, N)
+        check_against_oracle(rowptr, colidx, vals, B, C, value_type="bf16")
+        Cn = run_spmm(plan, B, M, N, naive=True)
+        check_against_oracle(rowptr, colidx, vals, B, Cn, value_type="bf16")
+        packed = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_VALUES)
+        assert sorted(packed.tolist()) == sorted(vals.tolist())          # bits pass through the encoder untouched
     finally:
         acc.acc_spmm_destroy(plan)
 

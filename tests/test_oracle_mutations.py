@@ -10,7 +10,7 @@ import sys
 import numpy as np
 import pytest
 
-from _util import csr_from_rows, csr_from_edges, random_csr, random_sym_csr, load_golden, f16
+from _util import csr_from_rows, csr_from_edges, random_csr, random_sym_csr, load_golden, f16, bf16, bf16_to_f64
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "oracle.cpp")
@@ -21,6 +21,9 @@ MUTATIONS = {
     "B row taken from the row index": ("B + (int64_t)colidx[p] * N;", "B + (int64_t)(i % 3) * N;"),
     "fp16 subnormal scale": ("std::ldexp((double)f, -24)", "std::ldexp((double)f, -25)"),
     "fp16 exponent bias": ("std::ldexp((double)(f + 1024), e - 25)", "std::ldexp((double)(f + 1024), e - 24)"),
+    "bf16 exponent bias": ("std::ldexp((double)(f + 128), e - 134)", "std::ldexp((double)(f + 128), e - 133)"),
+    "bf16 subnormal scale": ("std::ldexp((double)f, -133)", "std::ldexp((double)f, -134)"),
+    "bf16 read as fp16": ("return value_type == 1 ? bf2d(h) : h2d(h);", "return h2d(h);"),
     "padding repeats the first column": ("cols[std::min<int64_t>(t * TW + c, d - 1)]", "cols[(t * TW + c < d) ? t * TW + c : 0]"),
     "bit index transposed": ("int bit = (int)((r - r0) * TW + cc % TW);\n                    uint64_t& word",
                              "int bit = (int)((cc % TW) * WH + (r - r0));\n                    uint64_t& word"),
@@ -77,6 +80,15 @@ def _pins(orc, lit):
     C, bound = orc.spmm(rowptr, colidx, vals, Bf.view(np.uint16))
     np.testing.assert_allclose(C, A.astype(np.float64) @ Bf.astype(np.float64), atol=1e-13)
     np.testing.assert_allclose(bound, np.abs(A).astype(np.float64) @ np.abs(Bf).astype(np.float64), atol=1e-13)
+    # bfloat16: decode against the bits placed in the upper half of a binary32, SpMM against a dense matmul
+    bits = np.arange(0, 65536, 5, dtype=np.uint16)
+    got = np.array([orc._load().orc_bf16_to_f64(int(b)) for b in bits])
+    np.testing.assert_array_equal(got, bf16_to_f64(bits))
+    a_bits, b_bits = bf16(rng.uniform(-2, 2, mask.sum())), bf16(rng.uniform(-1, 1, (K, N)))
+    Ad = np.zeros((M, K))
+    Ad[mask] = bf16_to_f64(a_bits)
+    C, _ = orc.spmm(rowptr, colidx, a_bits, b_bits, value_type="bf16")
+    np.testing.assert_allclose(C, Ad @ bf16_to_f64(b_bits), atol=1e-13)
     # format: hand-worked example, closed form, literal transcription, round trip
     g = load_golden("format_8x8_toy.json")
     rowptr, colidx, vals = csr_from_rows(g["rows"])

@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 from oracle import literal
-from _util import csr_from_rows, random_csr, f16
+from _util import csr_from_rows, random_csr, f16, bf16, bf16_to_f64
 
 
 def test_f16_decode_matches_numpy_for_every_bit_pattern():
@@ -14,6 +14,49 @@ def test_f16_decode_matches_numpy_for_every_bit_pattern():
     lit = np.array([literal.f16_bits_to_float(int(b)) for b in bits[::3]])
     np.testing.assert_array_equal(mine, ref[::3])
     np.testing.assert_array_equal(lit, ref[::3])
+
+
+def test_bf16_decode_matches_torch_and_the_closed_form_for_every_bit_pattern():
+    import torch
+    from fractions import Fraction
+    bits = np.arange(65536, dtype=np.uint16)
+    mine = np.array([oracle._load().orc_bf16_to_f64(int(b)) for b in bits])
+    ref = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(mine, ref)                      # NaNs compare equal here
+    np.testing.assert_array_equal(mine, bf16_to_f64(bits))
+    for b in range(0, 65536, 97):                                 # (-1)^s 2^(e-127) (1 + f/128), exactly
+        s, e, f = b >> 15, (b >> 7) & 255, b & 127
+        if e == 255:
+            continue
+        v = Fraction(f, 128) * Fraction(2) ** -126 if e == 0 else (1 + Fraction(f, 128)) * Fraction(2) ** (e - 127)
+        assert Fraction(float(mine[b])) == (-v if s else v)
+
+
+def test_bf16_spmm_matches_numpy_matmul():
+    rng = np.random.default_rng(7)
+    M, K, N = 9, 14, 5
+    mask = rng.random((M, K)) < 0.4
+    a_bits = bf16(rng.uniform(-2, 2, mask.sum()))
+    rows = [np.nonzero(mask[i])[0].tolist() for i in range(M)]
+    rowptr, colidx, _ = csr_from_rows(rows)
+    A = np.zeros((M, K))
+    A[mask] = bf16_to_f64(a_bits)
+    b_bits = bf16(rng.uniform(-1, 1, (K, N)))
+    Bd = bf16_to_f64(b_bits)
+    C, bound = oracle.spmm(rowptr, colidx, a_bits, b_bits, value_type="bf16")
+    np.testing.assert_allclose(C, A @ Bd, atol=1e-13)
+    np.testing.assert_allclose(bound, np.abs(A) @ np.abs(Bd), atol=1e-13)
+    # the same bits read as binary16 are different numbers: the type switch is not a no-op
+    C16, _ = oracle.spmm(rowptr, colidx, a_bits, b_bits)
+    assert not np.allclose(C16, C)
+
+
+def test_bf16_rounding_helper_is_round_to_nearest_even():
+    import torch
+    x = np.random.default_rng(3).standard_normal(4096).astype(np.float32)
+    x[:4] = [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -9, -(1.0 + 2.0 ** -8)]   # ties and a non-tie
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    np.testing.assert_array_equal(bf16(x), ref)
 
 
 @pytest.mark.parametrize("seed", range(6))

@@ -53,6 +53,10 @@ def main() -> int:
     ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
     ap.add_argument("--no-prefetch", action="store_true")
     ap.add_argument("--streaming-stores", action="store_true")
+    ap.add_argument("--column-order", choices=("off", "on", "auto"), default="auto")
+    ap.add_argument("--b-in-plan-order", action="store_true",
+                    help="hand B over in the plan's column order (permuted once, outside the timed region) "
+                         "instead of letting every step gather it")
     ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2),
                     help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -86,7 +90,8 @@ def main() -> int:
     opt = acc.make_options(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
                            max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
                            no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores),
-                           value_fetch=args.value_fetch)
+                           value_fetch=args.value_fetch, column_order=mode[args.column_order],
+                           operand_order=int(args.b_in_plan_order))
     plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
     t_plan = time.time() - t0
     st = acc.acc_spmm_plan_stats(plan)
@@ -97,6 +102,10 @@ def main() -> int:
     B = torch.from_numpy(w.B.view(np.int16)).to(dev)
     C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
+    B_caller = B
+    if args.b_in_plan_order:
+        B = torch.empty_like(B_caller)
+        acc.acc_spmm_permute_rows(plan, B_caller, B, w.N * 2, 0, stream)
     torch.cuda.synchronize()
 
     if args.calibrate_copy:
@@ -120,11 +129,12 @@ def main() -> int:
     value = flops / t_step / 1e9
 
     # ---- per-kernel durations (HIP events on the launch stream), same launches
-    tiles_ms, combine_ms = [], []
+    tiles_ms, combine_ms, gather_ms = [], [], []
     for _ in range(args.steps):
-        a, b = acc.acc_spmm_execute_timed(plan, B, w.N, C, stream)
+        a, b, g = acc.acc_spmm_execute_timed(plan, B, w.N, C, stream)
         tiles_ms.append(a)
         combine_ms.append(b)
+        gather_ms.append(g)
     tiles_avg = float(np.mean(tiles_ms))
     alg_bytes = tr["a_bytes"] + tr["b_bytes"] + tr["c_bytes"]
     achieved = alg_bytes / (tiles_avg * 1e-3) / 1e9 if tiles_avg > 0 else 0.0
@@ -141,7 +151,7 @@ def main() -> int:
     # ---- naive GPU baseline
     naive = None
     if not args.no_naive:
-        acc.acc_spmm_execute_csr_naive(plan, B, w.N, C, stream)
+        acc.acc_spmm_execute_csr_naive(plan, B, w.N, C, stream)   # reads B as execute is given it
         torch.cuda.synchronize()
         reps = 3
         t0 = time.perf_counter()
@@ -177,12 +187,14 @@ def main() -> int:
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
-                   "reorder": args.reorder, "load_balance": args.load_balance},
+                   "reorder": args.reorder, "load_balance": args.load_balance, "column_order": args.column_order,
+                   "B_order": "plan" if args.b_in_plan_order else "caller"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name) if args.reorder == "auto" and args.load_balance == "auto" else None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)
+                     if (args.reorder, args.load_balance, args.column_order) == ("auto", "auto", "auto") else None,
                      "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
-                     "combine_ms_avg": float(np.mean(combine_ms)),
+                     "combine_ms_avg": float(np.mean(combine_ms)), "gather_B_ms_avg": float(np.mean(gather_ms)),
                      "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"],
                      "c_bytes": tr["c_bytes"], "b_bytes_upper_nnzN2": 2 * w.nnz * w.N, "b_bytes_lower_KN2": 2 * w.K * w.N,
                      "mfma_flops_issued": tr["mfma_flops"]},
@@ -195,7 +207,9 @@ def main() -> int:
                  "tiles": st["num_tiles"], "tiles_identity_order": st["num_tiles_identity"],
                  "mean_nnz_per_tile": st["mean_nnz_per_tile"], "ibd": st["ibd"], "items": st["num_items"],
                  "split_windows": st["num_split_windows"], "partial_slots": st["num_partial_slots"],
-                 "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"]},
+                 "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"],
+                 "column_order_applied": st["column_order_applied"], "hub_label_skew": st["hub_label_skew"],
+                 "column_order_s": st["t_column_order_s"]},
         "parity_spot_check": {"rows": int(len(rows)), "ok": bool(ok), "worst_error_over_limit": ratio},
         "generate_s": t_gen,
         "paper_context": PAPER_CONTEXT,

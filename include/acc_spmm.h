@@ -40,7 +40,7 @@ typedef enum {
 /* Opaque plan handle, owned by the library; release with acc_spmm_destroy. */
 typedef struct acc_spmm_plan_s acc_spmm_plan_t;
 
-/* Values for acc_spmm_options.reorder and .load_balance */
+/* Values for acc_spmm_options.reorder, .load_balance and .column_order */
 enum { ACC_SPMM_OFF = 0, ACC_SPMM_ON = 1, ACC_SPMM_AUTO = 2 };
 
 /* acc_spmm_options.value_type */
@@ -100,6 +100,23 @@ typedef struct {
      * binary16, ACC_SPMM_BF16 (1) = bfloat16.  C is fp32 and products are accumulated in fp32
      * either way. */
     int32_t value_type;
+    /* Column order of A = row order of B inside the plan (the paper names column reordering
+     * with the matching row reordering of B as the step after row reordering; Section 4.3.1
+     * and the conclusion).  ON: columns are grouped by floor(log2(entries in the column)),
+     * classes descending, input ids ascending inside a class, unused columns last, so the
+     * rows of B that many windows gather sit together whatever labels the input gave them.
+     * AUTO: ON when K >= 2^21 (B then exceeds the memory-side cache at usual N, and the
+     * gain outweighs the per-call gather of B) and the labels of the most used columns are
+     * concentrated on few residues modulo 16, 256 or 4096 (acc_spmm_stats.hub_label_skew
+     * >= 4), which is when gathering their rows of B collides in the memory system; else
+     * OFF. */
+    int32_t column_order;
+    /* 0: B is given in the caller's row order; when the plan has a column order, every
+     *    execute first gathers B into a buffer of the plan (K x N values) in that order.
+     * 1: B is given in the plan's order already (B_plan[j] = B[col_order[j]], see
+     *    acc_spmm_permute_rows and ACC_SPMM_ARR_COL_ORDER); execute reads it in place.
+     * C is in the caller's row order in both cases. */
+    int32_t operand_order;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */
@@ -122,6 +139,12 @@ typedef struct {
     double reorder_work_ratio;  /* dendrogram edge-record visits per graph entry (0 if not run)  */
     double t_validate_s, t_reorder_s, t_encode_s, t_schedule_s, t_total_s;
     double t_graph_s, t_dendrogram_s, t_ordering_s; /* parts of t_reorder_s (the rest: tile counting) */
+    int32_t column_order_applied;
+    int32_t reserved0;
+    double hub_label_skew;      /* most loaded residue class of the most used columns' labels,  */
+                                /* relative to an even spread (0 if not computed: column_order */
+                                /* OFF or K < 65536)                                           */
+    double t_column_order_s;
 } acc_spmm_stats;
 
 /* Arrays acc_spmm_plan_export can copy out (element type, element count). */
@@ -134,8 +157,13 @@ typedef enum {
     ACC_SPMM_ARR_TC_LOCAL_BIT = 5,      /* uint64 T*ceil(window_height*tile_width/64)       */
     ACC_SPMM_ARR_VALUES = 6,            /* uint16 nnz        fp16 bits in tile order        */
     ACC_SPMM_ARR_WORK_ITEMS = 7,        /* int32  4*num_items, see acc_spmm_plan_export     */
-    ACC_SPMM_ARR_DENDROGRAM_PARENT = 8  /* int32  M          -1 for roots; empty if reorder */
+    ACC_SPMM_ARR_DENDROGRAM_PARENT = 8, /* int32  M          -1 for roots; empty if reorder */
                                         /*                   was off                        */
+    ACC_SPMM_ARR_COL_ORDER = 9,         /* int32  K          plan column -> input column    */
+    ACC_SPMM_ARR_COL_RANK = 10          /* int32  K          input column -> plan column    */
+                                        /*                   (both empty without a column   */
+                                        /*                   order; SparseAToB then holds   */
+                                        /*                   input columns, else plan ones) */
 } acc_spmm_array;
 
 /*
@@ -169,19 +197,32 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz
  *           caller's original order whatever the plan's internal reordering
  *   stream  hipStream_t, NULL = the default stream
  * Returns without waiting for the GPU.  Calls on one plan must not overlap in time on
- * different streams when the plan has split windows (they share one partial-sum
- * workspace, which the first call with a larger N (re)allocates).
+ * different streams when the plan has split windows or gathers B (they share the plan's
+ * partial-sum workspace and its buffer for the gathered B, which the first call with a
+ * larger N (re)allocates).
  */
 ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 
 /*
  * acc_spmm_execute with per-kernel timing, for benchmarks: records HIP events on `stream`
- * around the tile kernel and around the split-window combine kernel, waits for them, and
- * returns the two durations in milliseconds (combine_ms = 0 when the plan has no split
- * windows).  Same contract as acc_spmm_execute otherwise, but it blocks the calling thread.
+ * around the gather of B (if the plan does one), the tile kernel and the split-window
+ * combine kernel, waits for them, and returns the durations in milliseconds (gather_ms and
+ * combine_ms, which may be NULL, are 0 when the plan runs no such kernel).  Same contract
+ * as acc_spmm_execute otherwise, but it blocks the calling thread.
  */
 ACC_SPMM_API int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C,
-                                        void* stream, float* tiles_ms, float* combine_ms);
+                                        void* stream, float* tiles_ms, float* combine_ms, float* gather_ms);
+
+/*
+ * Reorder the rows of a K-row DEVICE matrix between the caller's order and the plan's
+ * column order (for callers that keep B in the plan's order, options.operand_order = 1).
+ *   row_bytes  bytes per row, a multiple of 2
+ *   to_caller  0: dst[j] = src[col_order[j]] (caller's order -> plan's order)
+ *              1: dst[col_order[j]] = src[j] (plan's order -> caller's order)
+ * src and dst must not overlap.  Without a column order in the plan this is a plain copy.
+ */
+ACC_SPMM_API int acc_spmm_permute_rows(const acc_spmm_plan_t* plan, const void* src, void* dst, int64_t row_bytes,
+                                       int32_t to_caller, void* stream);
 
 /*
  * Baseline for comparisons: one wavefront per CSR row, fp32 FMA, no tiles, no matrix

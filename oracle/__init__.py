@@ -164,3 +164,26 @@ def within_bound(C_gpu, C_ref, bound, rel=2e-3, abs_=1e-5):
     lim = rel * bound + abs_
     ratio = float((err / lim).max()) if err.size else 0.0
     return bool(np.all(err <= lim)) and bool(np.isfinite(C_gpu).all()), ratio
+
+
+def column_order(colidx, K):
+    """Column order used for the rows of B: columns grouped by floor(log2(number of stored
+    entries in the column)), groups by descending class, ascending column id inside a group,
+    columns without entries last.  Returns (order, rank): order[j] = input column at plan
+    position j, rank = its inverse.
+
+    The paper only names column reordering with the matching row reordering of B as the step
+    after row reordering (Section 4.3.1, conclusion) and gives no rule: this rule is the
+    library's own, so it is PARITY UNPINNED against the paper; the tests pin it to this
+    definition by brute force.  C = A.B does not depend on it."""
+    colidx = np.asarray(colidx, np.int64)
+    count = np.bincount(colidx, minlength=K)
+    cls = np.full(K, -1, np.int64)
+    used = count > 0
+    cls[used] = np.floor(np.log2(count[used])).astype(np.int64)
+    # exact for counts < 2^31: log2 of a power of two is exact in fp64, and other counts are
+    # at least one part in 2^31 away from the next power of two
+    order = np.argsort(-cls, kind="stable").astype(np.int32)
+    rank = np.empty(K, np.int32)
+    rank[order] = np.arange(K, dtype=np.int32)
+    return order, rank

@@ -23,18 +23,19 @@ ACC_SPMM_FP16, ACC_SPMM_BF16 = 0, 1
 
 (ACC_SPMM_ARR_PERM, ACC_SPMM_ARR_IPERM, ACC_SPMM_ARR_ROW_WINDOW_OFFSET, ACC_SPMM_ARR_TC_OFFSET,
  ACC_SPMM_ARR_SPARSE_A_TO_B, ACC_SPMM_ARR_TC_LOCAL_BIT, ACC_SPMM_ARR_VALUES, ACC_SPMM_ARR_WORK_ITEMS,
- ACC_SPMM_ARR_DENDROGRAM_PARENT) = range(9)
+ ACC_SPMM_ARR_DENDROGRAM_PARENT, ACC_SPMM_ARR_COL_ORDER, ACC_SPMM_ARR_COL_RANK) = range(11)
 
 _ARRAY_DTYPES = {
     ACC_SPMM_ARR_PERM: np.int32, ACC_SPMM_ARR_IPERM: np.int32, ACC_SPMM_ARR_ROW_WINDOW_OFFSET: np.int32,
     ACC_SPMM_ARR_TC_OFFSET: np.int32, ACC_SPMM_ARR_SPARSE_A_TO_B: np.int32, ACC_SPMM_ARR_TC_LOCAL_BIT: np.uint64,
     ACC_SPMM_ARR_VALUES: np.uint16, ACC_SPMM_ARR_WORK_ITEMS: np.int32, ACC_SPMM_ARR_DENDROGRAM_PARENT: np.int32,
+    ACC_SPMM_ARR_COL_ORDER: np.int32, ACC_SPMM_ARR_COL_RANK: np.int32,
 }
 
 EXPORTED_SYMBOLS = [
     "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
-    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy",
+    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows",
 ]
 
 
@@ -46,6 +47,8 @@ class acc_spmm_options(ctypes.Structure):
         ("no_prefetch", ctypes.c_int32), ("streaming_stores", ctypes.c_int32), ("pipeline_depth", ctypes.c_int32),
         ("value_fetch", ctypes.c_int32),
         ("value_type", ctypes.c_int32),
+        ("column_order", ctypes.c_int32),
+        ("operand_order", ctypes.c_int32),
     ]
 
 
@@ -64,6 +67,8 @@ class acc_spmm_stats(ctypes.Structure):
         ("t_validate_s", ctypes.c_double), ("t_reorder_s", ctypes.c_double), ("t_encode_s", ctypes.c_double),
         ("t_schedule_s", ctypes.c_double), ("t_total_s", ctypes.c_double),
         ("t_graph_s", ctypes.c_double), ("t_dendrogram_s", ctypes.c_double), ("t_ordering_s", ctypes.c_double),
+        ("column_order_applied", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("hub_label_skew", ctypes.c_double), ("t_column_order_s", ctypes.c_double),
     ]
 
     def as_dict(self):
@@ -93,7 +98,9 @@ def load():
     L.acc_spmm_execute.restype = ctypes.c_int
     L.acc_spmm_execute.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_execute_timed.restype = ctypes.c_int
-    L.acc_spmm_execute_timed.argtypes = [vp, vp, i32, vp, vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_float)]
+    L.acc_spmm_execute_timed.argtypes = [vp, vp, i32, vp, vp] + [ctypes.POINTER(ctypes.c_float)] * 3
+    L.acc_spmm_permute_rows.restype = ctypes.c_int
+    L.acc_spmm_permute_rows.argtypes = [vp, vp, vp, i64, i32, vp]
     L.acc_spmm_execute_csr_naive.restype = ctypes.c_int
     L.acc_spmm_execute_csr_naive.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_destroy.restype = None
@@ -145,6 +152,7 @@ def make_options(**kw) -> acc_spmm_options:
     o.struct_size = ctypes.sizeof(acc_spmm_options)
     o.reorder = ACC_SPMM_AUTO
     o.load_balance = ACC_SPMM_AUTO
+    o.column_order = ACC_SPMM_AUTO
     for k, v in kw.items():
         if not hasattr(o, k):
             raise TypeError(f"unknown option {k}")
@@ -176,11 +184,17 @@ def acc_spmm_execute(plan, B, N, C, stream=None):
 
 
 def acc_spmm_execute_timed(plan, B, N, C, stream=None):
-    """Blocking execute; returns (tile kernel ms, combine kernel ms) from HIP events on `stream`."""
-    t, c = ctypes.c_float(), ctypes.c_float()
-    if load().acc_spmm_execute_timed(plan, _dev_ptr(B), N, _dev_ptr(C), stream, ctypes.byref(t), ctypes.byref(c)) != 0:
+    """Blocking execute; returns (tile kernel ms, combine kernel ms, B gather ms) from HIP events on `stream`."""
+    t, c, g = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
+    if load().acc_spmm_execute_timed(plan, _dev_ptr(B), N, _dev_ptr(C), stream, ctypes.byref(t), ctypes.byref(c),
+                                     ctypes.byref(g)) != 0:
         _raise()
-    return t.value, c.value
+    return t.value, c.value, g.value
+
+
+def acc_spmm_permute_rows(plan, src, dst, row_bytes, to_caller=0, stream=None):
+    if load().acc_spmm_permute_rows(plan, _dev_ptr(src), _dev_ptr(dst), row_bytes, to_caller, stream) != 0:
+        _raise()
 
 
 def acc_spmm_calibration_copy(dst, src, nbytes, stream=None):

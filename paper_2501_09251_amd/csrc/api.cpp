@@ -23,6 +23,32 @@ constexpr double kAutoReorderMinGain = 0.04;     // AUTO keeps the reordering on
 constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
 constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry
+constexpr int64_t kHubSkewMinK = 65536;          // fewer columns: too few labels for the statistic
+// AUTO column order only from 2^21 columns on: measured on R-MAT inputs, relabelling pays for
+// the per-call gather of B once B exceeds about 256 MB (2^21 columns at N = 64), the size of
+// the memory-side cache; below that the tile kernel gains little and the gather is a net loss
+constexpr int64_t kAutoColumnOrderMinK = (int64_t)1 << 21;
+constexpr int64_t kHubSample = 65536;            // most used columns whose labels are examined
+constexpr double kAutoColumnOrderSkew = 4.0;
+
+// How unevenly the labels of the most used columns (`top`, any order) fall on the residue
+// classes modulo 16, 256 and 4096: the fullest class over an even share, the largest of the
+// three moduli that leave at least 8 labels per class on average.  About 1 to 2 for labels
+// unrelated to use counts; large when the heavy columns sit at power-of-two strides (the ids
+// with few set bits of an unscrambled R-MAT graph), where their rows of B collide in the
+// memory system.
+double hub_label_skew(const std::vector<int32_t>& top) {
+    double worst = 0.0;
+    for (int bits : {4, 8, 12}) {
+        const size_t classes = (size_t)1 << bits;
+        if (top.size() < 8 * classes) continue;
+        std::vector<int32_t> count(classes, 0);
+        for (int32_t c : top) ++count[(size_t)c & (classes - 1)];
+        const double even = (double)top.size() / (double)classes;
+        worst = std::max(worst, (double)*std::max_element(count.begin(), count.end()) / even);
+    }
+    return worst;
+}
 }  // namespace
 
 void set_error(int code, const std::string& msg) {
@@ -80,11 +106,14 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     acc_spmm_options opt{};
     opt.reorder = ACC_SPMM_AUTO;
     opt.load_balance = ACC_SPMM_AUTO;
+    opt.column_order = ACC_SPMM_AUTO;
     if (user) {
         if (user->struct_size != (int32_t)sizeof(acc_spmm_options))
             fail(ACC_SPMM_ERR_INVALID_ARG, "options.struct_size does not match this library");
         opt = *user;
     }
+    if (opt.column_order < 0 || opt.column_order > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "column_order must be OFF, ON or AUTO");
+    if (opt.operand_order < 0 || opt.operand_order > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "operand_order must be 0 or 1");
     if (opt.reorder < 0 || opt.reorder > 2 || opt.load_balance < 0 || opt.load_balance > 2)
         fail(ACC_SPMM_ERR_INVALID_ARG, "reorder / load_balance must be OFF, ON or AUTO");
     if (opt.window_height == 0) opt.window_height = 16;
@@ -183,10 +212,41 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         }
         std::vector<int32_t>().swap(identity);
 
+        // ---- column order ----
+        const double c0 = now_s();
+        double skew = 0.0;
+        DevBuf<int32_t> d_colidx_plan;   // column indices in the plan's column order (only if one is applied)
+        if (opt.column_order != ACC_SPMM_OFF && K > 0 && nnz > 0) {
+            DevBuf<int32_t> d_order, d_rank;
+            column_order_on_device(K, nnz, P.d_colidx.p, d_order, d_rank);
+            bool apply = opt.column_order == ACC_SPMM_ON;
+            if (K >= kHubSkewMinK) {
+                std::vector<int32_t> top((size_t)std::min<int64_t>(kHubSample, K / 16));
+                ACC_HIP(hipMemcpy(top.data(), d_order.p, sizeof(int32_t) * top.size(), hipMemcpyDeviceToHost));
+                skew = hub_label_skew(top);
+            }
+            if (opt.column_order == ACC_SPMM_AUTO) apply = K >= kAutoColumnOrderMinK && skew >= kAutoColumnOrderSkew;
+            if (apply) {
+                P.col_order.resize(K);
+                P.col_rank.resize(K);
+                d_order.download(P.col_order.data());
+                d_rank.download(P.col_rank.data());
+                d_colidx_plan.alloc(nnz);
+                remap_columns_on_device(nnz, P.d_colidx.p, d_rank.p, d_colidx_plan.p);
+                P.d_col_order.swap(d_order);
+            }
+        }
+        const bool use_col_order = P.d_col_order.p != nullptr;
+        const double t_col_order = now_s() - c0;
+
         // ---- format ----
         const double e0 = now_s();
-        encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, P.fmt, false);
+        encode_on_device(M, K, nnz, P.d_rowptr.p, use_col_order ? d_colidx_plan.p : P.d_colidx.p, P.d_vals.p, d_perm.p, WH,
+                         TW, P.fmt, false);
         const double t_encode = now_s() - e0;
+        // the comparison kernel reads B as execute is given it
+        if (use_col_order && opt.operand_order == 1 && opt.keep_csr) P.d_colidx.swap(d_colidx_plan);
+        d_colidx_plan.release();
         if (!opt.keep_csr) {
             P.d_rowptr.release();
             P.d_colidx.release();
@@ -234,6 +294,9 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.t_reorder_s = t_reorder;
         st.t_encode_s = t_encode;
         st.t_schedule_s = t_schedule;
+        st.column_order_applied = use_col_order;
+        st.hub_label_skew = skew;
+        st.t_column_order_s = t_col_order;
         st.t_total_s = now_s() - t0;
     } catch (...) {
         delete handle;
@@ -287,10 +350,29 @@ int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void
 }
 
 int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream,
-                           float* tiles_ms, float* combine_ms) {
+                           float* tiles_ms, float* combine_ms, float* gather_ms) {
     return guarded([&] {
         if (!plan || !C || !tiles_ms || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
-        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), tiles_ms, combine_ms);
+        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), tiles_ms, combine_ms, gather_ms);
+    });
+}
+
+int acc_spmm_permute_rows(const acc_spmm_plan_t* plan, const void* src, void* dst, int64_t row_bytes, int32_t to_caller,
+                          void* stream) {
+    return guarded([&] {
+        if (!plan || !src || !dst) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        if (row_bytes <= 0 || (row_bytes & 1)) fail(ACC_SPMM_ERR_INVALID_ARG, "row_bytes must be a positive multiple of 2");
+        const Plan& P = plan->plan;
+        int dev = -1;
+        ACC_HIP(hipGetDevice(&dev));
+        if (dev != P.device) fail(ACC_SPMM_ERR_INVALID_ARG, "the plan lives on another device than the current one");
+        if (P.stats.K == 0) return;
+        if (!P.d_col_order.p) {
+            ACC_HIP(hipMemcpyAsync(dst, src, (size_t)P.stats.K * (size_t)row_bytes, hipMemcpyDeviceToDevice,
+                                   static_cast<hipStream_t>(stream)));
+            return;
+        }
+        launch_permute_rows(P.d_col_order.p, P.stats.K, src, dst, row_bytes, to_caller != 0, static_cast<hipStream_t>(stream));
     });
 }
 
@@ -399,6 +481,8 @@ int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst,
             case ACC_SPMM_ARR_PERM: host = P.perm.data(); need = P.perm.size() * 4; break;
             case ACC_SPMM_ARR_IPERM: host = P.iperm.data(); need = P.iperm.size() * 4; break;
             case ACC_SPMM_ARR_DENDROGRAM_PARENT: host = P.parent.data(); need = P.parent.size() * 4; break;
+            case ACC_SPMM_ARR_COL_ORDER: host = P.col_order.data(); need = P.col_order.size() * 4; break;
+            case ACC_SPMM_ARR_COL_RANK: host = P.col_rank.data(); need = P.col_rank.size() * 4; break;
             case ACC_SPMM_ARR_WORK_ITEMS: host = P.items.data(); need = P.items.size() * sizeof(WorkItem); break;
             case ACC_SPMM_ARR_ROW_WINDOW_OFFSET: dev = f.row_window_offset.p; need = (size_t)(f.W + 1) * 4; break;
             case ACC_SPMM_ARR_TC_OFFSET: dev = f.tc_offset.p; need = (size_t)(f.T + 1) * 4; break;

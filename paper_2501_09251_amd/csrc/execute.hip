@@ -3,6 +3,8 @@
 // holds the small kernels used for comparison and calibration.
 #include <algorithm>
 
+#include <mutex>
+
 #include "execute.h"
 
 namespace accspmm {
@@ -77,17 +79,18 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
 }  // namespace
 
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream, float* tiles_ms,
-                    float* combine_ms) {
+                    float* combine_ms, float* gather_ms) {
     const bool timed = tiles_ms != nullptr;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     if (timed) {
         *tiles_ms = 0.f;
         if (combine_ms) *combine_ms = 0.f;
+        if (gather_ms) *gather_ms = 0.f;
         for (auto& e : ev) ACC_HIP(hipEventCreate(&e));
     }
     struct EventGuard {
         hipEvent_t* ev;
-        ~EventGuard() { for (int i = 0; i < 3; ++i) if (ev[i]) (void)hipEventDestroy(ev[i]); }
+        ~EventGuard() { for (int i = 0; i < 4; ++i) if (ev[i]) (void)hipEventDestroy(ev[i]); }
     } guard{ev};
     const DeviceFormat& f = plan.fmt;
     if (f.WH != 16 || f.TW != 16)
@@ -106,6 +109,19 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
             plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
             plan.workspace_N = N;
         }
+    }
+    const bool gather = plan.d_col_order.p != nullptr && plan.opt.operand_order == 0 && f.nnz > 0;
+    if (gather) {
+        std::lock_guard<std::mutex> lock(plan.workspace_mutex);
+        if (plan.b_gathered_N < N) {
+            plan.b_gathered.alloc((size_t)plan.stats.K * (size_t)N);
+            plan.b_gathered_N = N;
+        }
+    }
+    if (timed) ACC_HIP(hipEventRecord(ev[3], stream));
+    if (gather) {
+        launch_permute_rows(plan.d_col_order.p, plan.stats.K, B, plan.b_gathered.p, (int64_t)N * 2, false, stream);
+        B = plan.b_gathered.p;
     }
     ExecParams p;
     p.rwo = f.row_window_offset.p;
@@ -170,6 +186,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
         ACC_HIP(hipEventSynchronize(ev[2]));
         ACC_HIP(hipEventElapsedTime(tiles_ms, ev[0], ev[1]));
         if (combine_ms && !plan.splits.empty()) ACC_HIP(hipEventElapsedTime(combine_ms, ev[1], ev[2]));
+        if (gather_ms && gather) ACC_HIP(hipEventElapsedTime(gather_ms, ev[3], ev[0]));
     }
 }
 

@@ -5,6 +5,7 @@
 #include <cstdint>
 #include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "acc_spmm.h"
@@ -52,6 +53,10 @@ struct DevBuf {
     }
     void download(T* host) const {
         if (n) ACC_HIP(hipMemcpy(host, p, n * sizeof(T), hipMemcpyDeviceToHost));
+    }
+    void swap(DevBuf& other) {
+        std::swap(p, other.p);
+        std::swap(n, other.n);
     }
 };
 
@@ -110,6 +115,15 @@ void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowp
                         const std::vector<int32_t>& seq, const std::vector<int64_t>& seg_start, int32_t seg_len,
                         int32_t max_row_len, DevBuf<int32_t>& d_perm);
 
+// colorder.hip: the plan's column order (d_order: plan column -> input column, d_rank its
+// inverse), the relabelling of a column-index array, and the row permutation of a matrix
+// (gather: dst row j = src row order[j]; scatter: dst row order[j] = src row j).
+void column_order_on_device(int64_t K, int64_t nnz, const int32_t* d_colidx, DevBuf<int32_t>& d_order,
+                            DevBuf<int32_t>& d_rank);
+void remap_columns_on_device(int64_t nnz, const int32_t* d_colidx, const int32_t* d_rank, int32_t* d_out);
+void launch_permute_rows(const int32_t* d_order, int64_t rows, const void* src, void* dst, int64_t row_bytes, bool scatter,
+                         hipStream_t stream);
+
 // schedule.cpp: Section 3.5.
 double imbalance_degree(const std::vector<int32_t>& rwo);
 void build_schedule(const std::vector<int32_t>& rwo, bool balance, int32_t cap, int32_t WH, int32_t TW,
@@ -131,15 +145,20 @@ struct Plan {
     mutable std::mutex workspace_mutex;
     mutable DevBuf<float> workspace;
     mutable int32_t workspace_N = 0;
+    // column order (empty when not applied) and the buffer for B gathered into it
+    DevBuf<int32_t> d_col_order;
+    std::vector<int32_t> col_order, col_rank;
+    mutable DevBuf<uint16_t> b_gathered;
+    mutable int32_t b_gathered_N = 0;
     // optional CSR copy for the naive baseline
     DevBuf<int32_t> d_rowptr, d_colidx;
     DevBuf<uint16_t> d_vals;
 };
 
 // execute.hip
-// tiles_ms / combine_ms non-null: time the two kernels with events and wait for them
+// tiles_ms non-null: time the kernels with events and wait for them
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream,
-                    float* tiles_ms = nullptr, float* combine_ms = nullptr);
+                    float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr);
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 

@@ -62,4 +62,5 @@ def bf16(a):
 
 
 def bf16_to_f64(bits):
-    return (np.asarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    with np.errstate(invalid="ignore"):                      # signalling NaN patterns are fine here
+        return (np.asarray(bits, np.uint16).astype(np.uint32) << 16).view(np.float32).astype(np.float64)

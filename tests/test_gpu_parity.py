@@ -49,6 +49,9 @@ def check_against_oracle(rowptr, colidx, vals, B, C, rows=None, value_type="f16"
 
 def check_format(plan, rowptr, colidx, vals, WH=16, TW=16):
     perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
+    rank = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_RANK)
+    if len(rank):                       # the plan's arrays hold columns in its own column order
+        colidx, vals = sorted_rows(rowptr, rank[colidx], vals)
     fmt = oracle.encode(rowptr, colidx, vals, perm, WH, TW)
     for which, key in ((acc.ACC_SPMM_ARR_ROW_WINDOW_OFFSET, "row_window_offset"), (acc.ACC_SPMM_ARR_TC_OFFSET, "tc_offset"),
                        (acc.ACC_SPMM_ARR_SPARSE_A_TO_B, "sparse_a_to_b"), (acc.ACC_SPMM_ARR_TC_LOCAL_BIT, "tc_local_bit"),
@@ -193,6 +196,82 @@ def test_bfloat16_values(N, fetch):
         assert sorted(packed.tolist()) == sorted(vals.tolist())          # bits pass through the encoder untouched
     finally:
         acc.acc_spmm_destroy(plan)
+
+
+def _permuted(plan, X, to_caller=0):
+    """X (numpy, K rows) through acc_spmm_permute_rows."""
+    src = torch.from_numpy(np.ascontiguousarray(X).view(np.int16 if X.dtype == np.uint16 else X.dtype)).cuda()
+    dst = torch.zeros_like(src)
+    acc.acc_spmm_permute_rows(plan, src, dst, X.shape[1] * X.dtype.itemsize, to_caller, None)
+    torch.cuda.synchronize()
+    return dst.cpu().numpy().view(X.dtype)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(2, 6), (5, 7), (4, 4), (1, 0)])
+@pytest.mark.parametrize("operand_order", [0, 1])
+def test_column_order_forced_on(cfg, shrink, operand_order):
+    """The plan's column order equals its definition, the tile format is that of the relabelled
+    matrix, and C is the same whether execute gathers B itself or is handed B in plan order."""
+    w = wl.config(cfg, shrink)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(column_order=acc.ACC_SPMM_ON, operand_order=operand_order, keep_csr=1))
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        assert st["column_order_applied"] == 1
+        order, rank = oracle.column_order(w.colidx, w.K)
+        np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_ORDER), order)
+        np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_RANK), rank)
+        check_format(plan, w.rowptr, w.colidx, w.vals)
+        B_plan = _permuted(plan, w.B)
+        np.testing.assert_array_equal(B_plan, w.B[order])
+        np.testing.assert_array_equal(_permuted(plan, B_plan, to_caller=1), w.B)
+        B_given = B_plan if operand_order == 1 else w.B
+        C = run_spmm(plan, B_given, w.M, w.N)
+        check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C)
+        Cn = run_spmm(plan, B_given, w.M, w.N, naive=True)
+        check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, Cn)
+        for N in (7, 200):                                   # the gathered-B buffer grows with N; odd row sizes
+            B2 = wl.dense(w.K, N, 5, "normal", 0.0, 1.0)
+            C2 = run_spmm(plan, _permuted(plan, B2) if operand_order == 1 else B2, w.M, N)
+            check_against_oracle(w.rowptr, w.colidx, w.vals, B2, C2)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_column_order_auto_detects_hubs_at_power_of_two_labels():
+    """AUTO relabels the unscrambled R-MAT graph (its heavy columns are the ids with few set
+    bits) and leaves alone the same graph under random labels, the randomly labelled block
+    model, the mesh and the uniform matrix."""
+    def applied(M, K, rowptr, colidx, vals):
+        plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                    acc.make_options(reorder=acc.ACC_SPMM_OFF))
+        try:
+            st = acc.acc_spmm_plan_stats(plan)
+            return st["column_order_applied"], st["hub_label_skew"]
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+    w = wl.config(5, 2, with_B=False)                         # 2^21 vertices
+    on, skew = applied(w.M, w.K, w.rowptr, w.colidx, w.vals)
+    assert on == 1 and skew >= 8.0
+    relabel = np.random.default_rng(0).permutation(w.K).astype(np.int32)
+    on, skew = applied(w.M, w.K, w.rowptr, relabel[w.colidx], w.vals)
+    assert on == 0 and skew < 2.5
+    w = wl.config(5, 5, with_B=False)                         # 2^18 vertices: same labels, but B is small
+    on, skew = applied(w.M, w.K, w.rowptr, w.colidx, w.vals)
+    assert on == 0 and skew >= 8.0
+    for cfg, shrink in ((4, 1), (3, 3)):
+        w = wl.config(cfg, shrink, with_B=False)
+        assert w.K >= 65536
+        on, skew = applied(w.M, w.K, w.rowptr, w.colidx, w.vals)
+        assert on == 0 and skew < 2.5, (cfg, skew)
+    rng = np.random.default_rng(1)
+    M = K = 100000
+    colidx = np.sort(rng.integers(0, K - 8, (M, 8)), axis=1) + np.arange(8)     # distinct inside a row
+    rowptr = np.arange(M + 1, dtype=np.int32) * 8
+    on, skew = applied(M, K, rowptr, np.ascontiguousarray(colidx.reshape(-1).astype(np.int32)),
+                       f16(np.ones(M * 8)))
+    assert on == 0 and skew < 2.5
 
 
 def test_identity_and_permutation_matrices_are_exact():

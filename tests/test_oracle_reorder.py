@@ -105,3 +105,33 @@ def test_reordering_recovers_hidden_blocks():
     t0 = len(oracle.encode(rowptr, colidx, vals, None, 16, 16)["tc_offset"]) - 1
     t1 = len(oracle.encode(rowptr, colidx, vals, perm, 16, 16)["tc_offset"]) - 1
     assert t1 < 0.6 * t0
+
+
+def test_column_order_against_brute_force_and_its_defining_properties():
+    rng = np.random.default_rng(5)
+    for K, nnz in ((1, 0), (7, 3), (50, 400), (300, 5000)):
+        # skewed use counts: squares of uniform numbers favour the low ids
+        colidx = (rng.random(nnz) ** 3 * K).astype(np.int32)
+        order, rank = oracle.column_order(colidx, K)
+        count = [0] * K
+        for c in colidx.tolist():
+            count[c] += 1
+        def cls(n):                      # floor(log2(n)) by integer shifts, -1 for unused columns
+            k = -1
+            while n:
+                n >>= 1
+                k += 1
+            return k
+        brute = sorted(range(K), key=lambda c: (-cls(count[c]), c))
+        assert order.tolist() == brute
+        assert sorted(order.tolist()) == list(range(K))
+        assert all(rank[order[j]] == j for j in range(K))
+        classes = [cls(count[c]) for c in order]
+        assert classes == sorted(classes, reverse=True)
+
+
+def test_column_order_keeps_inputs_with_even_counts_in_place():
+    K = 64
+    colidx = np.repeat(np.arange(K, dtype=np.int32), 5)      # every column used 5 times
+    order, rank = oracle.column_order(colidx, K)
+    assert order.tolist() == list(range(K)) and rank.tolist() == list(range(K))

@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the tile kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by the library's plain copy kernel (summaries under profiles/); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "rmat-2^23-deg32-N128": 60.00e9,
+    "rmat-2^23-deg32-N128": 59.97e9,
 }
 
 
@@ -46,7 +46,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..5 of BASELINE.json (default: 5, the metric's config)")
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 of the benchmark set (default: 5, the configuration the metric is quoted on)")
     ap.add_argument("--shrink", type=int, default=0, help="divide the row count by 2^shrink (debugging)")
     ap.add_argument("--reorder", choices=["off", "on", "auto"], default="auto")
     ap.add_argument("--load-balance", choices=["off", "on", "auto"], default="auto")

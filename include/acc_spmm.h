@@ -105,14 +105,15 @@ typedef struct {
      * and the conclusion).  ON: columns are grouped by floor(log2(entries in the column)),
      * classes descending, input ids ascending inside a class, unused columns last, so the
      * rows of B that many windows gather sit together whatever labels the input gave them.
-     * AUTO: ON when K >= 2^21 (B then exceeds the memory-side cache at usual N, and the
-     * gain outweighs the per-call gather of B) and the labels of the most used columns are
-     * concentrated on few residues modulo 16, 256 or 4096 (acc_spmm_stats.hub_label_skew
-     * >= 4), which is when gathering their rows of B collides in the memory system; else
-     * OFF. */
+     * AUTO: ON when K >= 2^21 (B then exceeds the memory-side cache at usual N) and the
+     * labels of the most used columns are concentrated on few residues modulo 16, 256 or
+     * 4096 (acc_spmm_stats.hub_label_skew >= 4), which is when gathering their rows of B
+     * collides in the memory system; else OFF. */
     int32_t column_order;
     /* 0: B is given in the caller's row order; when the plan has a column order, every
-     *    execute first gathers B into a buffer of the plan (K x N values) in that order.
+     *    execute first gathers the rows of B for the first min(K/16, 2^17) columns of that
+     *    order (the most used ones) into a buffer of the plan and reads the other rows of B
+     *    in place.
      * 1: B is given in the plan's order already (B_plan[j] = B[col_order[j]], see
      *    acc_spmm_permute_rows and ACC_SPMM_ARR_COL_ORDER); execute reads it in place.
      * C is in the caller's row order in both cases. */
@@ -140,7 +141,7 @@ typedef struct {
     double t_validate_s, t_reorder_s, t_encode_s, t_schedule_s, t_total_s;
     double t_graph_s, t_dendrogram_s, t_ordering_s; /* parts of t_reorder_s (the rest: tile counting) */
     int32_t column_order_applied;
-    int32_t reserved0;
+    int32_t num_hot_columns;    /* rows of B gathered per execute (operand_order 0 with a column order) */
     double hub_label_skew;      /* most loaded residue class of the most used columns' labels,  */
                                 /* relative to an even spread (0 if not computed: column_order */
                                 /* OFF or K < 65536)                                           */
@@ -153,7 +154,11 @@ typedef enum {
     ACC_SPMM_ARR_IPERM = 1,             /* int32  M          input row -> new row           */
     ACC_SPMM_ARR_ROW_WINDOW_OFFSET = 2, /* int32  W+1                                       */
     ACC_SPMM_ARR_TC_OFFSET = 3,         /* int32  T+1                                       */
-    ACC_SPMM_ARR_SPARSE_A_TO_B = 4,     /* int32  T*tile_width                              */
+    ACC_SPMM_ARR_SPARSE_A_TO_B = 4,     /* int32  T*tile_width; input columns, or, with a   */
+                                        /*        column order: plan columns (operand_order */
+                                        /*        1), or ~p for plan column p < num_hot_    */
+                                        /*        columns and the input column otherwise    */
+                                        /*        (operand_order 0)                         */
     ACC_SPMM_ARR_TC_LOCAL_BIT = 5,      /* uint64 T*ceil(window_height*tile_width/64)       */
     ACC_SPMM_ARR_VALUES = 6,            /* uint16 nnz        fp16 bits in tile order        */
     ACC_SPMM_ARR_WORK_ITEMS = 7,        /* int32  4*num_items, see acc_spmm_plan_export     */
@@ -162,8 +167,7 @@ typedef enum {
     ACC_SPMM_ARR_COL_ORDER = 9,         /* int32  K          plan column -> input column    */
     ACC_SPMM_ARR_COL_RANK = 10          /* int32  K          input column -> plan column    */
                                         /*                   (both empty without a column   */
-                                        /*                   order; SparseAToB then holds   */
-                                        /*                   input columns, else plan ones) */
+                                        /*                   order)                         */
 } acc_spmm_array;
 
 /*
@@ -197,9 +201,9 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz
  *           caller's original order whatever the plan's internal reordering
  *   stream  hipStream_t, NULL = the default stream
  * Returns without waiting for the GPU.  Calls on one plan must not overlap in time on
- * different streams when the plan has split windows or gathers B (they share the plan's
- * partial-sum workspace and its buffer for the gathered B, which the first call with a
- * larger N (re)allocates).
+ * different streams when the plan has split windows or gathers rows of B (they share the
+ * plan's partial-sum workspace and its buffer for the gathered rows, which the first call
+ * with a larger N (re)allocates).
  */
 ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 

@@ -67,7 +67,7 @@ class acc_spmm_stats(ctypes.Structure):
         ("t_validate_s", ctypes.c_double), ("t_reorder_s", ctypes.c_double), ("t_encode_s", ctypes.c_double),
         ("t_schedule_s", ctypes.c_double), ("t_total_s", ctypes.c_double),
         ("t_graph_s", ctypes.c_double), ("t_dendrogram_s", ctypes.c_double), ("t_ordering_s", ctypes.c_double),
-        ("column_order_applied", ctypes.c_int32), ("reserved0", ctypes.c_int32),
+        ("column_order_applied", ctypes.c_int32), ("num_hot_columns", ctypes.c_int32),
         ("hub_label_skew", ctypes.c_double), ("t_column_order_s", ctypes.c_double),
     ]
 

@@ -24,12 +24,17 @@ constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
 constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry
 constexpr int64_t kHubSkewMinK = 65536;          // fewer columns: too few labels for the statistic
-// AUTO column order only from 2^21 columns on: measured on R-MAT inputs, relabelling pays for
-// the per-call gather of B once B exceeds about 256 MB (2^21 columns at N = 64), the size of
-// the memory-side cache; below that the tile kernel gains little and the gather is a net loss
+// AUTO column order only from 2^21 columns on.  Measured on unscrambled R-MAT inputs with B in
+// the caller's order: the order pays once B exceeds about 256 MB, the size of the memory-side
+// cache (+22..30 % at N >= 128 from 2^20 columns on), while at N <= 64 the 64-bit addressing of
+// the two-matrix gather costs 12..26 % below 2^21 columns, 4 % at 2^21, and wins from 2^22 on.
 constexpr int64_t kAutoColumnOrderMinK = (int64_t)1 << 21;
 constexpr int64_t kHubSample = 65536;            // most used columns whose labels are examined
 constexpr double kAutoColumnOrderSkew = 4.0;
+// Rows of B gathered per execute when B comes in the caller's order: the first K/16 of the
+// column order, at most 2^17.  Measured on R-MAT 2^23: moving the 2^14 most used columns gives
+// most of the gain, 2^17 all of it (they carry 64 % of the entries), 2^20 nothing more.
+constexpr int64_t kMaxHotColumns = (int64_t)1 << 17;
 
 // How unevenly the labels of the most used columns (`top`, any order) fall on the residue
 // classes modulo 16, 256 and 4096: the fullest class over an even share, the largest of the
@@ -247,6 +252,11 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         // the comparison kernel reads B as execute is given it
         if (use_col_order && opt.operand_order == 1 && opt.keep_csr) P.d_colidx.swap(d_colidx_plan);
         d_colidx_plan.release();
+        if (use_col_order && opt.operand_order == 0) {
+            // B stays in the caller's order: only the most used rows are gathered per call
+            P.n_hot = (int32_t)std::min<int64_t>(kMaxHotColumns, K / 16);
+            hot_cold_entries_on_device(P.fmt.T * TW, P.fmt.sparse_a_to_b.p, P.d_col_order.p, P.n_hot);
+        }
         if (!opt.keep_csr) {
             P.d_rowptr.release();
             P.d_colidx.release();
@@ -295,6 +305,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.t_encode_s = t_encode;
         st.t_schedule_s = t_schedule;
         st.column_order_applied = use_col_order;
+        st.num_hot_columns = P.n_hot;
         st.hub_label_skew = skew;
         st.t_column_order_s = t_col_order;
         st.t_total_s = now_s() - t0;

@@ -1,5 +1,5 @@
 // Column order of A = row order of B (the paper's Section 4.3.1 and its conclusion name
-// "column reordering of A with the matching row reordering of B" as the next step after row
+// column reordering of A with the matching row reordering of B as the next step after row
 // reordering; the order itself is this library's choice).
 //
 // The order groups columns by how often they are used: class(c) = floor(log2(entries in
@@ -10,6 +10,11 @@
 // on an R-MAT graph with unscrambled labels the hubs are the ids with few set bits, their
 // rows of B lie at large power-of-two strides, and gathering them collides in the memory
 // system; relabelling removed a quarter of the kernel time at 2^23 columns.
+//
+// Two ways to use the order.  The caller keeps B in it (all of SparseAToB in plan ids).  Or B
+// stays in the caller's order and only the first n_hot rows of the order, which carry most of
+// the gathers, are copied together before each execute; SparseAToB then names either a row of
+// that copy or a row of B in place.
 #include "device_util.h"
 
 namespace accspmm {
@@ -42,6 +47,17 @@ __global__ void remap_kernel(int64_t nnz, const int32_t* __restrict__ colidx, co
                              int32_t* __restrict__ out) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nnz) out[i] = rank[colidx[i]];
+}
+
+// Entries of SparseAToB in plan column ids -> what the tile kernel reads when B stays in the
+// caller's order: plan column r < n_hot becomes ~r (row r of the gathered hot rows), the others
+// become their input column order[r] (a row of B in place).
+__global__ void hot_cold_entries_kernel(int64_t n, int32_t* __restrict__ a2b, const int32_t* __restrict__ order,
+                                        int32_t n_hot) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int32_t r = a2b[i];
+    a2b[i] = r < n_hot ? ~r : order[r];
 }
 
 // dst row j = src row order[j] (gather) or dst row order[j] = src row j (scatter); rows of
@@ -88,6 +104,13 @@ void remap_columns_on_device(int64_t nnz, const int32_t* d_colidx, const int32_t
     if (nnz == 0) return;
     hipLaunchKernelGGL(remap_kernel, dim3(blocks_for(nnz, 256)), dim3(256), 0, 0, nnz, d_colidx, d_rank, d_out);
     ACC_HIP(hipGetLastError());
+}
+
+void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot) {
+    if (n == 0) return;
+    hipLaunchKernelGGL(hot_cold_entries_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, 0, n, d_a2b, d_order, n_hot);
+    ACC_HIP(hipGetLastError());
+    ACC_HIP(hipDeviceSynchronize());
 }
 
 void launch_permute_rows(const int32_t* d_order, int64_t rows, const void* src, void* dst, int64_t row_bytes, bool scatter,

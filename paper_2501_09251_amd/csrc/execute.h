@@ -6,6 +6,7 @@ namespace accspmm {
 
 constexpr int kWavesPerBlock = 4;   // wavefronts (work items) per thread block of the tile kernel
 constexpr int kMaxN = 65536;
+constexpr int kAddrNarrow = 0, kAddrWide = 1, kAddrHot = 2;   // how the tile kernel addresses rows of B
 
 struct ExecParams {
     const int32_t* __restrict__ rwo;
@@ -21,7 +22,8 @@ struct ExecParams {
     int32_t n_items;
     int32_t n_blocks;  // logical thread blocks = ceil(n_items / kWavesPerBlock)
     int32_t N;
-    bool wide;         // B needs 64-bit row offsets
+    int32_t addr;      // kAddrNarrow / kAddrWide / kAddrHot
+    const uint16_t* __restrict__ B_hot;  // kAddrHot: the gathered most used rows of B
     bool coop;         // cooperative value fetch
     bool tail;         // N is not a whole number of slabs
     bool bf16;         // values are bfloat16

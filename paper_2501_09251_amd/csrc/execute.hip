@@ -111,18 +111,15 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
         }
     }
     const bool gather = plan.d_col_order.p != nullptr && plan.opt.operand_order == 0 && f.nnz > 0;
-    if (gather) {
+    if (gather && plan.n_hot > 0) {
         std::lock_guard<std::mutex> lock(plan.workspace_mutex);
-        if (plan.b_gathered_N < N) {
-            plan.b_gathered.alloc((size_t)plan.stats.K * (size_t)N);
-            plan.b_gathered_N = N;
+        if (plan.b_hot_N < N) {
+            plan.b_hot.alloc((size_t)plan.n_hot * (size_t)N);
+            plan.b_hot_N = N;
         }
     }
     if (timed) ACC_HIP(hipEventRecord(ev[3], stream));
-    if (gather) {
-        launch_permute_rows(plan.d_col_order.p, plan.stats.K, B, plan.b_gathered.p, (int64_t)N * 2, false, stream);
-        B = plan.b_gathered.p;
-    }
+    if (gather) launch_permute_rows(plan.d_col_order.p, plan.n_hot, B, plan.b_hot.p, (int64_t)N * 2, false, stream);
     ExecParams p;
     p.rwo = f.row_window_offset.p;
     p.tco = f.tc_offset.p;
@@ -144,7 +141,10 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     const bool narrow_rows = N >= 32 && N <= 64 && plan.stats.num_tiles >= 16384;
     p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && (dense_tiles || narrow_rows));
     p.N = N;
-    p.wide = plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32);
+    p.B_hot = plan.b_hot.p;
+    p.addr = gather ? kAddrHot
+                    : ((plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32)) ? kAddrWide
+                                                                                                        : kAddrNarrow);
     // Shape of the launch: FPL features per lane (a divisor of N, so that vector loads stay
     // aligned and no lane straddles N, and no wider than N needs), 16*FPL features per slab,
     // one or two slabs per wave, the rest of N over gridDim.y.

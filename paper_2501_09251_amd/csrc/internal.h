@@ -121,6 +121,7 @@ void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowp
 void column_order_on_device(int64_t K, int64_t nnz, const int32_t* d_colidx, DevBuf<int32_t>& d_order,
                             DevBuf<int32_t>& d_rank);
 void remap_columns_on_device(int64_t nnz, const int32_t* d_colidx, const int32_t* d_rank, int32_t* d_out);
+void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot);
 void launch_permute_rows(const int32_t* d_order, int64_t rows, const void* src, void* dst, int64_t row_bytes, bool scatter,
                          hipStream_t stream);
 
@@ -145,11 +146,13 @@ struct Plan {
     mutable std::mutex workspace_mutex;
     mutable DevBuf<float> workspace;
     mutable int32_t workspace_N = 0;
-    // column order (empty when not applied) and the buffer for B gathered into it
+    // column order (empty when not applied); with B in the caller's order, the first n_hot
+    // rows of the order are gathered into b_hot before every execute
     DevBuf<int32_t> d_col_order;
     std::vector<int32_t> col_order, col_rank;
-    mutable DevBuf<uint16_t> b_gathered;
-    mutable int32_t b_gathered_N = 0;
+    int32_t n_hot = 0;
+    mutable DevBuf<uint16_t> b_hot;
+    mutable int32_t b_hot_N = 0;
     // optional CSR copy for the naive baseline
     DevBuf<int32_t> d_rowptr, d_colidx;
     DevBuf<uint16_t> d_vals;

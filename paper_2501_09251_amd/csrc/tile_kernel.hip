@@ -85,19 +85,23 @@ struct TileData {       // what the multiply needs
 // The index arrays are passed as separate const __restrict__ kernel arguments (not inside a
 // struct) so that the compiler knows they are read-only and wave-uniform accesses to them
 // become scalar loads.
-// WIDE = false: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
+// ADDR = kAddrNarrow: B is smaller than 4 GiB and K < 2^24, so a B row's byte offset is formed
 // with one 24-bit multiply in 32 bits and added to the uniform base by the load itself.
+// kAddrWide: 64-bit row offsets.  kAddrHot: a SparseAToB entry h < 0 names row ~h of a second,
+// small matrix (the plan's copy of the most used rows of B, gathered together); entries >= 0 are
+// rows of B as before; 64-bit addresses.
 // TAIL = true: N is not a whole number of this kernel's feature slabs (16*FPL features per slab,
 // NS slabs per wave, gridDim.y waves per item); lanes whose features lie at or beyond N neither
 // load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
 // BF16 = true: the 16-bit values of A and B are bfloat16 instead of IEEE half; only the MFMA
 // instruction differs, the data movement is the same.
-template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL, bool BF16>
+template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
-    const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, float* __restrict__ g_C,
-    float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg, int32_t streaming_stores) {
+    const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, const uint16_t* __restrict__ g_Bhot,
+    float* __restrict__ g_C, float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg,
+    int32_t streaming_stores) {
     constexpr int R = DEPTH + 1;
     constexpr int SW = 16 * FPL;  // features per slab
     struct {
@@ -191,7 +195,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint16_t* row;
-            if constexpr (WIDE) {
+            if constexpr (ADDR == kAddrHot) {
+                const int32_t e = m.cols[q];
+                const bool hot = e < 0;
+                row = (hot ? g_Bhot : p.B) + (size_t)(uint32_t)(hot ? ~e : e) * (size_t)N + f0;
+            } else if constexpr (ADDR == kAddrWide) {
                 row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
             } else {
                 const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
@@ -371,23 +379,27 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     }
 }
 
-template <int FPL, int NS, int DEPTH, bool WIDE, bool COOP, bool TAIL, bool BF16>
+template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16>
 void launch_one(const ExecParams& p, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
     dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
-    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, WIDE, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
-                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.C, p.ws, p.n_items, p.n_blocks, p.N,
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
+                       p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items, p.n_blocks, p.N,
                        p.streaming_stores);
+}
+
+template <int FPL, int NS, int DEPTH, int ADDR, bool TAIL, bool BF16>
+void launch_fetch(const ExecParams& p, hipStream_t stream) {
+    if (p.coop) launch_one<FPL, NS, DEPTH, ADDR, true, TAIL, BF16>(p, stream);
+    else launch_one<FPL, NS, DEPTH, ADDR, false, TAIL, BF16>(p, stream);
 }
 
 template <int FPL, int NS, int DEPTH, bool TAIL, bool BF16>
 void launch_type(const ExecParams& p, hipStream_t stream) {
-    if (p.wide) {
-        if (p.coop) launch_one<FPL, NS, DEPTH, true, true, TAIL, BF16>(p, stream);
-        else launch_one<FPL, NS, DEPTH, true, false, TAIL, BF16>(p, stream);
-    } else {
-        if (p.coop) launch_one<FPL, NS, DEPTH, false, true, TAIL, BF16>(p, stream);
-        else launch_one<FPL, NS, DEPTH, false, false, TAIL, BF16>(p, stream);
+    switch (p.addr) {
+        case kAddrHot: launch_fetch<FPL, NS, DEPTH, kAddrHot, TAIL, BF16>(p, stream); break;
+        case kAddrWide: launch_fetch<FPL, NS, DEPTH, kAddrWide, TAIL, BF16>(p, stream); break;
+        default: launch_fetch<FPL, NS, DEPTH, kAddrNarrow, TAIL, BF16>(p, stream); break;
     }
 }
 

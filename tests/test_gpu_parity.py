@@ -47,12 +47,19 @@ def check_against_oracle(rowptr, colidx, vals, B, C, rows=None, value_type="f16"
     return ratio
 
 
-def check_format(plan, rowptr, colidx, vals, WH=16, TW=16):
+def check_format(plan, rowptr, colidx, vals, WH=16, TW=16, operand_order=0):
     perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
     rank = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_RANK)
     if len(rank):                       # the plan's arrays hold columns in its own column order
         colidx, vals = sorted_rows(rowptr, rank[colidx], vals)
     fmt = oracle.encode(rowptr, colidx, vals, perm, WH, TW)
+    if len(rank) and operand_order == 0:
+        # B in the caller's order: the most used plan columns name rows of the gathered copy
+        # (as ~p), the others the input column
+        order = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_ORDER)
+        H = acc.acc_spmm_plan_stats(plan)["num_hot_columns"]
+        a2b = fmt["sparse_a_to_b"]
+        fmt["sparse_a_to_b"] = np.where(a2b < H, ~a2b, order[a2b]).astype(np.int32)
     for which, key in ((acc.ACC_SPMM_ARR_ROW_WINDOW_OFFSET, "row_window_offset"), (acc.ACC_SPMM_ARR_TC_OFFSET, "tc_offset"),
                        (acc.ACC_SPMM_ARR_SPARSE_A_TO_B, "sparse_a_to_b"), (acc.ACC_SPMM_ARR_TC_LOCAL_BIT, "tc_local_bit"),
                        (acc.ACC_SPMM_ARR_VALUES, "vals")):
@@ -221,7 +228,8 @@ def test_column_order_forced_on(cfg, shrink, operand_order):
         order, rank = oracle.column_order(w.colidx, w.K)
         np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_ORDER), order)
         np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_COL_RANK), rank)
-        check_format(plan, w.rowptr, w.colidx, w.vals)
+        check_format(plan, w.rowptr, w.colidx, w.vals, operand_order=operand_order)
+        assert st["num_hot_columns"] == (min(w.K // 16, 1 << 17) if operand_order == 0 else 0)
         B_plan = _permuted(plan, w.B)
         np.testing.assert_array_equal(B_plan, w.B[order])
         np.testing.assert_array_equal(_permuted(plan, B_plan, to_caller=1), w.B)

@@ -53,6 +53,9 @@ def main() -> int:
     ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
     ap.add_argument("--no-prefetch", action="store_true")
     ap.add_argument("--streaming-stores", action="store_true")
+    ap.add_argument("--mtx", default=None, metavar="FILE",
+                    help="instead of a synthetic workload: A from this Matrix Market file, B = N(0,1) with --mtx-n columns")
+    ap.add_argument("--mtx-n", type=int, default=128)
     ap.add_argument("--column-order", choices=("off", "on", "auto"), default="auto")
     ap.add_argument("--b-in-plan-order", action="store_true",
                     help="hand B over in the plan's column order (permuted once, outside the timed region) "
@@ -82,7 +85,12 @@ def main() -> int:
     mode = {"off": acc.ACC_SPMM_OFF, "on": acc.ACC_SPMM_ON, "auto": acc.ACC_SPMM_AUTO}
 
     t0 = time.time()
-    w = wl.config(args.config, args.shrink)
+    if args.mtx:
+        M, K, rowptr, colidx, vals = acc.read_matrix_market(args.mtx)
+        w = wl.Workload(name=f"{os.path.basename(args.mtx)}-N{args.mtx_n}", M=M, K=K, N=args.mtx_n, rowptr=rowptr,
+                        colidx=colidx, vals=vals, B=wl.dense(K, args.mtx_n, wl.SEED_BASE, "normal", 0.0, 1.0))
+    else:
+        w = wl.config(args.config, args.shrink)
     t_gen = time.time() - t0
     log(f"[bench] workload {w.name}: M={w.M} nnz={w.nnz} N={w.N} generated in {t_gen:.1f}s")
 
@@ -185,7 +193,7 @@ def main() -> int:
         "metric": "SpMM effective GFLOP/s (2·nnz·N/t) + achieved HBM GB/s vs roofline, 1 MI355X",
         "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "synthetic",
+        "dtype": "f16", "data": "A from a user file, B synthetic" if args.mtx else "synthetic",
         "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
                    "reorder": args.reorder, "load_balance": args.load_balance, "column_order": args.column_order,
                    "B_order": "plan" if args.b_in_plan_order else "caller"},

@@ -262,6 +262,28 @@ ACC_SPMM_API int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, i
 ACC_SPMM_API int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst, size_t* bytes);
 
 /*
+ * Matrix Market files (the format of the SuiteSparse and graph collections the paper
+ * evaluates on, Section 4.1) -> the HOST CSR arrays acc_spmm_plan takes.  Host code only; no
+ * GPU is needed.
+ *   acc_spmm_mtx_open   parses `path` ("matrix coordinate", field real / integer / pattern,
+ *                       symmetry general / symmetric / skew-symmetric; the stored triangle
+ *                       of a symmetric file is mirrored, pattern entries get the value 1,
+ *                       entries given twice are summed) and converts the values to
+ *                       value_type (ACC_SPMM_FP16 or ACC_SPMM_BF16, round to nearest even;
+ *                       magnitudes beyond the type's range become infinity).  Returns NULL
+ *                       on failure (acc_spmm_last_error has the reason).
+ *   acc_spmm_mtx_shape  M, K and the number of stored entries (any pointer may be NULL)
+ *   acc_spmm_mtx_csr    copies out rowptr[M+1], colidx[nnz] (ascending inside a row) and
+ *                       vals[nnz]; a NULL array is skipped
+ *   acc_spmm_mtx_close  releases the handle
+ */
+typedef struct acc_spmm_mtx_s acc_spmm_mtx_t;
+ACC_SPMM_API acc_spmm_mtx_t* acc_spmm_mtx_open(const char* path, int32_t value_type);
+ACC_SPMM_API int acc_spmm_mtx_shape(const acc_spmm_mtx_t* mtx, int64_t* M, int64_t* K, int64_t* nnz);
+ACC_SPMM_API int acc_spmm_mtx_csr(const acc_spmm_mtx_t* mtx, int32_t* csr_rowptr, int32_t* csr_colidx, uint16_t* csr_vals);
+ACC_SPMM_API void acc_spmm_mtx_close(acc_spmm_mtx_t* mtx);
+
+/*
  * Measurement aid: a plain streaming copy kernel (16 bytes per lane, grid-stride) that
  * reads `bytes` from src and writes them to dst (both DEVICE, 16-byte aligned, bytes a
  * multiple of 16).  Hardware counters read for it calibrate the counters read for the

@@ -36,6 +36,7 @@ EXPORTED_SYMBOLS = [
     "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
     "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows",
+    "acc_spmm_mtx_open", "acc_spmm_mtx_shape", "acc_spmm_mtx_csr", "acc_spmm_mtx_close",
 ]
 
 
@@ -99,6 +100,14 @@ def load():
     L.acc_spmm_execute.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_execute_timed.restype = ctypes.c_int
     L.acc_spmm_execute_timed.argtypes = [vp, vp, i32, vp, vp] + [ctypes.POINTER(ctypes.c_float)] * 3
+    L.acc_spmm_mtx_open.restype = vp
+    L.acc_spmm_mtx_open.argtypes = [ctypes.c_char_p, i32]
+    L.acc_spmm_mtx_shape.restype = ctypes.c_int
+    L.acc_spmm_mtx_shape.argtypes = [vp] + [ctypes.POINTER(i64)] * 3
+    L.acc_spmm_mtx_csr.restype = ctypes.c_int
+    L.acc_spmm_mtx_csr.argtypes = [vp, vp, vp, vp]
+    L.acc_spmm_mtx_close.restype = None
+    L.acc_spmm_mtx_close.argtypes = [vp]
     L.acc_spmm_permute_rows.restype = ctypes.c_int
     L.acc_spmm_permute_rows.argtypes = [vp, vp, vp, i64, i32, vp]
     L.acc_spmm_execute_csr_naive.restype = ctypes.c_int
@@ -190,6 +199,26 @@ def acc_spmm_execute_timed(plan, B, N, C, stream=None):
                                      ctypes.byref(g)) != 0:
         _raise()
     return t.value, c.value, g.value
+
+
+def read_matrix_market(path, value_type=ACC_SPMM_FP16):
+    """acc_spmm_mtx_open / _shape / _csr / _close in one call: (M, K, rowptr, colidx, vals) as numpy arrays."""
+    L = load()
+    h = L.acc_spmm_mtx_open(os.fsencode(path), value_type)
+    if not h:
+        _raise()
+    try:
+        M, K, nnz = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+        if L.acc_spmm_mtx_shape(h, ctypes.byref(M), ctypes.byref(K), ctypes.byref(nnz)) != 0:
+            _raise()
+        rowptr = np.zeros(M.value + 1, np.int32)
+        colidx = np.zeros(nnz.value, np.int32)
+        vals = np.zeros(nnz.value, np.uint16)
+        if L.acc_spmm_mtx_csr(h, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data) != 0:
+            _raise()
+    finally:
+        L.acc_spmm_mtx_close(h)
+    return M.value, K.value, rowptr, colidx, vals
 
 
 def acc_spmm_permute_rows(plan, src, dst, row_bytes, to_caller=0, stream=None):

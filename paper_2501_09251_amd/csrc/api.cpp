@@ -511,4 +511,26 @@ int acc_spmm_plan_export(const acc_spmm_plan_t* plan, int which, void* host_dst,
     });
 }
 
+acc_spmm_mtx_t* acc_spmm_mtx_open(const char* path, int32_t value_type) {
+    MtxFile* m = nullptr;
+    guarded([&] { m = read_matrix_market(path, value_type); });
+    return reinterpret_cast<acc_spmm_mtx_t*>(m);
+}
+
+int acc_spmm_mtx_shape(const acc_spmm_mtx_t* mtx, int64_t* M, int64_t* K, int64_t* nnz) {
+    return guarded([&] {
+        if (!mtx) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        matrix_market_shape(reinterpret_cast<const MtxFile*>(mtx), M, K, nnz);
+    });
+}
+
+int acc_spmm_mtx_csr(const acc_spmm_mtx_t* mtx, int32_t* csr_rowptr, int32_t* csr_colidx, uint16_t* csr_vals) {
+    return guarded([&] {
+        if (!mtx) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        matrix_market_csr(reinterpret_cast<const MtxFile*>(mtx), csr_rowptr, csr_colidx, csr_vals);
+    });
+}
+
+void acc_spmm_mtx_close(acc_spmm_mtx_t* mtx) { free_matrix_market(reinterpret_cast<MtxFile*>(mtx)); }
+
 }  // extern "C"

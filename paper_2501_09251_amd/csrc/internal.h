@@ -165,7 +165,16 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 
+// mtx.cpp: Matrix Market coordinate file -> host CSR
+struct MtxFile;
+MtxFile* read_matrix_market(const char* path, int32_t value_type);
+void free_matrix_market(MtxFile* m);
+void matrix_market_shape(const MtxFile* m, int64_t* M, int64_t* K, int64_t* nnz);
+void matrix_market_csr(const MtxFile* m, int32_t* rowptr, int32_t* colidx, uint16_t* vals);
+
 }  // namespace accspmm
+
+struct acc_spmm_mtx_s;  // opaque to callers: an accspmm::MtxFile
 
 struct acc_spmm_plan_s {
     accspmm::Plan plan;

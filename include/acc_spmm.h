@@ -118,6 +118,9 @@ typedef struct {
      *    acc_spmm_permute_rows and ACC_SPMM_ARR_COL_ORDER); execute reads it in place.
      * C is in the caller's row order in both cases. */
     int32_t operand_order;
+    /* 1: keep, for every packed value, the index of its CSR entry (4 bytes per entry), which
+     * acc_spmm_sddmm needs.  With operand_order 0 this switches the column order off. */
+    int32_t keep_entry_map;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */
@@ -216,6 +219,23 @@ ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, in
  */
 ACC_SPMM_API int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C,
                                         void* stream, float* tiles_ms, float* combine_ms, float* gather_ms);
+
+/*
+ * Sampled dense-dense product on the plan's sparsity pattern (the companion of SpMM in graph
+ * neural network layers; not an operation of the paper, whose Section 5 names use from GNN
+ * frameworks as the goal): for every stored entry p = (i, j) of A
+ *     out[p] = sum over f < N of X[i][f] * Y[j][f]        (times A's value at p if use_values)
+ * on the matrix cores, fp32 accumulation.  Needs a plan built with keep_entry_map = 1.
+ *   X    DEVICE 16-bit floats (the plan's value_type), row-major M x N, rows in the caller's order
+ *   Y    DEVICE, row-major K x N, rows as acc_spmm_execute takes B (operand_order)
+ *   N    32, 64, 96, 128, or a multiple of 128 up to 4096
+ *   out  DEVICE fp32[nnz], entry p in row-major order with ascending columns inside a row
+ *        (the order of csr_colidx when its rows are sorted)
+ * X and Y 16-byte aligned.  Enqueues two kernels on `stream` and returns; the first call
+ * allocates a buffer of nnz floats in the plan, which calls that overlap in time would share.
+ */
+ACC_SPMM_API int acc_spmm_sddmm(const acc_spmm_plan_t* plan, const void* X, const void* Y, int32_t N, void* out,
+                                int32_t use_values, void* stream);
 
 /*
  * Reorder the rows of a K-row DEVICE matrix between the caller's order and the plan's

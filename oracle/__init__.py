@@ -40,6 +40,8 @@ def _load():
         L.orc_bf16_to_f64.argtypes = [ctypes.c_uint16]
         L.orc_spmm_rows.restype = None
         L.orc_spmm_rows.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp]
+        L.orc_sddmm.restype = None
+        L.orc_sddmm.argtypes = [i64, i64, vp, vp, vp, vp, vp, vp, vp, ctypes.c_int]
         L.orc_spmm_rows_typed.restype = None
         L.orc_spmm_rows_typed.argtypes = [i64, vp, i64, vp, vp, vp, vp, vp, vp, ctypes.c_int]
         L.orc_encode.restype = i64
@@ -83,6 +85,20 @@ def spmm(rowptr, colidx, vals, B, rows=None, want_bound=True, value_type="f16"):
     _load().orc_spmm_rows_typed(n, rp, N, _p(rowptr), _p(colidx), _p(vals), _p(B), _p(C), _p(bound),
                                 {"f16": 0, "bf16": 1}[value_type])
     return C, bound
+
+
+def sddmm(rowptr, colidx, X, Y, vals=None, value_type="f16"):
+    """fp64 out[p] = (vals[p] if given) * <X[i_p], Y[j_p]> for every stored entry p, and
+    bound[p] = |vals[p]| * <|X[i_p]|, |Y[j_p]|>.  X: M x N, Y: K x N bit patterns."""
+    rowptr, colidx, X, Y = _i32(rowptr), _i32(colidx), _u16(X), _u16(Y)
+    vals = None if vals is None else _u16(vals)
+    M, N = len(rowptr) - 1, X.shape[1]
+    assert X.shape[0] == M and Y.shape[1] == N
+    out = np.empty(len(colidx), np.float64)
+    bound = np.empty(len(colidx), np.float64)
+    _load().orc_sddmm(M, N, _p(rowptr), _p(colidx), _p(vals), _p(X), _p(Y), _p(out), _p(bound),
+                      {"f16": 0, "bf16": 1}[value_type])
+    return out, bound
 
 
 def encode(rowptr, colidx, vals, perm=None, WH=16, TW=16):

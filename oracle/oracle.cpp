@@ -106,6 +106,31 @@ void orc_spmm_rows(int64_t nrows, const int64_t* rows, int64_t N, const int32_t*
     orc_spmm_rows_typed(nrows, rows, N, rowptr, colidx, vals, B, C, bound, 0);
 }
 
+// Sampled dense-dense product: for every stored entry p = (i, j) of the pattern,
+// out[p] = scale_p * sum_f X[i][f] * Y[j][f] in fp64, with scale_p = the entry's value if
+// `vals` is given, else 1; bound[p] = |scale_p| * sum_f |X[i][f]| * |Y[j][f]| (may be null).
+// X is M x N, Y is K x N, both row-major bit patterns of `value_type`.  (Not an operation of
+// the paper; the definition is the standard one of the SpMM / SDDMM pair of GNN layers.)
+void orc_sddmm(int64_t M, int64_t N, const int32_t* rowptr, const int32_t* colidx, const uint16_t* vals,
+               const uint16_t* X, const uint16_t* Y, double* out, double* bound, int value_type) {
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = 0; i < M; ++i) {
+        const uint16_t* x = X + i * N;
+        for (int64_t p = rowptr[i]; p < rowptr[i + 1]; ++p) {
+            const uint16_t* y = Y + (int64_t)colidx[p] * N;
+            double dot = 0.0, mag = 0.0;
+            for (int64_t f = 0; f < N; ++f) {
+                const double a = widen(x[f], value_type), b = widen(y[f], value_type);
+                dot += a * b;
+                mag += std::fabs(a) * std::fabs(b);
+            }
+            const double scale = vals ? widen(vals[p], value_type) : 1.0;
+            out[p] = scale * dot;
+            if (bound) bound[p] = std::fabs(scale) * mag;
+        }
+    }
+}
+
 void orc_spmm(int64_t M, int64_t N, const int32_t* rowptr, const int32_t* colidx, const uint16_t* vals,
               const uint16_t* B, double* C, double* bound) {
     orc_spmm_rows(M, nullptr, N, rowptr, colidx, vals, B, C, bound);

@@ -119,6 +119,12 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     }
     if (opt.column_order < 0 || opt.column_order > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "column_order must be OFF, ON or AUTO");
     if (opt.operand_order < 0 || opt.operand_order > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "operand_order must be 0 or 1");
+    if (opt.keep_entry_map && opt.operand_order == 0) {
+        // sddmm reads rows of Y by SparseAToB alone, so the two-matrix form of a column order is not available
+        if (opt.column_order == ACC_SPMM_ON)
+            fail(ACC_SPMM_ERR_UNSUPPORTED, "keep_entry_map with column_order ON needs operand_order = 1");
+        opt.column_order = ACC_SPMM_OFF;
+    }
     if (opt.reorder < 0 || opt.reorder > 2 || opt.load_balance < 0 || opt.load_balance > 2)
         fail(ACC_SPMM_ERR_INVALID_ARG, "reorder / load_balance must be OFF, ON or AUTO");
     if (opt.window_height == 0) opt.window_height = 16;
@@ -247,7 +253,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         // ---- format ----
         const double e0 = now_s();
         encode_on_device(M, K, nnz, P.d_rowptr.p, use_col_order ? d_colidx_plan.p : P.d_colidx.p, P.d_vals.p, d_perm.p, WH,
-                         TW, P.fmt, false);
+                         TW, P.fmt, false, opt.keep_entry_map ? &P.d_entry_of : nullptr);
         const double t_encode = now_s() - e0;
         // the comparison kernel reads B as execute is given it
         if (use_col_order && opt.operand_order == 1 && opt.keep_csr) P.d_colidx.swap(d_colidx_plan);
@@ -365,6 +371,14 @@ int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N
     return guarded([&] {
         if (!plan || !C || !tiles_ms || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
         launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), tiles_ms, combine_ms, gather_ms);
+    });
+}
+
+int acc_spmm_sddmm(const acc_spmm_plan_t* plan, const void* X, const void* Y, int32_t N, void* out, int32_t use_values,
+                   void* stream) {
+    return guarded([&] {
+        if (!plan || ((!X || !Y || !out) && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_sddmm(plan->plan, X, Y, N, out, use_values != 0, static_cast<hipStream_t>(stream));
     });
 }
 

@@ -135,7 +135,8 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(int64_t M, const in
                                                              const int32_t* __restrict__ tile_of,
                                                              const uint16_t* __restrict__ bit_of,
                                                              const uint64_t* __restrict__ bits, int32_t NW,
-                                                             const int32_t* __restrict__ tco, uint16_t* __restrict__ packed) {
+                                                             const int32_t* __restrict__ tco, uint16_t* __restrict__ packed,
+                                                             int32_t* __restrict__ entry_of) {
     int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (r >= M) return;
     const int lane = threadIdx.x & 63;
@@ -148,6 +149,7 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(int64_t M, const in
         for (int q = 0; q < (bit >> 6); ++q) rank += __popcll(bm[q]);
         rank += __popcll(bm[bit >> 6] & ((1ull << (bit & 63)) - 1ull));
         packed[tco[g] + rank] = vals[src + k];
+        if (entry_of) entry_of[tco[g] + rank] = src + k;  // which CSR entry sits at this packed position
     }
 }
 
@@ -155,7 +157,7 @@ __global__ __launch_bounds__(256) void scatter_values_kernel(int64_t M, const in
 
 void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,
                       const uint16_t* d_vals, const int32_t* d_perm, int32_t WH, int32_t TW, DeviceFormat& out,
-                      bool tiles_only) {
+                      bool tiles_only, DevBuf<int32_t>* entry_of) {
     const int64_t W = (M + WH - 1) / WH;
     const int32_t NW = (WH * TW + 63) / 64;
     out.WH = WH; out.TW = TW; out.NW = NW; out.M = M; out.W = W; out.nnz = nnz; out.T = 0; out.sum_dw = 0;
@@ -261,8 +263,10 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
     // 8. values (8 halves of zero padding: the runtime kernel reads up to 4 past a tile's end)
     out.vals.alloc(nnz + 8);
     ACC_HIP(hipMemset(out.vals.p + nnz, 0, 16));
+    if (entry_of) entry_of->alloc(nnz);
     hipLaunchKernelGGL(scatter_values_kernel, dim3(blocks_for(M, 4)), dim3(256), 0, 0, M, d_rowptr, d_vals, d_perm,
-                       new_rowptr.p, tile_of.p, bit_of.p, out.tc_local_bit.p, NW, out.tc_offset.p, out.vals.p);
+                       new_rowptr.p, tile_of.p, bit_of.p, out.tc_local_bit.p, NW, out.tc_offset.p, out.vals.p,
+                       entry_of ? entry_of->p : nullptr);
     ACC_HIP(hipGetLastError());
     ACC_HIP(hipDeviceSynchronize());
 }

@@ -79,10 +79,11 @@ struct DeviceFormat {
     DevBuf<uint16_t> vals;              // nnz (+ padding so that 4 halves past the end are readable)
 };
 
-// encode.hip: CSR (device) + perm (device, new->old, M entries) -> DeviceFormat.
+// encode.hip: CSR (device) + perm (device, new->old, M entries) -> DeviceFormat.  entry_of
+// (optional) gets, for every packed value position, the index of its CSR entry.
 void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx,
                       const uint16_t* d_vals, const int32_t* d_perm, int32_t WH, int32_t TW, DeviceFormat& out,
-                      bool tiles_only);
+                      bool tiles_only, DevBuf<int32_t>* entry_of = nullptr);
 
 // Symmetric adjacency of the pattern graph in (pinned) host memory: vertex i's neighbours,
 // ascending, without i itself, are adj[ptr[i] .. ptr[i+1]).
@@ -153,6 +154,10 @@ struct Plan {
     int32_t n_hot = 0;
     mutable DevBuf<uint16_t> b_hot;
     mutable int32_t b_hot_N = 0;
+    // optional: CSR entry index of every packed value (for sddmm), and sddmm's results in packed
+    // order before they are moved to entry order (allocated by the first sddmm call)
+    DevBuf<int32_t> d_entry_of;
+    mutable DevBuf<float> sddmm_packed;
     // optional CSR copy for the naive baseline
     DevBuf<int32_t> d_rowptr, d_colidx;
     DevBuf<uint16_t> d_vals;
@@ -164,6 +169,9 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
                     float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr);
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
+// sddmm.hip
+void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, void* out, int32_t use_values,
+                  hipStream_t stream);
 
 // mtx.cpp: Matrix Market coordinate file -> host CSR
 struct MtxFile;

@@ -90,6 +90,31 @@ def main() -> int:
                           "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"],
                           "column_order_applied": st["column_order_applied"]}),
               flush=True)
+    # --- sampled dense-dense product on the same pattern (N = 64 and 128 features)
+    plan = plan_with(keep_entry_map=1)
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        out = torch.empty(max(w.nnz, 1), dtype=torch.float32, device=dev)
+        for N in (64, 128):
+            X = torch.randint(-15000, 15000, (w.M, N), dtype=torch.int16, device=dev)
+            Y = torch.randint(-15000, 15000, (w.K, N), dtype=torch.int16, device=dev)
+            for _ in range(2):
+                acc.acc_spmm_sddmm(plan, X, Y, N, out, 1, stream)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                acc.acc_spmm_sddmm(plan, X, Y, N, out, 1, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            # rows of Y gathered per window, X once, results and their entry map, the format's index arrays
+            alg = st["sum_distinct_cols"] * N * 2 + w.M * N * 2 + 8 * w.nnz + 2 * w.nnz + st["index_bytes"]
+            print(json.dumps({"report": "sddmm", "workload": w.name, "N": N, "ms": ms,
+                              "gflops": 2.0 * w.nnz * N / (ms * 1e-3) / 1e9, "algorithmic_bytes": alg,
+                              "GBps": alg / (ms * 1e-3) / 1e9, "frac_of_8TBps": alg / (ms * 1e-3) / 8e12}), flush=True)
+            del X, Y
+    finally:
+        acc.acc_spmm_destroy(plan)
     return 0
 
 

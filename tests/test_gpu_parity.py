@@ -282,6 +282,110 @@ def test_column_order_auto_detects_hubs_at_power_of_two_labels():
     assert on == 0 and skew < 2.5
 
 
+# ------------------------------------------------------------------ sampled dense-dense product
+def run_sddmm(plan, X_u16, Y_u16, nnz, N, use_values):
+    dev = torch.device("cuda:0")
+    Xd = torch.from_numpy(X_u16.view(np.int16)).to(dev)
+    Yd = torch.from_numpy(Y_u16.view(np.int16)).to(dev)
+    guard = 1024
+    buf = torch.full((nnz + guard,), float("nan"), dtype=torch.float32, device=dev)   # every entry must be written
+    buf[nnz:] = 12345.0
+    acc.acc_spmm_sddmm(plan, Xd, Yd, N, buf, use_values, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool((buf[nnz:] == 12345.0).all()), "wrote past the end of out"
+    return buf[:nnz].cpu().numpy()
+
+
+def check_sddmm(rowptr, colidx, vals, X, Y, got, use_values, value_type="f16"):
+    ref, bound = oracle.sddmm(rowptr, colidx, X, Y, vals if use_values else None, value_type=value_type)
+    ok, ratio = oracle.within_bound(got, ref, bound)
+    assert ok, f"outside tolerance, worst error/limit = {ratio}"
+
+
+@pytest.mark.parametrize("N", [32, 64, 96, 128, 256, 512])
+@pytest.mark.parametrize("lb,use_values", [(acc.ACC_SPMM_OFF, 0), (acc.ACC_SPMM_ON, 1)])
+def test_sddmm_all_widths(N, lb, use_values):
+    rng = np.random.default_rng(N + lb)
+    M, K = 333, 500                                    # ragged last window, a window split by the balancer,
+    rowptr, colidx, _ = random_csr(rng, M, K, 0.04)    # empty rows and (rows 64..95) three empty windows in a row
+    rows = [colidx[rowptr[i]:rowptr[i + 1]].tolist() for i in range(M)]
+    rows[40] = np.sort(rng.choice(K, 450, replace=False)).tolist()
+    for i in range(64, 112):
+        rows[i] = []
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    X, Y = f16(rng.standard_normal((M, N))), f16(rng.standard_normal((K, N)))
+    plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                acc.make_options(load_balance=lb, max_tiles_per_item=8, keep_entry_map=1))
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        assert (st["num_split_windows"] >= 1) == (lb == acc.ACC_SPMM_ON)
+        got = run_sddmm(plan, X, Y, len(colidx), N, use_values)
+        check_sddmm(rowptr, colidx, vals, X, Y, got, use_values)
+        np.testing.assert_array_equal(got, run_sddmm(plan, X, Y, len(colidx), N, use_values))   # repeatable
+        # the same plan still does SpMM
+        C = run_spmm(plan, Y, M, N)
+        check_against_oracle(rowptr, colidx, vals, Y, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(2, 6), (4, 4), (3, 6), (5, 7)])
+def test_sddmm_on_the_workloads_reordered(cfg, shrink):
+    """Row reordering on (where AUTO takes it): out stays in the caller's entry order."""
+    w = wl.config(cfg, shrink)
+    X = wl.dense(w.M, 64, 3, "normal", 0.0, 1.0)
+    Y = wl.dense(w.K, 64, 4, "normal", 0.0, 1.0)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(reorder=acc.ACC_SPMM_ON, keep_entry_map=1))
+    try:
+        got = run_sddmm(plan, X, Y, w.nnz, 64, 1)
+        check_sddmm(w.rowptr, w.colidx, w.vals, X, Y, got, 1)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_sddmm_bf16_and_column_order_in_plan_order():
+    rng = np.random.default_rng(5)
+    w = wl.config(2, 6)
+    vals = bf16(rng.uniform(-1, 1, w.nnz))
+    X, Y = bf16(rng.standard_normal((w.M, 128)) * 100.0), bf16(rng.standard_normal((w.K, 128)) * 0.01)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, vals,
+                                acc.make_options(value_type=acc.ACC_SPMM_BF16, keep_entry_map=1,
+                                                 column_order=acc.ACC_SPMM_ON, operand_order=1))
+    try:
+        assert acc.acc_spmm_plan_stats(plan)["column_order_applied"] == 1
+        got = run_sddmm(plan, X, _permuted(plan, Y), w.nnz, 128, 1)      # Y in the plan's order, as B would be
+        check_sddmm(w.rowptr, w.colidx, vals, X, Y, got, 1, value_type="bf16")
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_sddmm_argument_errors():
+    rowptr, colidx, vals = csr_from_rows([[0]])
+    X = torch.zeros(1, 48, dtype=torch.float16, device="cuda")
+    out = torch.zeros(1, device="cuda")
+    plan = acc.acc_spmm_plan(1, 1, 1, rowptr, colidx, vals)
+    try:
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_sddmm(plan, X, X, 32, out)                       # built without keep_entry_map
+        assert e.value.code == -1
+    finally:
+        acc.acc_spmm_destroy(plan)
+    plan = acc.acc_spmm_plan_ex(1, 1, 1, rowptr, colidx, vals, acc.make_options(keep_entry_map=1))
+    try:
+        for bad_N in (0, 48, 160, 8192):
+            with pytest.raises(acc.AccSpmmError) as e:
+                acc.acc_spmm_sddmm(plan, X, X, bad_N, out)
+            assert e.value.code == -3
+    finally:
+        acc.acc_spmm_destroy(plan)
+    with pytest.raises(acc.AccSpmmError) as e:                            # the two-matrix column order cannot serve sddmm
+        acc.acc_spmm_plan_ex(1, 1, 1, rowptr, colidx, vals,
+                             acc.make_options(keep_entry_map=1, column_order=acc.ACC_SPMM_ON))
+    assert e.value.code == -3
+
+
 def test_identity_and_permutation_matrices_are_exact():
     rng = np.random.default_rng(0)
     n, N = 100, 64

@@ -24,6 +24,9 @@ MUTATIONS = {
     "bf16 exponent bias": ("std::ldexp((double)(f + 128), e - 134)", "std::ldexp((double)(f + 128), e - 133)"),
     "bf16 subnormal scale": ("std::ldexp((double)f, -133)", "std::ldexp((double)f, -134)"),
     "bf16 read as fp16": ("return value_type == 1 ? bf2d(h) : h2d(h);", "return h2d(h);"),
+    "sddmm takes the Y row from the row index": ("const uint16_t* y = Y + (int64_t)colidx[p] * N;", "const uint16_t* y = Y + (int64_t)(i % 3) * N;"),
+    "sddmm bound drops the absolute values": ("mag += std::fabs(a) * std::fabs(b);\n            }\n            const double scale",
+                                              "mag += a * b;\n            }\n            const double scale"),
     "padding repeats the first column": ("cols[std::min<int64_t>(t * TW + c, d - 1)]", "cols[(t * TW + c < d) ? t * TW + c : 0]"),
     "bit index transposed": ("int bit = (int)((r - r0) * TW + cc % TW);\n                    uint64_t& word",
                              "int bit = (int)((cc % TW) * WH + (r - r0));\n                    uint64_t& word"),
@@ -89,6 +92,13 @@ def _pins(orc, lit):
     Ad[mask] = bf16_to_f64(a_bits)
     C, _ = orc.spmm(rowptr, colidx, a_bits, b_bits, value_type="bf16")
     np.testing.assert_allclose(C, Ad @ bf16_to_f64(b_bits), atol=1e-13)
+    # sampled dense-dense product against a masked dense matmul (X is M x N, Y is K x N)
+    Xf = rng.uniform(-1, 1, (M, 6)).astype(np.float16)
+    Yf = rng.uniform(-1, 1, (K, 6)).astype(np.float16)
+    sd, sb = orc.sddmm(rowptr, colidx, Xf.view(np.uint16), Yf.view(np.uint16), vals)
+    np.testing.assert_allclose(sd, (Xf.astype(np.float64) @ Yf.astype(np.float64).T)[mask] * A[mask].astype(np.float64), atol=1e-13)
+    np.testing.assert_allclose(sb, (np.abs(Xf).astype(np.float64) @ np.abs(Yf).astype(np.float64).T)[mask]
+                               * np.abs(A[mask]).astype(np.float64), atol=1e-13)
     # format: hand-worked example, closed form, literal transcription, round trip
     g = load_golden("format_8x8_toy.json")
     rowptr, colidx, vals = csr_from_rows(g["rows"])

@@ -151,3 +151,45 @@ def test_within_bound_accepts_and_rejects():
     assert not ok and ratio > 1
     ok, _ = oracle.within_bound(np.array([[np.nan, -2.0]], np.float32), C_ref, bound)
     assert not ok
+
+
+# ------------------------------------------------------------------ sampled dense-dense product
+@pytest.mark.parametrize("use_values", [False, True])
+def test_sddmm_matches_masked_numpy_matmul(use_values):
+    # non-square, N differs from both: a swapped operand or index cannot survive this
+    rng = np.random.default_rng(11)
+    M, K, N = 7, 13, 5
+    mask = rng.random((M, K)) < 0.4
+    rows = [np.nonzero(mask[i])[0].tolist() for i in range(M)]
+    a = rng.uniform(-2, 2, int(mask.sum())).astype(np.float16)
+    rowptr, colidx, vals = csr_from_rows(rows, a)
+    X = rng.uniform(-1, 1, (M, N)).astype(np.float16)
+    Y = rng.uniform(-1, 1, (K, N)).astype(np.float16)
+    out, bound = oracle.sddmm(rowptr, colidx, X.view(np.uint16), Y.view(np.uint16), vals if use_values else None)
+    full = X.astype(np.float64) @ Y.astype(np.float64).T
+    mag = np.abs(X).astype(np.float64) @ np.abs(Y).astype(np.float64).T
+    scale = a.astype(np.float64) if use_values else np.ones(len(a))
+    np.testing.assert_allclose(out, full[mask] * scale, atol=1e-13)       # row-major order of the mask = CSR order
+    np.testing.assert_allclose(bound, mag[mask] * np.abs(scale), atol=1e-13)
+
+
+def test_sddmm_with_one_hot_rows_picks_single_products():
+    # X[i] = e_i scaled, Y[j] = e_j scaled over N = max(M, K) features: <X_i, Y_j> = s_i t_i if i == j else 0
+    n = 9
+    rowptr, colidx, _ = csr_from_rows([sorted([i, (i + 1) % n]) for i in range(n)])
+    s_, t_ = np.arange(1, n + 1, dtype=np.float64), np.arange(2, n + 2, dtype=np.float64)
+    X, Y = np.diag(s_).astype(np.float16), np.diag(t_).astype(np.float16)
+    out, _ = oracle.sddmm(rowptr, colidx, X.view(np.uint16), Y.view(np.uint16))
+    expect = np.array([s_[i] * t_[i] if j == i else 0.0 for i in range(n) for j in sorted([i, (i + 1) % n])])
+    np.testing.assert_array_equal(out, expect)
+
+
+def test_sddmm_bf16_reads_both_operands_as_bf16():
+    rng = np.random.default_rng(12)
+    M, K, N = 6, 8, 4
+    rowptr, colidx, _ = csr_from_rows([[int(c) for c in sorted(rng.choice(K, 3, replace=False))] for _ in range(M)])
+    xb, yb = bf16(rng.standard_normal((M, N)) * 1e5), bf16(rng.standard_normal((K, N)) * 1e-5)
+    out, _ = oracle.sddmm(rowptr, colidx, xb, yb, value_type="bf16")
+    full = bf16_to_f64(xb) @ bf16_to_f64(yb).T
+    rows = np.repeat(np.arange(M), 3)
+    np.testing.assert_allclose(out, full[rows, colidx], rtol=1e-14)

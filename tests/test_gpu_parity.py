@@ -587,3 +587,34 @@ def test_full_size_sampled_rows(cfg):
         print(f"[full-size] worst error/limit = {ratio:.3g}", flush=True)
     finally:
         acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg", [2, 5])
+def test_full_size_sddmm_sampled_rows(cfg):
+    """acc_spmm_sddmm at the benchmark's sizes; every entry of a sample of rows against the oracle."""
+    print(f"[full-size sddmm] generating workload {cfg}", flush=True)
+    w = wl.config(cfg, with_B=False)
+    N = 64
+    X = wl.dense(w.M, N, 21, "normal", 0.0, 1.0)
+    Y = wl.dense(w.K, N, 22, "normal", 0.0, 1.0)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(reorder=acc.ACC_SPMM_OFF, keep_entry_map=1))
+    try:
+        print("[full-size sddmm] executing", flush=True)
+        got = run_sddmm(plan, X, Y, w.nnz, N, 1)
+        assert np.isfinite(got).all()
+        rng = np.random.default_rng(cfg)
+        deg = np.diff(w.rowptr)
+        rows = np.unique(np.concatenate([rng.integers(0, w.M, 3000), np.argsort(deg)[-8:], np.arange(48),
+                                         np.arange(w.M - 48, w.M)]))
+        # the sampled rows as a matrix of their own (same columns), so that the oracle computes only them
+        sub_len = deg[rows]
+        sub_rowptr = np.concatenate([[0], np.cumsum(sub_len)]).astype(np.int32)
+        pick = np.concatenate([np.arange(w.rowptr[r], w.rowptr[r + 1]) for r in rows])
+        print(f"[full-size sddmm] checking {len(pick)} entries of {len(rows)} rows against the oracle", flush=True)
+        ref, bound = oracle.sddmm(sub_rowptr, w.colidx[pick], X[rows], Y, w.vals[pick])
+        ok, ratio = oracle.within_bound(got[pick], ref, bound)
+        print(f"[full-size sddmm] worst error/limit = {ratio:.3g}", flush=True)
+        assert ok
+    finally:
+        acc.acc_spmm_destroy(plan)

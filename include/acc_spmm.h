@@ -119,7 +119,7 @@ typedef struct {
      * C is in the caller's row order in both cases. */
     int32_t operand_order;
     /* 1: keep, for every packed value, the index of its CSR entry (4 bytes per entry), which
-     * acc_spmm_sddmm needs.  With operand_order 0 this switches the column order off. */
+     * acc_spmm_sddmm needs. */
     int32_t keep_entry_map;
 } acc_spmm_options;
 
@@ -227,7 +227,8 @@ ACC_SPMM_API int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void*
  *     out[p] = sum over f < N of X[i][f] * Y[j][f]        (times A's value at p if use_values)
  * on the matrix cores, fp32 accumulation.  Needs a plan built with keep_entry_map = 1.
  *   X    DEVICE 16-bit floats (the plan's value_type), row-major M x N, rows in the caller's order
- *   Y    DEVICE, row-major K x N, rows as acc_spmm_execute takes B (operand_order)
+ *   Y    DEVICE, row-major K x N, rows as acc_spmm_execute takes B (operand_order; in the
+ *        caller's order the most used rows are gathered first, as for B)
  *   N    32, 64, 96, 128, or a multiple of 128 up to 4096
  *   out  DEVICE fp32[nnz], entry p in row-major order with ascending columns inside a row
  *        (the order of csr_colidx when its rows are sorted)

@@ -119,12 +119,6 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     }
     if (opt.column_order < 0 || opt.column_order > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "column_order must be OFF, ON or AUTO");
     if (opt.operand_order < 0 || opt.operand_order > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "operand_order must be 0 or 1");
-    if (opt.keep_entry_map && opt.operand_order == 0) {
-        // sddmm reads rows of Y by SparseAToB alone, so the two-matrix form of a column order is not available
-        if (opt.column_order == ACC_SPMM_ON)
-            fail(ACC_SPMM_ERR_UNSUPPORTED, "keep_entry_map with column_order ON needs operand_order = 1");
-        opt.column_order = ACC_SPMM_OFF;
-    }
     if (opt.reorder < 0 || opt.reorder > 2 || opt.load_balance < 0 || opt.load_balance > 2)
         fail(ACC_SPMM_ERR_INVALID_ARG, "reorder / load_balance must be OFF, ON or AUTO");
     if (opt.window_height == 0) opt.window_height = 16;

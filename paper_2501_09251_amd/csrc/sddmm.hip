@@ -36,12 +36,14 @@ typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 // PASSES > 0: that many passes, the window's rows of X stay in registers and the rows of Y are
 // double-buffered pass by pass.  PASSES == 0: any number of passes (`passes`), X and Y re-read
 // per tile and pass, no prefetch (very wide rows).
-template <int NV, int PASSES, bool BF16>
+// HOT: SparseAToB entries e < 0 name row ~e of Y_hot, the plan's gathered copy of the most used
+// rows of Y (the plan has a column order and Y comes in the caller's order); e >= 0 are rows of Y.
+template <int NV, int PASSES, bool BF16, bool HOT>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
     const int32_t* __restrict__ rwo, const int32_t* __restrict__ tco, const int32_t* __restrict__ a2b,
     const uint64_t* __restrict__ bits, const int32_t* __restrict__ perm_pad, const WorkItem* __restrict__ items,
-    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Y, float* __restrict__ packed_out, int32_t n_items,
-    int32_t n_blocks, int32_t N, int32_t passes) {
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Y, const uint16_t* __restrict__ Y_hot,
+    float* __restrict__ packed_out, int32_t n_items, int32_t n_blocks, int32_t N, int32_t passes) {
     const int lane = threadIdx.x & 63;
     const int g = lane >> 4, c = lane & 15;
     const int per_xcd = (n_blocks + 7) >> 3;
@@ -61,6 +63,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
         const uint16_t* p = base + (size_t)(uint32_t)row * (size_t)N + pass * (NV * 32) + g * 8;
 #pragma unroll
         for (int v = 0; v < NV; ++v) dst[v] = *reinterpret_cast<const uintx4*>(p + v * 32);
+    };
+    auto load_y = [&](int32_t e, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
+        if constexpr (HOT) {
+            const bool hot = e < 0;
+            load_row(hot ? Y_hot : Y, hot ? ~e : e, pass, dst);
+        } else {
+            load_row(Y, e, pass, dst);
+        }
     };
     auto contract = [&](const uintx4 (&x)[NV], const uintx4 (&y)[NV], floatx4& acc) __attribute__((always_inline)) {
 #pragma unroll
@@ -111,13 +121,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
         load_window();
         // column ids are requested one tile further ahead than the rows they address
         int32_t col_after = a2b[(size_t)(tb + 1 < te ? tb + 1 : tb) * 16 + c];
-        load_row(Y, a2b[(size_t)tb * 16 + c], 0, y0);
+        load_y(a2b[(size_t)tb * 16 + c], 0, y0);
         TileWords words_next = load_words(tb);
         auto tile_step = [&](int t, const uintx4 (&y_cur)[NV], uintx4 (&y_next)[NV]) __attribute__((always_inline)) {
             const TileWords words = words_next;
             words_next = load_words(t + 1 < te ? t + 1 : t);
             const int32_t col_ahead = a2b[(size_t)(t + 2 < te ? t + 2 : te - 1) * 16 + c];
-            if (t + 1 < te) load_row(Y, col_after, 0, y_next);
+            if (t + 1 < te) load_y(col_after, 0, y_next);
             col_after = col_ahead;
             if (t == wend) {  // the previous tile closed its window: move to the window of tile t
                 do { ++w; wend = rwo[w + 1]; } while (wend <= t);
@@ -147,7 +157,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
         int32_t col_cur = a2b[(size_t)tb * 16 + c];
         int32_t col_next = a2b[(size_t)(tb + 1 < te ? tb + 1 : tb) * 16 + c];
         int32_t col_ahead = col_next;
-        load_row(Y, col_cur, 0, y0);
+        load_y(col_cur, 0, y0);
         TileWords words = load_words(tb), words_next = words;
         floatx4 acc{0.f, 0.f, 0.f, 0.f};
         int t = tb, p = 0;  // the step being contracted: pass p of tile t
@@ -165,8 +175,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
                 }
             }
             const bool last_pass = p == PASSES - 1;
-            if (!last_pass) load_row(Y, col_cur, p + 1, y_next);
-            else if (t + 1 < te) load_row(Y, col_next, 0, y_next);
+            if (!last_pass) load_y(col_cur, p + 1, y_next);
+            else if (t + 1 < te) load_y(col_next, 0, y_next);
 #pragma unroll
             for (int pp = 0; pp < PASSES; ++pp)
                 if (pp == p) contract(x[pp], y_cur, acc);
@@ -198,7 +208,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
 #pragma unroll
                 for (int v = 0; v < NV; ++v) x[v] = uintx4{0u, 0u, 0u, 0u};
                 if (row >= 0) load_row(X, row, pass, x);
-                load_row(Y, col, pass, y);
+                load_y(col, pass, y);
                 contract(x, y, acc);
             }
             emit(load_words(t), acc);
@@ -223,30 +233,35 @@ __global__ __launch_bounds__(256) void sddmm_finish_kernel(int64_t nnz, const fl
 }
 
 template <int NV, int PASSES, bool BF16>
-void launch_nv(const Plan& plan, const uint16_t* X, const uint16_t* Y, int32_t N, int32_t passes, float* packed_out,
-               hipStream_t stream) {
+void launch_nv(const Plan& plan, const uint16_t* X, const uint16_t* Y, const uint16_t* Y_hot, int32_t N, int32_t passes,
+               float* packed_out, hipStream_t stream) {
     const DeviceFormat& f = plan.fmt;
     const int32_t n_items = (int32_t)plan.items.size();
     const int32_t n_blocks = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     const int blocks = ((n_blocks + 7) / 8) * 8;
-    hipLaunchKernelGGL((sddmm_tiles_kernel<NV, PASSES, BF16>), dim3(blocks), dim3(kWavesPerBlock * 64), 0, stream,
-                       f.row_window_offset.p, f.tc_offset.p, f.sparse_a_to_b.p, f.tc_local_bit.p, plan.d_perm_pad.p,
-                       plan.d_items.p, X, Y, packed_out, n_items, n_blocks, N, passes);
+    if (Y_hot)
+        hipLaunchKernelGGL((sddmm_tiles_kernel<NV, PASSES, BF16, true>), dim3(blocks), dim3(kWavesPerBlock * 64), 0, stream,
+                           f.row_window_offset.p, f.tc_offset.p, f.sparse_a_to_b.p, f.tc_local_bit.p, plan.d_perm_pad.p,
+                           plan.d_items.p, X, Y, Y_hot, packed_out, n_items, n_blocks, N, passes);
+    else
+        hipLaunchKernelGGL((sddmm_tiles_kernel<NV, PASSES, BF16, false>), dim3(blocks), dim3(kWavesPerBlock * 64), 0,
+                           stream, f.row_window_offset.p, f.tc_offset.p, f.sparse_a_to_b.p, f.tc_local_bit.p,
+                           plan.d_perm_pad.p, plan.d_items.p, X, Y, Y_hot, packed_out, n_items, n_blocks, N, passes);
 }
 
 template <bool BF16>
-void launch_typed(const Plan& plan, const uint16_t* X, const uint16_t* Y, int32_t N, float* out, int32_t use_values,
-                  hipStream_t stream) {
+void launch_typed(const Plan& plan, const uint16_t* X, const uint16_t* Y, const uint16_t* Y_hot, int32_t N, float* out,
+                  int32_t use_values, hipStream_t stream) {
     float* packed = plan.sddmm_packed.p;
     switch (N) {
-        case 32: launch_nv<1, 1, BF16>(plan, X, Y, N, 1, packed, stream); break;
-        case 64: launch_nv<2, 1, BF16>(plan, X, Y, N, 1, packed, stream); break;
-        case 96: launch_nv<3, 1, BF16>(plan, X, Y, N, 1, packed, stream); break;
-        case 128: launch_nv<4, 1, BF16>(plan, X, Y, N, 1, packed, stream); break;
-        case 256: launch_nv<4, 2, BF16>(plan, X, Y, N, 2, packed, stream); break;
-        case 384: launch_nv<4, 3, BF16>(plan, X, Y, N, 3, packed, stream); break;
-        case 512: launch_nv<4, 4, BF16>(plan, X, Y, N, 4, packed, stream); break;
-        default: launch_nv<4, 0, BF16>(plan, X, Y, N, N / 128, packed, stream); break;
+        case 32: launch_nv<1, 1, BF16>(plan, X, Y, Y_hot, N, 1, packed, stream); break;
+        case 64: launch_nv<2, 1, BF16>(plan, X, Y, Y_hot, N, 1, packed, stream); break;
+        case 96: launch_nv<3, 1, BF16>(plan, X, Y, Y_hot, N, 1, packed, stream); break;
+        case 128: launch_nv<4, 1, BF16>(plan, X, Y, Y_hot, N, 1, packed, stream); break;
+        case 256: launch_nv<4, 2, BF16>(plan, X, Y, Y_hot, N, 2, packed, stream); break;
+        case 384: launch_nv<4, 3, BF16>(plan, X, Y, Y_hot, N, 3, packed, stream); break;
+        case 512: launch_nv<4, 4, BF16>(plan, X, Y, Y_hot, N, 4, packed, stream); break;
+        default: launch_nv<4, 0, BF16>(plan, X, Y, Y_hot, N, N / 128, packed, stream); break;
     }
     const int64_t nnz = plan.fmt.nnz;
     const unsigned blocks = (unsigned)std::min<int64_t>((nnz + 255) / 256, 256 * 32);
@@ -274,11 +289,24 @@ void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, voi
         std::lock_guard<std::mutex> lock(plan.workspace_mutex);
         if (!plan.sddmm_packed.p) plan.sddmm_packed.alloc((size_t)f.nnz);
     }
+    // Y in the caller's order under a column order: gather its most used rows, as execute does for B
+    const uint16_t* Y_hot = nullptr;
+    if (plan.d_col_order.p && plan.opt.operand_order == 0) {
+        {
+            std::lock_guard<std::mutex> lock(plan.workspace_mutex);
+            if (plan.b_hot_N < N && plan.n_hot > 0) {
+                plan.b_hot.alloc((size_t)plan.n_hot * (size_t)N);
+                plan.b_hot_N = N;
+            }
+        }
+        launch_permute_rows(plan.d_col_order.p, plan.n_hot, Y, plan.b_hot.p, (int64_t)N * 2, false, stream);
+        Y_hot = plan.b_hot.p;
+    }
     if (plan.opt.value_type == ACC_SPMM_BF16)
-        launch_typed<true>(plan, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Y), N,
+        launch_typed<true>(plan, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Y), Y_hot, N,
                            static_cast<float*>(out), use_values, stream);
     else
-        launch_typed<false>(plan, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Y), N,
+        launch_typed<false>(plan, static_cast<const uint16_t*>(X), static_cast<const uint16_t*>(Y), Y_hot, N,
                             static_cast<float*>(out), use_values, stream);
     ACC_HIP(hipGetLastError());
 }

@@ -102,6 +102,96 @@ bool validate_csr(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, cons
     return unsorted;
 }
 
+struct RowOrderInfo {
+    bool applied = false;
+    int64_t tiles_identity = -1;   // tile count in the input order, if it was counted
+    double work_ratio = 0.0, t_graph = 0.0, t_dendrogram = 0.0, t_ordering = 0.0, t_total = 0.0;
+};
+
+// Row order of the plan (Section 3.2): d_perm / P.perm / P.iperm get the data-affinity order if
+// the options ask for it and, under AUTO, it pays; else the identity.
+void choose_row_order(Plan& P, int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, DevBuf<int32_t>& d_perm,
+                      RowOrderInfo& info) {
+    const acc_spmm_options& opt = P.opt;
+    const int32_t WH = opt.window_height, TW = opt.tile_width;
+    std::vector<int32_t> identity(M);
+    for (int64_t i = 0; i < M; ++i) identity[i] = (int32_t)i;
+    d_perm.upload(identity.data(), M);
+    if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
+        const double r0 = now_s();
+        // AUTO gives up on inputs whose dendrogram is expensive to build (large uniform
+        // meshes), where the identity order is kept anyway; ON always completes.
+        const double budget = opt.reorder == ACC_SPMM_AUTO ? kAutoReorderWorkBudget : 0.0;
+        std::vector<int32_t> seq;
+        std::vector<int64_t> seg_start;
+        bool complete;
+        {
+            const double g0 = now_s();
+            HostGraph graph;
+            build_graph_on_device(M, nnz, P.d_rowptr.p, P.d_colidx.p, graph);
+            const double g1 = now_s();
+            complete = build_dendrogram_host(M, graph.ptr, graph.adj, opt.segment_length, budget, P.parent, seq, seg_start,
+                                             &info.work_ratio);
+            info.t_graph = g1 - g0;
+            info.t_dendrogram = now_s() - g1;
+        }
+        if (!complete) {
+            P.parent.clear();
+        } else {
+            const double o0 = now_s();
+            int32_t max_row_len = 0;
+            for (int64_t i = 0; i < M; ++i) max_row_len = std::max(max_row_len, rowptr[i + 1] - rowptr[i]);
+            DevBuf<int32_t> d_new;
+            ordering_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, seq, seg_start, opt.segment_length, max_row_len, d_new);
+            info.t_ordering = now_s() - o0;
+            DeviceFormat probe;
+            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
+            info.tiles_identity = probe.T;
+            encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
+            info.applied = opt.reorder == ACC_SPMM_ON ||
+                           (double)probe.T <= (1.0 - kAutoReorderMinGain) * (double)info.tiles_identity;
+            if (info.applied) {
+                P.perm.resize(M);
+                d_new.download(P.perm.data());
+                P.iperm.resize(M);
+                for (int64_t r = 0; r < M; ++r) P.iperm[P.perm[r]] = (int32_t)r;
+                ACC_HIP(hipMemcpy(d_perm.p, d_new.p, sizeof(int32_t) * M, hipMemcpyDeviceToDevice));
+            }
+        }
+        info.t_total = now_s() - r0;
+    }
+    if (!info.applied) {
+        P.perm = identity;
+        P.iperm = std::move(identity);
+    }
+}
+
+// Column order of the plan: when the options ask for one and, under AUTO, the labels of the
+// most used columns call for it, P.d_col_order / col_order / col_rank are filled and
+// d_colidx_plan gets the column indices relabelled into it; else everything stays empty.
+void choose_column_order(Plan& P, int64_t K, int64_t nnz, DevBuf<int32_t>& d_colidx_plan, double& skew) {
+    const acc_spmm_options& opt = P.opt;
+    skew = 0.0;
+    if (opt.column_order == ACC_SPMM_OFF || K == 0 || nnz == 0) return;
+    if (opt.column_order == ACC_SPMM_AUTO && K < kHubSkewMinK) return;   // too small for AUTO to ever apply
+    DevBuf<int32_t> d_order, d_rank;
+    column_order_on_device(K, nnz, P.d_colidx.p, d_order, d_rank);
+    if (K >= kHubSkewMinK) {
+        std::vector<int32_t> top((size_t)std::min<int64_t>(kHubSample, K / 16));
+        ACC_HIP(hipMemcpy(top.data(), d_order.p, sizeof(int32_t) * top.size(), hipMemcpyDeviceToHost));
+        skew = hub_label_skew(top);
+    }
+    const bool apply = opt.column_order == ACC_SPMM_ON || (K >= kAutoColumnOrderMinK && skew >= kAutoColumnOrderSkew);
+    if (!apply) return;
+    P.col_order.resize(K);
+    P.col_rank.resize(K);
+    d_order.download(P.col_order.data());
+    d_rank.download(P.col_rank.data());
+    d_colidx_plan.alloc(nnz);
+    remap_columns_on_device(nnz, P.d_colidx.p, d_rank.p, d_colidx_plan.p);
+    P.d_col_order.swap(d_order);
+}
+
 acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
                             const uint16_t* vals, const acc_spmm_options* user) {
     const double t0 = now_s();
@@ -160,87 +250,15 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         P.d_vals.upload(vals, nnz);
 
         // ---- row order ----
-        std::vector<int32_t> identity(M);
-        for (int64_t i = 0; i < M; ++i) identity[i] = (int32_t)i;
         DevBuf<int32_t> d_perm;
-        d_perm.upload(identity.data(), M);
-        bool use_reorder = false;
-        int64_t tiles_identity = -1;
-        double t_reorder = 0.0, reorder_work = 0.0, reorder_phases[3] = {0.0, 0.0, 0.0};
-        if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
-            const double r0 = now_s();
-            // AUTO gives up on inputs whose dendrogram is expensive to build (large uniform
-            // meshes), where the identity order is kept anyway; ON always completes.
-            const double budget = opt.reorder == ACC_SPMM_AUTO ? kAutoReorderWorkBudget : 0.0;
-            std::vector<int32_t> seq;
-            std::vector<int64_t> seg_start;
-            bool complete;
-            {
-                const double g0 = now_s();
-                HostGraph graph;
-                build_graph_on_device(M, nnz, P.d_rowptr.p, P.d_colidx.p, graph);
-                const double g1 = now_s();
-                complete = build_dendrogram_host(M, graph.ptr, graph.adj, opt.segment_length, budget, P.parent, seq,
-                                                 seg_start, &reorder_work);
-                reorder_phases[0] = g1 - g0;
-                reorder_phases[1] = now_s() - g1;
-            }
-            if (!complete) {
-                P.parent.clear();
-            } else {
-                const double o0 = now_s();
-                int32_t max_row_len = 0;
-                for (int64_t i = 0; i < M; ++i) max_row_len = std::max(max_row_len, rowptr[i + 1] - rowptr[i]);
-                DevBuf<int32_t> d_new;
-                ordering_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, seq, seg_start, opt.segment_length, max_row_len,
-                                   d_new);
-                reorder_phases[2] = now_s() - o0;
-                DeviceFormat probe;
-                encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_perm.p, WH, TW, probe, true);
-                tiles_identity = probe.T;
-                encode_on_device(M, K, nnz, P.d_rowptr.p, P.d_colidx.p, P.d_vals.p, d_new.p, WH, TW, probe, true);
-                use_reorder = opt.reorder == ACC_SPMM_ON ||
-                              (double)probe.T <= (1.0 - kAutoReorderMinGain) * (double)tiles_identity;
-                if (use_reorder) {
-                    P.perm.resize(M);
-                    d_new.download(P.perm.data());
-                    P.iperm.resize(M);
-                    for (int64_t r = 0; r < M; ++r) P.iperm[P.perm[r]] = (int32_t)r;
-                    ACC_HIP(hipMemcpy(d_perm.p, d_new.p, sizeof(int32_t) * M, hipMemcpyDeviceToDevice));
-                }
-            }
-            t_reorder = now_s() - r0;
-        }
-        if (!use_reorder) {
-            P.perm = identity;
-            P.iperm = identity;
-        }
-        std::vector<int32_t>().swap(identity);
+        RowOrderInfo ro;
+        choose_row_order(P, M, K, nnz, rowptr, d_perm, ro);
 
         // ---- column order ----
         const double c0 = now_s();
         double skew = 0.0;
         DevBuf<int32_t> d_colidx_plan;   // column indices in the plan's column order (only if one is applied)
-        if (opt.column_order != ACC_SPMM_OFF && K > 0 && nnz > 0) {
-            DevBuf<int32_t> d_order, d_rank;
-            column_order_on_device(K, nnz, P.d_colidx.p, d_order, d_rank);
-            bool apply = opt.column_order == ACC_SPMM_ON;
-            if (K >= kHubSkewMinK) {
-                std::vector<int32_t> top((size_t)std::min<int64_t>(kHubSample, K / 16));
-                ACC_HIP(hipMemcpy(top.data(), d_order.p, sizeof(int32_t) * top.size(), hipMemcpyDeviceToHost));
-                skew = hub_label_skew(top);
-            }
-            if (opt.column_order == ACC_SPMM_AUTO) apply = K >= kAutoColumnOrderMinK && skew >= kAutoColumnOrderSkew;
-            if (apply) {
-                P.col_order.resize(K);
-                P.col_rank.resize(K);
-                d_order.download(P.col_order.data());
-                d_rank.download(P.col_rank.data());
-                d_colidx_plan.alloc(nnz);
-                remap_columns_on_device(nnz, P.d_colidx.p, d_rank.p, d_colidx_plan.p);
-                P.d_col_order.swap(d_order);
-            }
-        }
+        choose_column_order(P, K, nnz, d_colidx_plan, skew);
         const bool use_col_order = P.d_col_order.p != nullptr;
         const double t_col_order = now_s() - c0;
 
@@ -285,23 +303,23 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.num_windows = W;
         st.num_tiles = P.fmt.T;
         st.sum_distinct_cols = P.fmt.sum_dw;
-        st.num_tiles_identity = tiles_identity >= 0 ? tiles_identity : P.fmt.T;
+        st.num_tiles_identity = ro.tiles_identity >= 0 ? ro.tiles_identity : P.fmt.T;
         st.num_items = (int64_t)P.items.size();
         st.num_split_windows = (int64_t)P.splits.size();
         st.num_partial_slots = P.n_slots;
         st.max_tiles_per_item = opt.max_tiles_per_item;
-        st.reorder_applied = use_reorder;
+        st.reorder_applied = ro.applied;
         st.load_balance_applied = balance;
         st.ibd = ibd;
         st.mean_nnz_per_tile = P.fmt.T ? (double)nnz / (double)P.fmt.T : 0.0;
         st.index_bytes = 4 * (W + 1) + 4 * (P.fmt.T + 1) + 4 * P.fmt.T * TW + 8 * P.fmt.T * P.fmt.NW;
         st.schedule_bytes = (int64_t)(sizeof(WorkItem) * P.items.size() + sizeof(SplitWindow) * P.splits.size()) + 4 * W * WH;
-        st.reorder_work_ratio = reorder_work;
-        st.t_graph_s = reorder_phases[0];
-        st.t_dendrogram_s = reorder_phases[1];
-        st.t_ordering_s = reorder_phases[2];
+        st.reorder_work_ratio = ro.work_ratio;
+        st.t_graph_s = ro.t_graph;
+        st.t_dendrogram_s = ro.t_dendrogram;
+        st.t_ordering_s = ro.t_ordering;
         st.t_validate_s = t1 - t0;
-        st.t_reorder_s = t_reorder;
+        st.t_reorder_s = ro.t_total;
         st.t_encode_s = t_encode;
         st.t_schedule_s = t_schedule;
         st.column_order_applied = use_col_order;

@@ -41,6 +41,24 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def gpu_clocks():
+    """Current clocks as rocm-smi prints them (best effort: None if the tool is missing or fails)."""
+    import re
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([exe, "--showclocks"], capture_output=True, text=True, timeout=20).stdout
+    except Exception:
+        return None
+    clocks = {}
+    for name in ("sclk", "mclk", "fclk"):
+        m = re.search(name + r" clock level: \S+ \((\d+)Mhz\)", out)
+        if m:
+            clocks[name + "_mhz"] = int(m.group(1))
+    return clocks or None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,6 +162,16 @@ def main() -> int:
         combine_ms.append(b)
         gather_ms.append(g)
     tiles_avg = float(np.mean(tiles_ms))
+    # a launch-bound workload is better described by many launches back to back
+    back_to_back_us = None
+    if t_step < 1e-4:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(100):
+            acc.acc_spmm_execute(plan, B, w.N, C, stream)
+        torch.cuda.synchronize()
+        back_to_back_us = (time.perf_counter() - t0) / 100 * 1e6
+    clocks = gpu_clocks()
     alg_bytes = tr["a_bytes"] + tr["b_bytes"] + tr["c_bytes"]
     achieved = alg_bytes / (tiles_avg * 1e-3) / 1e9 if tiles_avg > 0 else 0.0
 
@@ -202,6 +230,7 @@ def main() -> int:
                      "traffic": MEASURED_TRAFFIC_BYTES.get(w.name)
                      if (args.reorder, args.load_balance, args.column_order) == ("auto", "auto", "auto") else None,
                      "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
+                     "kernel_ms_median": float(np.median(tiles_ms)),
                      "combine_ms_avg": float(np.mean(combine_ms)), "gather_B_ms_avg": float(np.mean(gather_ms)),
                      "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"],
                      "c_bytes": tr["c_bytes"], "b_bytes_upper_nnzN2": 2 * w.nnz * w.N, "b_bytes_lower_KN2": 2 * w.K * w.N,
@@ -219,6 +248,8 @@ def main() -> int:
                  "column_order_applied": st["column_order_applied"], "hub_label_skew": st["hub_label_skew"],
                  "column_order_s": st["t_column_order_s"]},
         "parity_spot_check": {"rows": int(len(rows)), "ok": bool(ok), "worst_error_over_limit": ratio},
+        "back_to_back_100_launches_us": back_to_back_us,
+        "clocks": clocks,
         "generate_s": t_gen,
         "paper_context": PAPER_CONTEXT,
     }

@@ -574,6 +574,62 @@ def test_execute_argument_errors():
         acc.acc_spmm_destroy(plan)
 
 
+# -------------------------------------------------- random shapes x random options
+@pytest.mark.parametrize("block", range(6))
+def test_randomised_shapes_and_options(block):
+    """Seeded sweep over shapes (empty matrices, M != K, K below one tile, one heavy row, empty
+    windows) and over every option, SpMM and SDDMM, each case against the oracle."""
+    rng = np.random.default_rng(9000 + block)
+    for case in range(12):
+        M = int(rng.choice([0, 1, 15, 16, 17, 100, 333, 1000]))
+        K = int(rng.choice([1, 5, 16, 40, 257, 1000])) if rng.random() < 0.6 else max(M, 1)
+        density = float(rng.choice([0.0, 0.01, 0.05, 0.3]))
+        rowptr, colidx, _ = random_csr(rng, M, K, density, empty_row_frac=float(rng.choice([0.0, 0.3, 0.9])))
+        rows = [colidx[rowptr[i]:rowptr[i + 1]].tolist() for i in range(M)]
+        if M > 40 and rng.random() < 0.5:
+            rows[int(rng.integers(0, M))] = np.sort(rng.choice(K, min(K, 400), replace=False)).tolist()
+        if M > 64 and rng.random() < 0.5:
+            for i in range(16, 64):
+                rows[i] = []
+        rowptr, colidx, _ = csr_from_rows(rows)
+        nnz = len(colidx)
+        use_bf16 = bool(rng.random() < 0.3)
+        to_bits = bf16 if use_bf16 else f16
+        vt = "bf16" if use_bf16 else "f16"
+        vals = to_bits(rng.uniform(-1, 1, nnz))
+        N = int(rng.choice([1, 8, 16, 24, 32, 50, 64, 128, 136, 256]))
+        B = to_bits(rng.standard_normal((K, N)))
+        operand_order = int(rng.integers(0, 2))
+        opt = dict(reorder=int(rng.integers(0, 3)), load_balance=int(rng.integers(0, 3)),
+                   max_tiles_per_item=int(rng.choice([0, 1, 3, 8, 64])), column_order=int(rng.integers(0, 3)),
+                   operand_order=operand_order, value_fetch=int(rng.integers(0, 3)),
+                   pipeline_depth=int(rng.integers(0, 4)), streaming_stores=int(rng.integers(0, 2)),
+                   segment_length=int(rng.choice([0, 2, 37, 4096])), keep_csr=1, keep_entry_map=1,
+                   value_type=acc.ACC_SPMM_BF16 if use_bf16 else acc.ACC_SPMM_FP16)
+        label = f"block {block} case {case}: M={M} K={K} nnz={nnz} N={N} {opt}"
+        print(label, flush=True)
+        plan = acc.acc_spmm_plan_ex(M, K, nnz, rowptr, colidx, vals, acc.make_options(**opt))
+        try:
+            in_plan_order = operand_order == 1 and acc.acc_spmm_plan_stats(plan)["column_order_applied"] == 1
+            B_given = _permuted(plan, B) if in_plan_order and K > 0 else B
+            C = run_spmm(plan, B_given, M, N)
+            if M > 0:
+                C_ref, bound = oracle.spmm(rowptr, colidx, vals, B, value_type=vt)
+                ok, ratio = oracle.within_bound(C, C_ref, bound)
+                assert ok, f"{label}: spmm outside tolerance, worst error/limit = {ratio}"
+                Cn = run_spmm(plan, B_given, M, N, naive=True)
+                ok, ratio = oracle.within_bound(Cn, C_ref, bound)
+                assert ok, f"{label}: row-per-wave kernel outside tolerance, worst error/limit = {ratio}"
+            Ns = int(rng.choice([32, 96, 128, 256]))
+            X, Y = to_bits(rng.standard_normal((M, Ns))), to_bits(rng.standard_normal((K, Ns)))
+            Y_given = _permuted(plan, Y) if in_plan_order and K > 0 else Y
+            got = run_sddmm(plan, X, Y_given, nnz, Ns, 1)
+            if nnz > 0:
+                check_sddmm(rowptr, colidx, vals, X, Y, got, 1, value_type=vt)
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+
 # -------------------------------------------------- full size, as the benchmark launches it
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
 def test_full_size_sampled_rows(cfg):

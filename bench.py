@@ -82,6 +82,7 @@ def main() -> int:
                     help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-naive", action="store_true")
+    ap.add_argument("--no-vendor", action="store_true", help="skip the torch.sparse.mm (hipSPARSE) comparison")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel on 1 GiB (for scaling rocprofv3 --pmc counters)")
     ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target CPU time of the oracle sample")
@@ -198,6 +199,33 @@ def main() -> int:
         naive = {"value": flops / t_naive / 1e9, "unit": "GFLOP/s", "ms": t_naive * 1e3,
                  "kind": "one wavefront per CSR row, fp32 FMA"}
 
+    # ---- the vendor library as PyTorch reaches it, for context (the paper's own headline is a speedup
+    #      over the vendor library of its GPUs).  hipSPARSE has no fp16 SpMM, so this leg runs in fp32.
+    vendor = None
+    if not args.no_vendor and w.nnz > 0:
+        try:
+            import warnings
+            with warnings.catch_warnings():
+                warnings.simplefilter("ignore")
+                A_t = torch.sparse_csr_tensor(torch.from_numpy(w.rowptr).to(dev), torch.from_numpy(w.colidx).to(dev),
+                                              torch.from_numpy(w.vals.view(np.float16).astype(np.float32)).to(dev),
+                                              size=(w.M, w.K))
+                B_t = B_caller.view(torch.float16).to(torch.float32)
+                torch.sparse.mm(A_t, B_t)
+                torch.cuda.synchronize()
+                reps = 3
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    C_t = torch.sparse.mm(A_t, B_t)
+                torch.cuda.synchronize()
+                t_vendor = (time.perf_counter() - t0) / reps
+            vendor = {"value": flops / t_vendor / 1e9, "unit": "GFLOP/s", "ms": t_vendor * 1e3,
+                      "kind": "torch.sparse.mm on a CSR tensor (hipSPARSE SpMM), fp32 values, fp32 B, fp32 C"}
+            del A_t, B_t, C_t
+        except Exception as ex:                                  # a missing or failing library is not this bench's failure
+            vendor = {"value": None, "kind": "torch.sparse.mm", "error": repr(ex)[:200]}
+        torch.cuda.empty_cache()
+
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows
     cpu = None
     if not args.no_cpu_baseline:
@@ -237,6 +265,7 @@ def main() -> int:
                      "mfma_flops_issued": tr["mfma_flops"]},
         "cpu_baseline": cpu,
         "naive_gpu": naive,
+        "vendor_library": vendor,
         "plan": {"seconds": t_plan, "validate_s": st["t_validate_s"], "reorder_s": st["t_reorder_s"],
                  "reorder_graph_s": st["t_graph_s"], "reorder_dendrogram_s": st["t_dendrogram_s"],
                  "reorder_ordering_s": st["t_ordering_s"], "reorder_work_ratio": st["reorder_work_ratio"],

@@ -105,7 +105,7 @@ typedef struct {
      * and the conclusion).  ON: columns are grouped by floor(log2(entries in the column)),
      * classes descending, input ids ascending inside a class, unused columns last, so the
      * rows of B that many windows gather sit together whatever labels the input gave them.
-     * AUTO: ON when K >= 2^21 (B then exceeds the memory-side cache at usual N) and the
+     * AUTO: ON when K >= 2^20 (B then exceeds the memory-side cache at usual N) and the
      * labels of the most used columns are concentrated on few residues modulo 16, 256 or
      * 4096 (acc_spmm_stats.hub_label_skew >= 4), which is when gathering their rows of B
      * collides in the memory system; else OFF. */
@@ -113,7 +113,8 @@ typedef struct {
     /* 0: B is given in the caller's row order; when the plan has a column order, every
      *    execute first gathers the rows of B for the first min(K/16, 2^17) columns of that
      *    order (the most used ones) into a buffer of the plan and reads the other rows of B
-     *    in place.
+     *    in place (plans with K < 2^22 read all of B in place when N <= 64, where the gathered
+     *    copy does not pay).
      * 1: B is given in the plan's order already (B_plan[j] = B[col_order[j]], see
      *    acc_spmm_permute_rows and ACC_SPMM_ARR_COL_ORDER); execute reads it in place.
      * C is in the caller's row order in both cases. */

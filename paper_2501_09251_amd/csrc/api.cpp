@@ -24,11 +24,14 @@ constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
 constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry
 constexpr int64_t kHubSkewMinK = 65536;          // fewer columns: too few labels for the statistic
-// AUTO column order only from 2^21 columns on.  Measured on unscrambled R-MAT inputs with B in
+// AUTO column order only from 2^20 columns on.  Measured on unscrambled R-MAT inputs with B in
 // the caller's order: the order pays once B exceeds about 256 MB, the size of the memory-side
-// cache (+22..30 % at N >= 128 from 2^20 columns on), while at N <= 64 the 64-bit addressing of
-// the two-matrix gather costs 12..26 % below 2^21 columns, 4 % at 2^21, and wins from 2^22 on.
-constexpr int64_t kAutoColumnOrderMinK = (int64_t)1 << 21;
+// cache (+22..30 % at N >= 128 from 2^20 columns on; nothing at 2^19 columns and N = 128).  At
+// N <= 64 the 64-bit addressing of the two-matrix gather costs more than the order gains below
+// 2^22 columns (-12..-26 %, -4 % at 2^21), so below kDualEntriesMaxK columns the plan also keeps
+// SparseAToB with plain input columns and execute reads all of B in place when N <= 64.
+constexpr int64_t kAutoColumnOrderMinK = (int64_t)1 << 20;
+constexpr int64_t kDualEntriesMaxK = (int64_t)1 << 22;
 constexpr int64_t kHubSample = 65536;            // most used columns whose labels are examined
 constexpr double kAutoColumnOrderSkew = 4.0;
 // Rows of B gathered per execute when B comes in the caller's order: the first K/16 of the
@@ -273,7 +276,10 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         if (use_col_order && opt.operand_order == 0) {
             // B stays in the caller's order: only the most used rows are gathered per call
             P.n_hot = (int32_t)std::min<int64_t>(kMaxHotColumns, K / 16);
-            hot_cold_entries_on_device(P.fmt.T * TW, P.fmt.sparse_a_to_b.p, P.d_col_order.p, P.n_hot);
+            // below kDualEntriesMaxK columns whether the gathered copy pays depends on N, known only
+            // at execute: keep the entries in both forms there
+            if (K < kDualEntriesMaxK) P.a2b_plain.alloc((size_t)(P.fmt.T * TW));
+            hot_cold_entries_on_device(P.fmt.T * TW, P.fmt.sparse_a_to_b.p, P.d_col_order.p, P.n_hot, P.a2b_plain.p);
         }
         if (!opt.keep_csr) {
             P.d_rowptr.release();

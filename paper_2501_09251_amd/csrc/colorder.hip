@@ -52,12 +52,15 @@ __global__ void remap_kernel(int64_t nnz, const int32_t* __restrict__ colidx, co
 // Entries of SparseAToB in plan column ids -> what the tile kernel reads when B stays in the
 // caller's order: plan column r < n_hot becomes ~r (row r of the gathered hot rows), the others
 // become their input column order[r] (a row of B in place).
+// `plain` (optional) gets the input column of every entry, for reading all of B in place.
 __global__ void hot_cold_entries_kernel(int64_t n, int32_t* __restrict__ a2b, const int32_t* __restrict__ order,
-                                        int32_t n_hot) {
+                                        int32_t n_hot, int32_t* __restrict__ plain) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t r = a2b[i];
-    a2b[i] = r < n_hot ? ~r : order[r];
+    const int32_t input_col = order[r];
+    a2b[i] = r < n_hot ? ~r : input_col;
+    if (plain) plain[i] = input_col;
 }
 
 // dst row j = src row order[j] (gather) or dst row order[j] = src row j (scatter); rows of
@@ -106,9 +109,10 @@ void remap_columns_on_device(int64_t nnz, const int32_t* d_colidx, const int32_t
     ACC_HIP(hipGetLastError());
 }
 
-void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot) {
+void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot, int32_t* d_plain) {
     if (n == 0) return;
-    hipLaunchKernelGGL(hot_cold_entries_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, 0, n, d_a2b, d_order, n_hot);
+    hipLaunchKernelGGL(hot_cold_entries_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, 0, n, d_a2b, d_order, n_hot,
+                       d_plain);
     ACC_HIP(hipGetLastError());
     ACC_HIP(hipDeviceSynchronize());
 }

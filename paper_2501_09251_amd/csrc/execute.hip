@@ -110,7 +110,11 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
             plan.workspace_N = N;
         }
     }
-    const bool gather = plan.d_col_order.p != nullptr && plan.opt.operand_order == 0 && f.nnz > 0;
+    // Column order with B in the caller's order: gather the most used rows and read the rest in place,
+    // unless the plan also kept plain entries and this call's rows are narrow (the gathered copy needs
+    // 64-bit addressing, which costs more than it gains at N <= 64 on plans of that size).
+    const bool hot_entries = plan.d_col_order.p != nullptr && plan.opt.operand_order == 0 && f.nnz > 0;
+    const bool gather = hot_entries && !(plan.a2b_plain.p != nullptr && N <= 64);
     if (gather && plan.n_hot > 0) {
         std::lock_guard<std::mutex> lock(plan.workspace_mutex);
         if (plan.b_hot_N < N) {
@@ -123,7 +127,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     ExecParams p;
     p.rwo = f.row_window_offset.p;
     p.tco = f.tc_offset.p;
-    p.a2b = f.sparse_a_to_b.p;
+    p.a2b = (hot_entries && !gather) ? plan.a2b_plain.p : f.sparse_a_to_b.p;
     p.bits = f.tc_local_bit.p;
     p.vals = f.vals.p;
     p.perm_pad = plan.d_perm_pad.p;

@@ -122,7 +122,7 @@ void ordering_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowp
 void column_order_on_device(int64_t K, int64_t nnz, const int32_t* d_colidx, DevBuf<int32_t>& d_order,
                             DevBuf<int32_t>& d_rank);
 void remap_columns_on_device(int64_t nnz, const int32_t* d_colidx, const int32_t* d_rank, int32_t* d_out);
-void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot);
+void hot_cold_entries_on_device(int64_t n, int32_t* d_a2b, const int32_t* d_order, int32_t n_hot, int32_t* d_plain);
 void launch_permute_rows(const int32_t* d_order, int64_t rows, const void* src, void* dst, int64_t row_bytes, bool scatter,
                          hipStream_t stream);
 
@@ -152,6 +152,7 @@ struct Plan {
     DevBuf<int32_t> d_col_order;
     std::vector<int32_t> col_order, col_rank;
     int32_t n_hot = 0;
+    DevBuf<int32_t> a2b_plain;   // SparseAToB with input columns throughout (kept below kDualEntriesMaxK columns)
     mutable DevBuf<uint16_t> b_hot;
     mutable int32_t b_hot_N = 0;
     // optional: CSR entry index of every packed value (for sddmm), and sddmm's results in packed

@@ -259,7 +259,7 @@ def test_column_order_auto_detects_hubs_at_power_of_two_labels():
         finally:
             acc.acc_spmm_destroy(plan)
 
-    w = wl.config(5, 2, with_B=False)                         # 2^21 vertices
+    w = wl.config(5, 3, with_B=False)                         # 2^20 vertices
     on, skew = applied(w.M, w.K, w.rowptr, w.colidx, w.vals)
     assert on == 1 and skew >= 8.0
     relabel = np.random.default_rng(0).permutation(w.K).astype(np.int32)

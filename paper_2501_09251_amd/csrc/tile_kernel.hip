@@ -4,7 +4,7 @@
 // One wavefront owns one work item: a run of whole row windows, or a slice of the tiles of
 // one heavy window (Section 3.5).  For every 16x16 tile the wavefront
 //   - reads the tile's 16 SparseAToB entries and gathers those 16 rows of B straight into
-//     registers (as in the paper's Fig. 5, B goes global -> registers): each 16-lane group
+//     registers (as in the paper's Section 3.4, B goes global -> registers): each 16-lane group
 //     reads four whole rows with 16-byte loads per lane,
 //   - decodes its own four positions of the tile from the bitmap (popcount of the lower
 //     bits gives the value offset, Section 3.3) and reads up to four packed values,
@@ -19,7 +19,8 @@
 // reads the tile's contiguous values once, one dword per lane, and every lane then picks its
 // values out of the other lanes' registers with ds_bpermute.  The second way issues a
 // quarter of the memory instructions and wins when tiles are dense; the first wins on the
-// sparse tiles of power-law inputs.  The plan's mean entries per tile selects the way.
+// sparse tiles of power-law inputs at N >= 128.  Execute selects the way from the plan's mean
+// entries per tile and N.
 //
 // Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
 // values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index

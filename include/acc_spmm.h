@@ -240,6 +240,16 @@ ACC_SPMM_API int acc_spmm_sddmm(const acc_spmm_plan_t* plan, const void* X, cons
                                 int32_t use_values, void* stream);
 
 /*
+ * Replace the values of A, keeping its pattern (and with it the whole plan): layers that
+ * recompute edge weights every step, for instance from acc_spmm_sddmm's output, re-use one plan.
+ *   csr_vals  DEVICE uint16[nnz], bit patterns of the plan's value_type, entry p in row-major
+ *             order with ascending columns inside a row (acc_spmm_sddmm's output order)
+ * Needs a plan built with keep_entry_map = 1.  Enqueues on `stream`; later executes on that
+ * stream see the new values.  The copy kept for acc_spmm_execute_csr_naive is not updated.
+ */
+ACC_SPMM_API int acc_spmm_update_values(acc_spmm_plan_t* plan, const void* csr_vals, void* stream);
+
+/*
  * Reorder the rows of a K-row DEVICE matrix between the caller's order and the plan's
  * column order (for callers that keep B in the plan's order, options.operand_order = 1).
  *   row_bytes  bytes per row, a multiple of 2

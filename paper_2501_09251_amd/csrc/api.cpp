@@ -400,6 +400,13 @@ int acc_spmm_sddmm(const acc_spmm_plan_t* plan, const void* X, const void* Y, in
     });
 }
 
+int acc_spmm_update_values(acc_spmm_plan_t* plan, const void* csr_vals, void* stream) {
+    return guarded([&] {
+        if (!plan || (!csr_vals && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_update_values(plan->plan, csr_vals, static_cast<hipStream_t>(stream));
+    });
+}
+
 int acc_spmm_permute_rows(const acc_spmm_plan_t* plan, const void* src, void* dst, int64_t row_bytes, int32_t to_caller,
                           void* stream) {
     return guarded([&] {

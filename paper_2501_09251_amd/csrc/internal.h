@@ -171,6 +171,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 // sddmm.hip
+void launch_update_values(const Plan& plan, const void* csr_vals, hipStream_t stream);
 void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, void* out, int32_t use_values,
                   hipStream_t stream);
 

@@ -232,6 +232,14 @@ __global__ __launch_bounds__(256) void sddmm_finish_kernel(int64_t nnz, const fl
     }
 }
 
+// packed[q] = csr_vals[entry_of[q]]: new values for the same pattern, CSR entry order -> packed order
+__global__ __launch_bounds__(256) void repack_values_kernel(int64_t nnz, const uint16_t* __restrict__ csr_vals,
+                                                            const int32_t* __restrict__ entry_of,
+                                                            uint16_t* __restrict__ packed) {
+    for (int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; q < nnz; q += (int64_t)gridDim.x * blockDim.x)
+        packed[q] = csr_vals[entry_of[q]];
+}
+
 template <int NV, int PASSES, bool BF16>
 void launch_nv(const Plan& plan, const uint16_t* X, const uint16_t* Y, const uint16_t* Y_hot, int32_t N, int32_t passes,
                float* packed_out, hipStream_t stream) {
@@ -270,6 +278,19 @@ void launch_typed(const Plan& plan, const uint16_t* X, const uint16_t* Y, const 
 }
 
 }  // namespace
+
+void launch_update_values(const Plan& plan, const void* csr_vals, hipStream_t stream) {
+    const int64_t nnz = plan.fmt.nnz;
+    if (nnz == 0) return;
+    if (!plan.d_entry_of.p) fail(ACC_SPMM_ERR_INVALID_ARG, "update_values needs a plan built with keep_entry_map = 1");
+    int dev = -1;
+    ACC_HIP(hipGetDevice(&dev));
+    if (dev != plan.device) fail(ACC_SPMM_ERR_INVALID_ARG, "the plan lives on another device than the current one");
+    const unsigned blocks = (unsigned)std::min<int64_t>((nnz + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(repack_values_kernel, dim3(blocks), dim3(256), 0, stream, nnz, static_cast<const uint16_t*>(csr_vals),
+                       plan.d_entry_of.p, plan.fmt.vals.p);
+    ACC_HIP(hipGetLastError());
+}
 
 void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, void* out, int32_t use_values,
                   hipStream_t stream) {

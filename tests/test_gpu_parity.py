@@ -382,6 +382,32 @@ def test_sddmm_bf16_and_column_order_in_plan_order():
         acc.acc_spmm_destroy(plan)
 
 
+@pytest.mark.parametrize("reorder", [acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON])
+def test_update_values_keeps_the_plan(reorder):
+    """New values for the same pattern: SpMM and SDDMM afterwards use them; one attention-style
+    round trip (SDDMM -> values -> SpMM) stays inside the library's order conventions."""
+    rng = np.random.default_rng(77)
+    w = wl.config(2, 6)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(reorder=reorder, load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16,
+                                                 keep_entry_map=1))
+    try:
+        new_vals = f16(rng.uniform(-2, 2, w.nnz))
+        acc.acc_spmm_update_values(plan, torch.from_numpy(new_vals.view(np.int16)).cuda(), None)
+        np.testing.assert_array_equal(np.sort(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_VALUES)), np.sort(new_vals))
+        C = run_spmm(plan, w.B, w.M, w.N)
+        check_against_oracle(w.rowptr, w.colidx, new_vals, w.B, C)
+        X, Y = wl.dense(w.M, 64, 8, "normal", 0.0, 0.3), wl.dense(w.K, 64, 9, "normal", 0.0, 0.3)
+        scores = run_sddmm(plan, X, Y, w.nnz, 64, 0)                  # fp32, entry order
+        check_sddmm(w.rowptr, w.colidx, None, X, Y, scores, 0)
+        edge_vals = f16(np.tanh(scores))                              # any entry-wise function of the scores
+        acc.acc_spmm_update_values(plan, torch.from_numpy(edge_vals.view(np.int16)).cuda(), None)
+        C = run_spmm(plan, w.B, w.M, w.N)
+        check_against_oracle(w.rowptr, w.colidx, edge_vals, w.B, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 def test_sddmm_argument_errors():
     rowptr, colidx, vals = csr_from_rows([[0]])
     X = torch.zeros(1, 48, dtype=torch.float16, device="cuda")

@@ -600,6 +600,52 @@ def test_execute_argument_errors():
         acc.acc_spmm_destroy(plan)
 
 
+def test_widest_rows():
+    """N at the documented maximum (many slab launches along gridDim.y) and just past a slab boundary."""
+    rng = np.random.default_rng(4)
+    M, K = 40, 50
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.2)
+    plan = acc.acc_spmm_plan(M, K, len(colidx), rowptr, colidx, vals)
+    try:
+        for N in (65536, 65535, 4104):
+            B = f16(rng.standard_normal((K, N)))
+            C = run_spmm(plan, B, M, N)
+            check_against_oracle(rowptr, colidx, vals, B, C)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_plans_release_their_device_memory():
+    """Two hundred plans built, run (with every lazily allocated buffer in use) and destroyed:
+    free device memory ends where it started."""
+    w = wl.config(2, 6)
+    X = torch.from_numpy(wl.dense(w.M, 64, 1, "normal", 0.0, 1.0).view(np.int16)).cuda()
+    B = torch.from_numpy(w.B.view(np.int16)).cuda()
+    C = torch.empty((w.M, w.N), device="cuda")
+    out = torch.empty(w.nnz, device="cuda")
+    opt = acc.make_options(reorder=acc.ACC_SPMM_OFF, load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=8,
+                           column_order=acc.ACC_SPMM_ON, keep_csr=1, keep_entry_map=1)
+
+    def one():
+        plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+        try:
+            acc.acc_spmm_execute(plan, B, w.N, C, None)
+            acc.acc_spmm_sddmm(plan, X, B[:, :64].contiguous(), 64, out, 1, None)
+            torch.cuda.synchronize()
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+    for _ in range(3):
+        one()                                   # warm up allocator pools of the runtime and of torch
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(200):
+        one()
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free0 - free1 < 64 << 20, f"device memory shrank by {(free0 - free1) >> 20} MiB over 200 plans"
+
+
 # -------------------------------------------------- random shapes x random options
 @pytest.mark.parametrize("block", range(6))
 def test_randomised_shapes_and_options(block):

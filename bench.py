@@ -42,20 +42,23 @@ def log(*a):
 
 
 def gpu_clocks():
-    """Current clocks as rocm-smi prints them (best effort: None if the tool is missing or fails)."""
+    """Current clocks of the first GPU, read from the driver's sysfs files (the figures rocm-smi
+    --showclocks prints; no child process is started).  None if the files are not there."""
+    import glob
     import re
-    import shutil
-    import subprocess
-    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        out = subprocess.run([exe, "--showclocks"], capture_output=True, text=True, timeout=20).stdout
-    except Exception:
-        return None
     clocks = {}
-    for name in ("sclk", "mclk", "fclk"):
-        m = re.search(name + r" clock level: \S+ \((\d+)Mhz\)", out)
-        if m:
-            clocks[name + "_mhz"] = int(m.group(1))
+    for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        for name, fname in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk")):
+            try:
+                with open(os.path.join(card, fname)) as f:
+                    text = f.read()
+            except OSError:
+                continue
+            m = re.search(r"(\d+)Mhz \*", text)       # the active level carries the star
+            if m:
+                clocks[name + "_mhz"] = int(m.group(1))
+        if clocks:
+            break
     return clocks or None
 
 

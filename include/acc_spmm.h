@@ -54,7 +54,7 @@ typedef struct {
     int32_t struct_size;
     /* Row reordering (Section 3.2, Algorithm 1).  OFF: identity.  ON: always apply.
      * AUTO (default when struct is NULL): compute it, keep it only if it lowers the number
-     * of tiles by at least 4 % (the paper notes in Section 4.3.5 that reordering can lose:
+     * of tiles by at least 1 % (the paper notes in Section 4.3.5 that reordering can lose:
      * it gives up the locality of the input order); AUTO also stops
      * the dendrogram construction, and keeps the identity, once it has visited 8 edge
      * records per graph entry (large uniform meshes, where nothing is gained).

@@ -19,7 +19,11 @@ double now_s() {
 }
 
 constexpr int32_t kDefaultCap = 256;
-constexpr double kAutoReorderMinGain = 0.04;     // AUTO keeps the reordering only for >= 4 % fewer tiles
+// AUTO keeps the reordering only for >= 1 % fewer tiles.  Measured, reordered against input order:
+// R-MAT 2^23 1.07 % fewer tiles, 3.6 % faster (fewer split windows); R-MAT 2^20 5.4 % fewer, 3 %
+// faster; block model 55 % fewer, 2.3x faster; stencil 1.2 % fewer, 1.3 % slower (AUTO gives up on
+// it earlier, on the work budget below).
+constexpr double kAutoReorderMinGain = 0.01;
 constexpr int32_t kDefaultSegLen = 1024;
 constexpr float kDefaultIbdThreshold = 8.0f;
 constexpr double kAutoReorderWorkBudget = 8.0;   // edge-record visits per graph entry

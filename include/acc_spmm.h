@@ -65,7 +65,9 @@ typedef struct {
      * heavy windows / pack light ones.  AUTO: apply iff IBD (Eq. 3) > ibd_threshold. */
     int32_t load_balance;
     /* Most tiles one work item may hold; heavier windows are split (Section 3.5 uses 32
-     * for 8x8x16 tiles on NVIDIA parts).  0 = default 256. */
+     * for 8x8x16 tiles on NVIDIA parts).  0 = default: the plan's tiles divided by twice the
+     * device's wave slots (12 per compute unit), between 32 and 1024
+     * (acc_spmm_stats.max_tiles_per_item reports it). */
     int32_t max_tiles_per_item;
     /* Tile geometry: rows per row window and condensed columns per tile.  0 = default
      * (16,16), the geometry the execute kernel runs.  (8,8), the paper's geometry
@@ -339,7 +341,8 @@ ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t by
  * Returns the number of segments, or a negative acc_spmm_status.
  *
  * acc_spmm_schedule_host: Section 3.5 for 16x16 tiles.  row_window_offset is HOST
- * int32[W+1].  load_balance / max_tiles_per_item / ibd_threshold as in acc_spmm_options.
+ * int32[W+1].  load_balance / max_tiles_per_item / ibd_threshold as in acc_spmm_options,
+ * except that max_tiles_per_item 0 means 256 here (there is no device to size it by).
  * *ibd_out receives Eq. 3 (may be NULL).  Work items (4 x int32 each, encoding as for
  * acc_spmm_plan_export) are written to `items` if it is not NULL; items_capacity is its
  * capacity in items.  Returns the number of work items, or a negative acc_spmm_status.

@@ -18,7 +18,18 @@ double now_s() {
     return duration<double>(steady_clock::now().time_since_epoch()).count();
 }
 
-constexpr int32_t kDefaultCap = 256;
+// Default cap on the tiles of one work item (Section 3.5 caps a thread block at 32 of its smaller
+// tiles): about two rounds of work items over the machine's wave slots, between 32 and 1024.
+// Swept on the two power-law workloads (tile + combine kernels): 0.89 M tiles, best at 128..192
+// (0.577..0.592 ms against 0.611 at 256 and 0.647 at 512); 14.9 M tiles, best at 512..1024
+// (8.20..8.36 ms against 8.47 at 256 and 8.56 at 2048).
+constexpr int32_t kDefaultCapMin = 32, kDefaultCapMax = 1024, kDefaultCapHostStage = 256;
+constexpr int64_t kWaveSlotsPerCu = 12, kItemRounds = 2;
+
+int32_t default_cap(int64_t tiles, int compute_units) {
+    const int64_t per_item = tiles / std::max<int64_t>(1, (int64_t)compute_units * kWaveSlotsPerCu * kItemRounds);
+    return (int32_t)std::min<int64_t>(kDefaultCapMax, std::max<int64_t>(kDefaultCapMin, per_item));
+}
 // AUTO keeps the reordering only for >= 1 % fewer tiles.  Measured, reordered against input order:
 // R-MAT 2^23 1.07 % fewer tiles, 3.6 % faster (fewer split windows); R-MAT 2^20 5.4 % fewer, 3 %
 // faster; block model 55 % fewer, 2.3x faster; stencil 1.2 % fewer, 1.3 % slower (AUTO gives up on
@@ -222,8 +233,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.tile_width == 0) opt.tile_width = 16;
     if (!((opt.window_height == 16 && opt.tile_width == 16) || (opt.window_height == 8 && opt.tile_width == 8)))
         fail(ACC_SPMM_ERR_UNSUPPORTED, "tile geometry must be 16x16 or 8x8");
-    if (opt.max_tiles_per_item == 0) opt.max_tiles_per_item = kDefaultCap;
-    if (opt.max_tiles_per_item < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "max_tiles_per_item must be positive");
+    if (opt.max_tiles_per_item < 0) fail(ACC_SPMM_ERR_INVALID_ARG, "max_tiles_per_item must not be negative");
     if (opt.segment_length == 0) opt.segment_length = kDefaultSegLen;
     if (opt.segment_length < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "segment_length must be positive");
     if (opt.ibd_threshold == 0.f) opt.ibd_threshold = kDefaultIbdThreshold;
@@ -298,7 +308,12 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         P.fmt.row_window_offset.download(rwo.data());
         const double ibd = imbalance_degree(rwo);
         const bool balance = opt.load_balance == ACC_SPMM_ON || (opt.load_balance == ACC_SPMM_AUTO && ibd > opt.ibd_threshold);
-        build_schedule(rwo, balance, opt.max_tiles_per_item, WH, TW, P.items, P.splits, P.n_slots);
+        if (opt.max_tiles_per_item == 0) {
+            int cus = 0;
+            ACC_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, P.device));
+            P.opt.max_tiles_per_item = default_cap(P.fmt.T, cus);
+        }
+        build_schedule(rwo, balance, P.opt.max_tiles_per_item, WH, TW, P.items, P.splits, P.n_slots);
         P.d_items.upload(P.items.data(), P.items.size());
         P.d_splits.upload(P.splits.data(), P.splits.size());
         std::vector<int32_t> pad((size_t)W * WH, -1);
@@ -317,7 +332,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.num_items = (int64_t)P.items.size();
         st.num_split_windows = (int64_t)P.splits.size();
         st.num_partial_slots = P.n_slots;
-        st.max_tiles_per_item = opt.max_tiles_per_item;
+        st.max_tiles_per_item = P.opt.max_tiles_per_item;
         st.reorder_applied = ro.applied;
         st.load_balance_applied = balance;
         st.ibd = ibd;
@@ -512,7 +527,7 @@ int64_t acc_spmm_schedule_host(int64_t W, const int32_t* row_window_offset, int3
         std::vector<WorkItem> it;
         std::vector<SplitWindow> sp;
         int64_t slots = 0;
-        build_schedule(rwo, balance, max_tiles_per_item > 0 ? max_tiles_per_item : kDefaultCap, 16, 16, it, sp, slots);
+        build_schedule(rwo, balance, max_tiles_per_item > 0 ? max_tiles_per_item : kDefaultCapHostStage, 16, 16, it, sp, slots);
         if (num_partial_slots) *num_partial_slots = slots;
         if (items) {
             if ((int64_t)it.size() > items_capacity) fail(ACC_SPMM_ERR_INVALID_ARG, "items_capacity too small");

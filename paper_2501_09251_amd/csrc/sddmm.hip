@@ -244,17 +244,19 @@ template <int NV, int PASSES, bool BF16>
 void launch_nv(const Plan& plan, const uint16_t* X, const uint16_t* Y, const uint16_t* Y_hot, int32_t N, int32_t passes,
                float* packed_out, hipStream_t stream) {
     const DeviceFormat& f = plan.fmt;
+    // without a gathered copy of Y's most used rows, a plan that kept plain entries is read through those
+    const int32_t* a2b = (!Y_hot && plan.a2b_plain.p) ? plan.a2b_plain.p : f.sparse_a_to_b.p;
     const int32_t n_items = (int32_t)plan.items.size();
     const int32_t n_blocks = (n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     const int blocks = ((n_blocks + 7) / 8) * 8;
     if (Y_hot)
         hipLaunchKernelGGL((sddmm_tiles_kernel<NV, PASSES, BF16, true>), dim3(blocks), dim3(kWavesPerBlock * 64), 0, stream,
-                           f.row_window_offset.p, f.tc_offset.p, f.sparse_a_to_b.p, f.tc_local_bit.p, plan.d_perm_pad.p,
+                           f.row_window_offset.p, f.tc_offset.p, a2b, f.tc_local_bit.p, plan.d_perm_pad.p,
                            plan.d_items.p, X, Y, Y_hot, packed_out, n_items, n_blocks, N, passes);
     else
         hipLaunchKernelGGL((sddmm_tiles_kernel<NV, PASSES, BF16, false>), dim3(blocks), dim3(kWavesPerBlock * 64), 0,
-                           stream, f.row_window_offset.p, f.tc_offset.p, f.sparse_a_to_b.p, f.tc_local_bit.p,
-                           plan.d_perm_pad.p, plan.d_items.p, X, Y, Y_hot, packed_out, n_items, n_blocks, N, passes);
+                           stream, f.row_window_offset.p, f.tc_offset.p, a2b, f.tc_local_bit.p, plan.d_perm_pad.p,
+                           plan.d_items.p, X, Y, Y_hot, packed_out, n_items, n_blocks, N, passes);
 }
 
 template <bool BF16>
@@ -312,7 +314,8 @@ void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, voi
     }
     // Y in the caller's order under a column order: gather its most used rows, as execute does for B
     const uint16_t* Y_hot = nullptr;
-    if (plan.d_col_order.p && plan.opt.operand_order == 0) {
+    // (as in execute, plans that also kept plain entries read all of Y in place when N <= 64)
+    if (plan.d_col_order.p && plan.opt.operand_order == 0 && !(plan.a2b_plain.p && N <= 64)) {
         {
             std::lock_guard<std::mutex> lock(plan.workspace_mutex);
             if (plan.b_hot_N < N && plan.n_hot > 0) {

@@ -270,6 +270,17 @@ ACC_SPMM_API int acc_spmm_execute_csr_naive(const acc_spmm_plan_t* plan, const v
 
 ACC_SPMM_API void acc_spmm_destroy(acc_spmm_plan_t* plan);
 
+/*
+ * A plan on disk (the paper amortises the preprocessing over iterative use, Section 4.3.2;
+ * this carries it across processes).  acc_spmm_plan_save writes everything execute, sddmm,
+ * update_values, the comparison kernel and plan_export need to `path`; acc_spmm_plan_load
+ * reads such a file into a new plan on the current HIP device (NULL on failure, reason in
+ * acc_spmm_last_error).  The file is only meant for the library version and machine type
+ * that wrote it: another version is refused with ACC_SPMM_ERR_UNSUPPORTED.
+ */
+ACC_SPMM_API int acc_spmm_plan_save(const acc_spmm_plan_t* plan, const char* path);
+ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_load(const char* path);
+
 /* Message of the calling thread's last failure; returns its status code (0 if none).
  * buf may be NULL. */
 ACC_SPMM_API int acc_spmm_last_error(char* buf, size_t len);

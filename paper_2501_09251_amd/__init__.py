@@ -35,7 +35,7 @@ _ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = [
     "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
-    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values",
+    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values", "acc_spmm_plan_save", "acc_spmm_plan_load",
     "acc_spmm_mtx_open", "acc_spmm_mtx_shape", "acc_spmm_mtx_csr", "acc_spmm_mtx_close",
 ]
 
@@ -109,6 +109,10 @@ def load():
     L.acc_spmm_mtx_csr.argtypes = [vp, vp, vp, vp]
     L.acc_spmm_mtx_close.restype = None
     L.acc_spmm_mtx_close.argtypes = [vp]
+    L.acc_spmm_plan_save.restype = ctypes.c_int
+    L.acc_spmm_plan_save.argtypes = [vp, ctypes.c_char_p]
+    L.acc_spmm_plan_load.restype = vp
+    L.acc_spmm_plan_load.argtypes = [ctypes.c_char_p]
     L.acc_spmm_update_values.restype = ctypes.c_int
     L.acc_spmm_update_values.argtypes = [vp, vp, vp]
     L.acc_spmm_sddmm.restype = ctypes.c_int
@@ -224,6 +228,18 @@ def read_matrix_market(path, value_type=ACC_SPMM_FP16):
     finally:
         L.acc_spmm_mtx_close(h)
     return M.value, K.value, rowptr, colidx, vals
+
+
+def acc_spmm_plan_save(plan, path):
+    if load().acc_spmm_plan_save(plan, os.fsencode(path)) != 0:
+        _raise()
+
+
+def acc_spmm_plan_load(path):
+    h = load().acc_spmm_plan_load(os.fsencode(path))
+    if not h:
+        _raise()
+    return h
 
 
 def acc_spmm_update_values(plan, csr_vals, stream=None):

@@ -454,6 +454,19 @@ int acc_spmm_execute_csr_naive(const acc_spmm_plan_t* plan, const void* B, int32
 
 void acc_spmm_destroy(acc_spmm_plan_t* plan) { delete plan; }
 
+int acc_spmm_plan_save(const acc_spmm_plan_t* plan, const char* path) {
+    return guarded([&] {
+        if (!plan) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        save_plan(plan->plan, path);
+    });
+}
+
+acc_spmm_plan_t* acc_spmm_plan_load(const char* path) {
+    acc_spmm_plan_t* out = nullptr;
+    guarded([&] { out = load_plan(path); });
+    return out;
+}
+
 int acc_spmm_last_error(char* buf, size_t len) {
     if (buf && len) {
         std::strncpy(buf, g_err_msg.c_str(), len - 1);

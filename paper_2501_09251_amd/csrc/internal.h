@@ -175,6 +175,9 @@ void launch_update_values(const Plan& plan, const void* csr_vals, hipStream_t st
 void launch_sddmm(const Plan& plan, const void* X, const void* Y, int32_t N, void* out, int32_t use_values,
                   hipStream_t stream);
 
+// serialize.cpp: a plan to and from a file
+void save_plan(const Plan& plan, const char* path);
+
 // mtx.cpp: Matrix Market coordinate file -> host CSR
 struct MtxFile;
 MtxFile* read_matrix_market(const char* path, int32_t value_type);
@@ -189,3 +192,7 @@ struct acc_spmm_mtx_s;  // opaque to callers: an accspmm::MtxFile
 struct acc_spmm_plan_s {
     accspmm::Plan plan;
 };
+
+namespace accspmm {
+acc_spmm_plan_t* load_plan(const char* path);
+}

@@ -197,3 +197,14 @@ def test_schedule_auto_follows_the_ibd_threshold():
     assert ibd > 8 and slots == -(-4000 // 64)
     items2, _, _ = acc.acc_spmm_schedule_host(skew, acc.ACC_SPMM_AUTO, 64, ibd_threshold=1e9)
     assert len(items2) == 100
+
+
+def test_plan_load_refuses_files_that_are_not_plans(tmp_path):
+    bad = tmp_path / "x.bin"
+    bad.write_bytes(b"not a plan at all, just some bytes that are long enough to hold a header")
+    with pytest.raises(acc.AccSpmmError) as e:
+        acc.acc_spmm_plan_load(str(bad))
+    assert e.value.code == -1
+    with pytest.raises(acc.AccSpmmError) as e:
+        acc.acc_spmm_plan_load(str(tmp_path / "missing.bin"))
+    assert e.value.code == -1

@@ -600,6 +600,45 @@ def test_execute_argument_errors():
         acc.acc_spmm_destroy(plan)
 
 
+def test_plan_survives_a_round_trip_through_a_file(tmp_path):
+    """Save, load: every exported array and statistic is the same, and so are C, the row-per-wave
+    result and the sddmm output, bit for bit."""
+    w = wl.config(2, 6)
+    X = wl.dense(w.M, 64, 3, "normal", 0.0, 1.0)
+    opt = acc.make_options(reorder=acc.ACC_SPMM_ON, load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16,
+                           column_order=acc.ACC_SPMM_ON, keep_csr=1, keep_entry_map=1)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+    path = str(tmp_path / "plan.bin")
+    try:
+        acc.acc_spmm_plan_save(plan, path)
+        twin = acc.acc_spmm_plan_load(path)
+        try:
+            assert acc.acc_spmm_plan_stats(twin) == acc.acc_spmm_plan_stats(plan)
+            for which in range(11):
+                np.testing.assert_array_equal(acc.acc_spmm_plan_export(twin, which), acc.acc_spmm_plan_export(plan, which))
+            for N in (128, 40):                                     # gathered rows at 128, plain entries at 40
+                B = wl.dense(w.K, N, 6, "normal", 0.0, 1.0)
+                C = run_spmm(twin, B, w.M, N)
+                np.testing.assert_array_equal(C, run_spmm(plan, B, w.M, N))
+                check_against_oracle(w.rowptr, w.colidx, w.vals, B, C)
+                np.testing.assert_array_equal(run_spmm(twin, B, w.M, N, naive=True), run_spmm(plan, B, w.M, N, naive=True))
+            Y = wl.dense(w.K, 64, 4, "normal", 0.0, 1.0)
+            np.testing.assert_array_equal(run_sddmm(twin, X, Y, w.nnz, 64, 1), run_sddmm(plan, X, Y, w.nnz, 64, 1))
+        finally:
+            acc.acc_spmm_destroy(twin)
+    finally:
+        acc.acc_spmm_destroy(plan)
+    # a damaged file is refused, not trusted
+    blob = open(path, "rb").read()
+    for name, data in (("short.bin", blob[: len(blob) // 2]), ("magic.bin", b"XX" + blob[2:]),
+                       ("version.bin", blob[:8] + b"\x09\x00\x00\x00" + blob[12:])):
+        bad = tmp_path / name
+        bad.write_bytes(data)
+        with pytest.raises(acc.AccSpmmError) as e:
+            acc.acc_spmm_plan_load(str(bad))
+        assert e.value.code in (-1, -3)
+
+
 def test_widest_rows():
     """N at the documented maximum (many slab launches along gridDim.y) and just past a slab boundary."""
     rng = np.random.default_rng(4)

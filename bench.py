@@ -167,7 +167,7 @@ def main() -> int:
         gather_ms.append(g)
     tiles_avg = float(np.mean(tiles_ms))
     # a launch-bound workload is better described by many launches back to back
-    back_to_back_us = None
+    back_to_back_us = graph_replay_us = None
     if t_step < 1e-4:
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -175,6 +175,19 @@ def main() -> int:
             acc.acc_spmm_execute(plan, B, w.N, C, stream)
         torch.cuda.synchronize()
         back_to_back_us = (time.perf_counter() - t0) / 100 * 1e6
+        # the same 100 calls captured once in a HIP graph and replayed (execute only enqueues kernels)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(100):
+                acc.acc_spmm_execute(plan, B, w.N, C, torch.cuda.current_stream().cuda_stream)
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_replay_us = (time.perf_counter() - t0) / 1000 * 1e6
+        del graph
     clocks = gpu_clocks()
     alg_bytes = tr["a_bytes"] + tr["b_bytes"] + tr["c_bytes"]
     achieved = alg_bytes / (tiles_avg * 1e-3) / 1e9 if tiles_avg > 0 else 0.0
@@ -281,6 +294,7 @@ def main() -> int:
                  "column_order_s": st["t_column_order_s"]},
         "parity_spot_check": {"rows": int(len(rows)), "ok": bool(ok), "worst_error_over_limit": ratio},
         "back_to_back_100_launches_us": back_to_back_us,
+        "hip_graph_of_100_launches_us_per_launch": graph_replay_us,
         "clocks": clocks,
         "generate_s": t_gen,
         "paper_context": PAPER_CONTEXT,

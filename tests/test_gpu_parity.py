@@ -639,6 +639,38 @@ def test_plan_survives_a_round_trip_through_a_file(tmp_path):
         assert e.value.code in (-1, -3)
 
 
+def test_execute_can_be_captured_in_a_hip_graph():
+    """After one eager call (which allocates the plan's buffers), execute only enqueues kernels:
+    captured into a graph and replayed with new contents of B, with eager work between the
+    replays, it gives the eager result every time."""
+    w = wl.config(2, 6)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(reorder=acc.ACC_SPMM_ON, load_balance=acc.ACC_SPMM_ON,
+                                                 max_tiles_per_item=16, column_order=acc.ACC_SPMM_ON))
+    try:
+        dev = torch.device("cuda:0")
+        B = torch.from_numpy(w.B.view(np.int16)).to(dev)
+        C = torch.full((w.M, w.N), float("nan"), device=dev)
+        C_eager = torch.empty_like(C)
+        acc.acc_spmm_execute(plan, B, w.N, C, torch.cuda.current_stream().cuda_stream)     # allocates
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            acc.acc_spmm_execute(plan, B, w.N, C, torch.cuda.current_stream().cuda_stream)
+        for rep in range(4):
+            new_B = wl.dense(w.K, w.N, 100 + rep, "normal", 0.0, 1.0)
+            B.copy_(torch.from_numpy(new_B.view(np.int16)).to(dev))
+            C.fill_(float("nan"))
+            graph.replay()
+            torch.cuda.synchronize()
+            acc.acc_spmm_execute(plan, B, w.N, C_eager, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert torch.equal(C, C_eager), f"replay {rep} differs from the eager call"
+            check_against_oracle(w.rowptr, w.colidx, w.vals, new_B, C.cpu().numpy())
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 def test_widest_rows():
     """N at the documented maximum (many slab launches along gridDim.y) and just past a slab boundary."""
     rng = np.random.default_rng(4)

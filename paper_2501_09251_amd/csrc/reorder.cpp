@@ -67,7 +67,8 @@ private:
     std::vector<Edge*> free_[40];
 };
 
-// Step I.  parent[v] = community v was merged into (-1: root); children lists in merge order.
+// Step I.  parent[v] = community v was merged into (-1: root); first_child / next_sibling list
+// every community's children from the last merged to the first.
 // `work` counts the edge records visited; when it exceeds `work_limit` (> 0) the
 // construction stops early and returns false.
 bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
@@ -84,18 +85,30 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
         for (int64_t d = 0; d <= maxdeg; ++d) start[d + 1] += start[d];
         for (int64_t i = 0; i < M; ++i) order[start[gptr[i + 1] - gptr[i]]++] = (int32_t)i;
     }
-    parent.assign(M, -1);
-    first_child.assign(M, -1);
-    next_sibling.assign(M, -1);
-    std::vector<int32_t> last_child(M, -1), up(M);
+    // What a vertex's own turn reads and writes, in one 24-byte record: consecutive turns visit
+    // unrelated ids, so with one array per field every field was a cache miss of its own.
+    struct Node {
+        int32_t parent = -1;
+        int32_t next_sibling = -1;   // next child of the same parent, in reverse merge order
+        Edge* agg_ptr = nullptr;     // community edges as of the vertex's turn (kept until the parent's turn)
+        int32_t agg_len = 0;
+    };
+    std::vector<Node> node(M);
+    // A merge touches the community joined only through compact arrays (the head of its child
+    // list and whether it has had its turn), not through its record: which community that is
+    // is known only when the gains are, so nothing can be requested ahead for it.  Children are
+    // pushed at the front; their order is immaterial for the sums of Step I, and the caller
+    // reads the lists back to front to get the merge order.
+    std::vector<int32_t>& head = first_child;
+    head.assign(M, -1);
+    std::vector<uint8_t> done(M, 0);
+    // What every edge record touches stays in compact arrays (they are hit far more often and
+    // should stay as cache-resident as they can): union-find links, scratch weights, degree sums.
+    std::vector<int32_t> up(M);
     std::vector<int64_t> dsum(M);
-    // community edges of v as of v's turn (kept only until the parent's turn)
     EdgeArena arena;
-    std::vector<Edge*> agg_ptr(M, nullptr);
-    std::vector<int32_t> agg_len(M, 0);
     std::vector<uint32_t> weight(M, 0);     // scratch: weight towards each community
     std::vector<int32_t> touched;
-    std::vector<char> done(M, 0);           // vertex has had its turn
     for (int64_t i = 0; i < M; ++i) { up[i] = (int32_t)i; dsum[i] = gptr[i + 1] - gptr[i]; }
     auto find = [&](int32_t x) {  // union-find root with full path compression
         int32_t r = x;
@@ -104,30 +117,52 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
         return r;
     };
     work = 0;
-    // The loop is bound by random accesses into up[], weight[] and dsum[] (tens of MB).  Each
-    // turn therefore runs in streaming passes over the gathered edge records, so that the
-    // cache misses of one pass are all in flight together: (1) collect the records and
-    // prefetch their union-find cells, (2) hop once and prefetch the next cell, (3) resolve
-    // roots and prefetch their weight cells, (4) accumulate.
+    // Each turn runs in streaming passes over the gathered edge records, so that the cache misses
+    // of one pass are all in flight together: (1) collect the records and prefetch their
+    // union-find cells, (2) hop once and prefetch the next cell, (3) resolve roots and prefetch
+    // their weight cells, (4) accumulate.  The records of the coming turns are requested ahead:
+    // record, row pointer and list head kFar turns ahead, then the adjacency row and the first
+    // child's record kMid turns ahead, then that child's edge list kNear turns ahead.
+    constexpr int64_t kFar = 24, kMid = 16, kNear = 8;
     std::vector<Edge> buf;
     for (int64_t step = 0; step < M; ++step) {
         const int32_t v = order[step];
         if (work_limit > 0 && work > work_limit) return false;
+        if (step + kFar < M) {
+            const int32_t f = order[step + kFar];
+            __builtin_prefetch(&node[f]);
+            __builtin_prefetch(&gptr[f]);
+            __builtin_prefetch(&head[f]);
+        }
+        if (step + kMid < M) {
+            const int32_t n = order[step + kMid];
+            __builtin_prefetch(&gadj[gptr[n]]);
+            if (head[n] >= 0) __builtin_prefetch(&node[head[n]]);
+        }
+        if (step + kNear < M) {
+            const int32_t c = head[order[step + kNear]];
+            if (c >= 0) {
+                __builtin_prefetch(node[c].agg_ptr);
+                if (node[c].next_sibling >= 0) __builtin_prefetch(&node[node[c].next_sibling]);
+            }
+        }
         touched.clear();
         buf.clear();
         for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) {
             __builtin_prefetch(&up[gadj[p]]);
             buf.push_back(Edge{gadj[p], 1u});
         }
-        for (int32_t c = first_child[v]; c >= 0; c = next_sibling[c]) {
-            const Edge* list = agg_ptr[c];
-            const int32_t n = agg_len[c];
+        for (int32_t c = head[v]; c >= 0; c = node[c].next_sibling) {
+            const Edge* list = node[c].agg_ptr;
+            const int32_t n = node[c].agg_len;
+            const int32_t nc = node[c].next_sibling;
+            if (nc >= 0) __builtin_prefetch(&node[nc]);
             for (int32_t k = 0; k < n; ++k) {
                 __builtin_prefetch(&up[list[k].to]);
                 buf.push_back(list[k]);
             }
-            if (list) arena.give_back(agg_ptr[c], EdgeArena::size_class((size_t)n));
-            agg_ptr[c] = nullptr;
+            if (list) arena.give_back(node[c].agg_ptr, EdgeArena::size_class((size_t)n));
+            node[c].agg_ptr = nullptr;
         }
         work += (int64_t)buf.size() + 1;
         for (Edge& e : buf) {  // one hop up, and ask for the next cell
@@ -159,18 +194,24 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
             Edge* mine = arena.take(EdgeArena::size_class(touched.size()));
             size_t k = 0;
             for (int32_t r : touched) mine[k++] = Edge{r, weight[r]};
-            agg_ptr[v] = mine;
-            agg_len[v] = (int32_t)touched.size();
+            node[v].agg_ptr = mine;
+            node[v].agg_len = (int32_t)touched.size();
         }
         for (int32_t r : touched) weight[r] = 0;
         if (merge) {
-            parent[v] = best;
+            node[v].parent = best;
             up[v] = best;
-            if (last_child[best] < 0) first_child[best] = v; else next_sibling[last_child[best]] = v;
-            last_child[best] = v;
+            node[v].next_sibling = head[best];
+            head[best] = v;
             dsum[best] += dsum[v];
         }
         done[v] = 1;
+    }
+    parent.resize(M);
+    next_sibling.resize(M);
+    for (int64_t i = 0; i < M; ++i) {
+        parent[i] = node[i].parent;
+        next_sibling[i] = node[i].next_sibling;
     }
     return true;
 }
@@ -197,15 +238,14 @@ bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, 
     for (int64_t r = 0; r < M; ++r) {
         if (parent[r] >= 0) continue;
         const int64_t tree_begin = (int64_t)seq.size();
-        // iterative pre-order: children pushed in reverse so that the first child pops first
+        // iterative pre-order; the child lists run from the last merged to the first, so pushing
+        // them in list order leaves the first merged child on top
         stack.push_back((int32_t)r);
         while (!stack.empty()) {
             int32_t x = stack.back();
             stack.pop_back();
             seq.push_back(x);
-            const size_t mark = stack.size();
             for (int32_t c = first_child[x]; c >= 0; c = next_sibling[c]) stack.push_back(c);
-            std::reverse(stack.begin() + mark, stack.end());
         }
         for (int64_t s = tree_begin; s < (int64_t)seq.size(); s += seg_len) seg_start.push_back(s);
     }

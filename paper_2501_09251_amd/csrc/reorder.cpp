@@ -124,7 +124,8 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
     // record, row pointer and list head kFar turns ahead, then the adjacency row and the first
     // child's record kMid turns ahead, then that child's edge list kNear turns ahead.
     constexpr int64_t kFar = 24, kMid = 16, kNear = 8;
-    std::vector<Edge> buf;
+    std::vector<Edge> buf(1024);
+    touched.resize(1024);
     for (int64_t step = 0; step < M; ++step) {
         const int32_t v = order[step];
         if (work_limit > 0 && work > work_limit) return false;
@@ -146,11 +147,15 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
                 if (node[c].next_sibling >= 0) __builtin_prefetch(&node[node[c].next_sibling]);
             }
         }
-        touched.clear();
-        buf.clear();
+        // size the record buffer once per turn (own adjacency + the children's lists), then fill it
+        size_t n_rec = (size_t)(gptr[v + 1] - gptr[v]);
+        for (int32_t c = head[v]; c >= 0; c = node[c].next_sibling) n_rec += (size_t)node[c].agg_len;
+        if (buf.size() < n_rec) buf.resize(std::max(n_rec, buf.size() * 2));
+        if (touched.size() < n_rec) touched.resize(std::max(n_rec, touched.size() * 2));
+        Edge* out = buf.data();
         for (int64_t p = gptr[v]; p < gptr[v + 1]; ++p) {
             __builtin_prefetch(&up[gadj[p]]);
-            buf.push_back(Edge{gadj[p], 1u});
+            *out++ = Edge{gadj[p], 1u};
         }
         for (int32_t c = head[v]; c >= 0; c = node[c].next_sibling) {
             const Edge* list = node[c].agg_ptr;
@@ -159,45 +164,48 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
             if (nc >= 0) __builtin_prefetch(&node[nc]);
             for (int32_t k = 0; k < n; ++k) {
                 __builtin_prefetch(&up[list[k].to]);
-                buf.push_back(list[k]);
+                *out++ = list[k];
             }
             if (list) arena.give_back(node[c].agg_ptr, EdgeArena::size_class((size_t)n));
             node[c].agg_ptr = nullptr;
         }
-        work += (int64_t)buf.size() + 1;
-        for (Edge& e : buf) {  // one hop up, and ask for the next cell
-            e.to = up[e.to];
-            __builtin_prefetch(&up[e.to]);
+        Edge* const rec = buf.data();
+        work += (int64_t)n_rec + 1;
+        for (size_t i = 0; i < n_rec; ++i) {  // one hop up, and ask for the next cell
+            rec[i].to = up[rec[i].to];
+            __builtin_prefetch(&up[rec[i].to]);
         }
-        for (Edge& e : buf) {
-            e.to = find(e.to);
-            __builtin_prefetch(&weight[e.to]);
-            __builtin_prefetch(&dsum[e.to]);
+        for (size_t i = 0; i < n_rec; ++i) {
+            rec[i].to = find(rec[i].to);
+            __builtin_prefetch(&weight[rec[i].to]);
+            __builtin_prefetch(&dsum[rec[i].to]);
         }
-        for (const Edge& e : buf) {
-            const int32_t r = e.to;
+        int32_t* const tch = touched.data();
+        size_t n_touched = 0;
+        for (size_t i = 0; i < n_rec; ++i) {
+            const int32_t r = rec[i].to;
             if (r == v) continue;
-            if (weight[r] == 0) {
-                touched.push_back(r);
-            }
-            weight[r] += e.w;
+            tch[n_touched] = r;
+            n_touched += weight[r] == 0;
+            weight[r] += rec[i].w;
         }
         int32_t best = -1;
         int64_t best_s = 0;
-        for (int32_t r : touched) {
-            int64_t s = (int64_t)weight[r] * two_m - dsum[r] * dsum[v];
+        const int64_t dv = dsum[v];
+        for (size_t i = 0; i < n_touched; ++i) {
+            const int32_t r = tch[i];
+            int64_t s = (int64_t)weight[r] * two_m - dsum[r] * dv;
             if (best < 0 || s > best_s || (s == best_s && r < best)) { best = r; best_s = s; }
         }
         const bool merge = best >= 0 && best_s > 0;
         // v's edge list is needed later only if the community it joins has its turn still ahead
         if (merge && !done[best]) {
-            Edge* mine = arena.take(EdgeArena::size_class(touched.size()));
-            size_t k = 0;
-            for (int32_t r : touched) mine[k++] = Edge{r, weight[r]};
+            Edge* mine = arena.take(EdgeArena::size_class(n_touched));
+            for (size_t i = 0; i < n_touched; ++i) mine[i] = Edge{tch[i], weight[tch[i]]};
             node[v].agg_ptr = mine;
-            node[v].agg_len = (int32_t)touched.size();
+            node[v].agg_len = (int32_t)n_touched;
         }
-        for (int32_t r : touched) weight[r] = 0;
+        for (size_t i = 0; i < n_touched; ++i) weight[tch[i]] = 0;
         if (merge) {
             node[v].parent = best;
             up[v] = best;

@@ -20,6 +20,7 @@
 // on a load issued after the prefetch of the next tile's rows, which drained the pipeline.)
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 #include "execute.h"
 
@@ -153,46 +154,47 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
             }
         };
         load_window();
-        // column ids are requested a tile before the rows they address are (col_ahead: tile t+2)
+        // column ids are requested a tile before the rows they address are
         int32_t col_cur = a2b[(size_t)tb * 16 + c];
         int32_t col_next = a2b[(size_t)(tb + 1 < te ? tb + 1 : tb) * 16 + c];
-        int32_t col_ahead = col_next;
         load_y(col_cur, 0, y0);
-        TileWords words = load_words(tb), words_next = words;
-        floatx4 acc{0.f, 0.f, 0.f, 0.f};
-        int t = tb, p = 0;  // the step being contracted: pass p of tile t
-        auto step = [&](const uintx4 (&y_cur)[NV], uintx4 (&y_next)[NV]) __attribute__((always_inline)) {
-            if (p == 0) {  // first pass of a tile: ask for what the next tile needs
-                words_next = load_words(t + 1 < te ? t + 1 : t);
-                if (t > tb) {
-                    col_cur = col_next;
-                    col_next = col_ahead;
-                }
-                col_ahead = a2b[(size_t)(t + 2 < te ? t + 2 : te - 1) * 16 + c];
-                if (t == wend) {  // the previous tile closed its window: move to the window of tile t
-                    do { ++w; wend = rwo[w + 1]; } while (wend <= t);
-                    load_window();
-                }
+        TileWords words_next = load_words(tb);
+        // One tile: its passes are unrolled, the two buffers alternating pass by pass; START says
+        // which buffer holds the tile's first pass (it alternates tile by tile when PASSES is odd).
+        auto tile_step = [&](int t, auto start_tag) __attribute__((always_inline)) {
+            constexpr int START = decltype(start_tag)::value;
+            const TileWords words = words_next;
+            words_next = load_words(t + 1 < te ? t + 1 : t);
+            const int32_t col_ahead = a2b[(size_t)(t + 2 < te ? t + 2 : te - 1) * 16 + c];
+            if (t == wend) {  // the previous tile closed its window: move to the window of tile t
+                do { ++w; wend = rwo[w + 1]; } while (wend <= t);
+                load_window();
             }
-            const bool last_pass = p == PASSES - 1;
-            if (!last_pass) load_y(col_cur, p + 1, y_next);
-            else if (t + 1 < te) load_y(col_next, 0, y_next);
+            floatx4 acc{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int pp = 0; pp < PASSES; ++pp)
-                if (pp == p) contract(x[pp], y_cur, acc);
-            if (last_pass) {
-                emit(words, acc);
-                acc = floatx4{0.f, 0.f, 0.f, 0.f};
-                words = words_next;
-                p = 0;
-                ++t;
-            } else {
-                ++p;
+            for (int p = 0; p < PASSES; ++p) {
+                const bool last_pass = p == PASSES - 1;
+                if (((START + p) & 1) == 0) {
+                    if (!last_pass) load_y(col_cur, p + 1, y1);
+                    else if (t + 1 < te) load_y(col_next, 0, y1);
+                    contract(x[p], y0, acc);
+                } else {
+                    if (!last_pass) load_y(col_cur, p + 1, y0);
+                    else if (t + 1 < te) load_y(col_next, 0, y0);
+                    contract(x[p], y1, acc);
+                }
             }
+            emit(words, acc);
+            col_cur = col_next;
+            col_next = col_ahead;
         };
-        while (t < te) {
-            step(y0, y1);
-            if (t < te) step(y1, y0);
+        if constexpr (PASSES % 2 == 0) {
+            for (int t = tb; t < te; ++t) tile_step(t, std::integral_constant<int, 0>{});
+        } else {
+            for (int t = tb; t < te; t += 2) {
+                tile_step(t, std::integral_constant<int, 0>{});
+                if (t + 1 < te) tile_step(t + 1, std::integral_constant<int, 1>{});
+            }
         }
     } else {
         // wide rows: the features are visited in passes of 32*NV, X and Y re-read per tile and pass

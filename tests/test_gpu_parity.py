@@ -302,7 +302,7 @@ def check_sddmm(rowptr, colidx, vals, X, Y, got, use_values, value_type="f16"):
     assert ok, f"outside tolerance, worst error/limit = {ratio}"
 
 
-@pytest.mark.parametrize("N", [32, 64, 96, 128, 256, 512])
+@pytest.mark.parametrize("N", [32, 64, 96, 128, 256, 384, 512, 640])
 @pytest.mark.parametrize("lb,use_values", [(acc.ACC_SPMM_OFF, 0), (acc.ACC_SPMM_ON, 1)])
 def test_sddmm_all_widths(N, lb, use_values):
     rng = np.random.default_rng(N + lb)

@@ -192,14 +192,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         m.tco = p.tco[t];
     };
 
+    // kAddrHot: this lane's byte address of feature f0 in row 0 of either matrix, and the row pitch
+    const uint64_t hot_base = reinterpret_cast<uint64_t>(g_Bhot) + (uint64_t)f0 * 2;
+    const uint64_t cold_base = reinterpret_cast<uint64_t>(p.B) + (uint64_t)f0 * 2;
+    const uint32_t row_bytes = (uint32_t)N * 2u;
     auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint16_t* row;
             if constexpr (ADDR == kAddrHot) {
+                // one 32x32+64-bit multiply-add on top of the lane's two precomputed bases
                 const int32_t e = m.cols[q];
                 const bool hot = e < 0;
-                row = (hot ? g_Bhot : p.B) + (size_t)(uint32_t)(hot ? ~e : e) * (size_t)N + f0;
+                row = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes +
+                                                        (hot ? hot_base : cold_base));
             } else if constexpr (ADDR == kAddrWide) {
                 row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
             } else {

@@ -192,7 +192,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         m.tco = p.tco[t];
     };
 
-    // kAddrHot: this lane's byte address of feature f0 in row 0 of either matrix, and the row pitch
+    // 64-bit addressing: this lane's byte address of feature f0 in row 0 of either matrix, and the row pitch
     const uint64_t hot_base = reinterpret_cast<uint64_t>(g_Bhot) + (uint64_t)f0 * 2;
     const uint64_t cold_base = reinterpret_cast<uint64_t>(p.B) + (uint64_t)f0 * 2;
     const uint32_t row_bytes = (uint32_t)N * 2u;
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 row = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes +
                                                         (hot ? hot_base : cold_base));
             } else if constexpr (ADDR == kAddrWide) {
-                row = p.B + (size_t)(uint32_t)m.cols[q] * (size_t)N + f0;
+                row = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)m.cols[q] * (uint64_t)row_bytes + cold_base);
             } else {
                 const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
                 row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);

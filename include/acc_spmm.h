@@ -194,6 +194,12 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz
                                   const int32_t* csr_colidx, const uint16_t* csr_vals,
                                   const acc_spmm_options* options);
 
+/* Same as acc_spmm_plan_ex for CSR arrays that live in DEVICE memory (of the current device):
+ * they are copied to the host first, since the plan validates and reorders there. */
+ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_device(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                                                   const int32_t* csr_colidx, const uint16_t* csr_vals,
+                                                   const acc_spmm_options* options);
+
 /*
  * Enqueue C = A.B on `stream` (Algorithm 2's runtime kernel; Section 3.5's split row
  * windows are combined by a second small kernel on the same stream).

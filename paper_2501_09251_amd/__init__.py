@@ -33,7 +33,7 @@ _ARRAY_DTYPES = {
 }
 
 EXPORTED_SYMBOLS = [
-    "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
+    "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_plan_device", "acc_spmm_execute", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
     "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values", "acc_spmm_plan_save", "acc_spmm_plan_load",
     "acc_spmm_mtx_open", "acc_spmm_mtx_shape", "acc_spmm_mtx_csr", "acc_spmm_mtx_close",
@@ -97,6 +97,8 @@ def load():
     L.acc_spmm_plan.argtypes = [i64, i64, i64, vp, vp, vp]
     L.acc_spmm_plan_ex.restype = vp
     L.acc_spmm_plan_ex.argtypes = [i64, i64, i64, vp, vp, vp, ctypes.POINTER(acc_spmm_options)]
+    L.acc_spmm_plan_device.restype = vp
+    L.acc_spmm_plan_device.argtypes = [i64, i64, i64, vp, vp, vp, ctypes.POINTER(acc_spmm_options)]
     L.acc_spmm_execute.restype = ctypes.c_int
     L.acc_spmm_execute.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_execute_timed.restype = ctypes.c_int
@@ -176,6 +178,15 @@ def make_options(**kw) -> acc_spmm_options:
             raise TypeError(f"unknown option {k}")
         setattr(o, k, v)
     return o
+
+
+def acc_spmm_plan_device(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, options=None):
+    """Plan from CSR arrays in device memory (torch tensors: int32, int32, int16/float16 bit patterns)."""
+    h = load().acc_spmm_plan_device(M, K, nnz, _dev_ptr(csr_rowptr), _dev_ptr(csr_colidx), _dev_ptr(csr_vals),
+                                    ctypes.byref(options) if options is not None else None)
+    if not h:
+        _raise()
+    return h
 
 
 def acc_spmm_plan(M, K, nnz, csr_rowptr, csr_colidx, csr_vals):

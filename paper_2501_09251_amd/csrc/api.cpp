@@ -391,6 +391,27 @@ acc_spmm_plan_t* acc_spmm_plan_ex(int64_t M, int64_t K, int64_t nnz, const int32
     return out;
 }
 
+acc_spmm_plan_t* acc_spmm_plan_device(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
+                                      const int32_t* csr_colidx, const uint16_t* csr_vals,
+                                      const acc_spmm_options* options) {
+    acc_spmm_plan_t* out = nullptr;
+    guarded([&] {
+        if (M < 0 || nnz < 0 || M >= ((int64_t)1 << 31) || nnz >= ((int64_t)1 << 31))
+            fail(ACC_SPMM_ERR_INVALID_ARG, "M, K and nnz must be in [0, 2^31)");
+        if (!csr_rowptr || (nnz > 0 && (!csr_colidx || !csr_vals))) fail(ACC_SPMM_ERR_INVALID_ARG, "null CSR pointer");
+        // the plan validates and reorders on the host: bring the arrays over, then proceed as for host input
+        std::vector<int32_t> rowptr((size_t)M + 1), colidx((size_t)nnz);
+        std::vector<uint16_t> vals((size_t)nnz);
+        ACC_HIP(hipMemcpy(rowptr.data(), csr_rowptr, rowptr.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+        if (nnz > 0) {
+            ACC_HIP(hipMemcpy(colidx.data(), csr_colidx, colidx.size() * sizeof(int32_t), hipMemcpyDeviceToHost));
+            ACC_HIP(hipMemcpy(vals.data(), csr_vals, vals.size() * sizeof(uint16_t), hipMemcpyDeviceToHost));
+        }
+        out = build_plan(M, K, nnz, rowptr.data(), colidx.data(), vals.data(), options);
+    });
+    return out;
+}
+
 acc_spmm_plan_t* acc_spmm_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* csr_rowptr,
                                const int32_t* csr_colidx, const uint16_t* csr_vals) {
     return acc_spmm_plan_ex(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, nullptr);

@@ -671,6 +671,22 @@ def test_execute_can_be_captured_in_a_hip_graph():
         acc.acc_spmm_destroy(plan)
 
 
+def test_plan_from_device_arrays_equals_plan_from_host_arrays():
+    w = wl.config(4, 4)
+    host = acc.acc_spmm_plan(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals)
+    dev = acc.acc_spmm_plan_device(w.M, w.K, w.nnz, torch.from_numpy(w.rowptr).cuda(), torch.from_numpy(w.colidx).cuda(),
+                                   torch.from_numpy(w.vals.view(np.int16)).cuda())
+    try:
+        for which in range(11):
+            np.testing.assert_array_equal(acc.acc_spmm_plan_export(dev, which), acc.acc_spmm_plan_export(host, which))
+        C = run_spmm(dev, w.B, w.M, w.N)
+        np.testing.assert_array_equal(C, run_spmm(host, w.B, w.M, w.N))
+        check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C)
+    finally:
+        acc.acc_spmm_destroy(host)
+        acc.acc_spmm_destroy(dev)
+
+
 def test_widest_rows():
     """N at the documented maximum (many slab launches along gridDim.y) and just past a slab boundary."""
     rng = np.random.default_rng(4)

@@ -373,6 +373,9 @@ int guarded(F&& fn) {
     } catch (const std::exception& e) {
         set_error(ACC_SPMM_ERR_INVALID_ARG, e.what());
         return ACC_SPMM_ERR_INVALID_ARG;
+    } catch (...) {   // nothing may leave through the C boundary
+        set_error(ACC_SPMM_ERR_INVALID_ARG, "unknown failure");
+        return ACC_SPMM_ERR_INVALID_ARG;
     }
 }
 

@@ -39,7 +39,7 @@ inline int bits_for(int64_t n) {  // bits needed to hold values in [0, n)
 }
 
 // head[i] = 1 where a run of equal keys starts
-static __global__ void mark_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, int32_t* __restrict__ head) {
+[[maybe_unused]] static __global__ void mark_heads_kernel(int64_t n, const uint64_t* __restrict__ sorted, int32_t* __restrict__ head) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) head[i] = (i == 0 || sorted[i] != sorted[i - 1]) ? 1 : 0;
 }

@@ -60,17 +60,23 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
     while (rwo[w + 1] <= tb) ++w;  // the window of the first tile (whole-window items may start with empty windows)
     int wend = rwo[w + 1];
 
-    auto load_row = [&](const uint16_t* base, int32_t row, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
-        const uint16_t* p = base + (size_t)(uint32_t)row * (size_t)N + pass * (NV * 32) + g * 8;
+    // a row's address is one 32x32+64-bit multiply-add on the lane's byte address in row 0 of the matrix
+    const uint32_t row_bytes = (uint32_t)N * 2u;
+    const uint64_t x_base = reinterpret_cast<uint64_t>(X) + (uint64_t)g * 16;
+    const uint64_t y_base = reinterpret_cast<uint64_t>(Y) + (uint64_t)g * 16;
+    const uint64_t y_hot_base = reinterpret_cast<uint64_t>(Y_hot) + (uint64_t)g * 16;
+    auto load_row = [&](uint64_t base, int32_t row, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
+        const uint16_t* p = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)row * (uint64_t)row_bytes + base) +
+                            pass * (NV * 32);
 #pragma unroll
         for (int v = 0; v < NV; ++v) dst[v] = *reinterpret_cast<const uintx4*>(p + v * 32);
     };
     auto load_y = [&](int32_t e, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
         if constexpr (HOT) {
             const bool hot = e < 0;
-            load_row(hot ? Y_hot : Y, hot ? ~e : e, pass, dst);
+            load_row(hot ? y_hot_base : y_base, hot ? ~e : e, pass, dst);
         } else {
-            load_row(Y, e, pass, dst);
+            load_row(y_base, e, pass, dst);
         }
     };
     auto contract = [&](const uintx4 (&x)[NV], const uintx4 (&y)[NV], floatx4& acc) __attribute__((always_inline)) {
@@ -117,7 +123,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
             const int32_t row = perm_pad[(size_t)w * 16 + c];
 #pragma unroll
             for (int v = 0; v < NV; ++v) x[v] = uintx4{0u, 0u, 0u, 0u};
-            if (row >= 0) load_row(X, row, 0, x);
+            if (row >= 0) load_row(x_base, row, 0, x);
         };
         load_window();
         // column ids are requested one tile further ahead than the rows they address
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
             for (int p = 0; p < PASSES; ++p) {
 #pragma unroll
                 for (int v = 0; v < NV; ++v) x[p][v] = uintx4{0u, 0u, 0u, 0u};
-                if (row >= 0) load_row(X, row, p, x[p]);
+                if (row >= 0) load_row(x_base, row, p, x[p]);
             }
         };
         load_window();
@@ -209,7 +215,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
                 uintx4 x[NV], y[NV];
 #pragma unroll
                 for (int v = 0; v < NV; ++v) x[v] = uintx4{0u, 0u, 0u, 0u};
-                if (row >= 0) load_row(X, row, pass, x);
+                if (row >= 0) load_row(x_base, row, pass, x);
                 load_y(col, pass, y);
                 contract(x, y, acc);
             }

@@ -282,7 +282,9 @@ ACC_SPMM_API void acc_spmm_destroy(acc_spmm_plan_t* plan);
  * update_values, the comparison kernel and plan_export need to `path`; acc_spmm_plan_load
  * reads such a file into a new plan on the current HIP device (NULL on failure, reason in
  * acc_spmm_last_error).  The file is only meant for the library version and machine type
- * that wrote it: another version is refused with ACC_SPMM_ERR_UNSUPPORTED.
+ * that wrote it: another version is refused with ACC_SPMM_ERR_UNSUPPORTED.  The file ends
+ * in a checksum; one that was cut short or whose bytes changed is refused with
+ * ACC_SPMM_ERR_INVALID_ARG and no kernel ever sees its contents.
  */
 ACC_SPMM_API int acc_spmm_plan_save(const acc_spmm_plan_t* plan, const char* path);
 ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_load(const char* path);

@@ -4,8 +4,10 @@
 //
 // Layout: a fixed header (magic, format version, the sizes of the option and statistics structs
 // as a compatibility check), the option and statistics structs, the scalar fields of the plan,
-// then every array as a 64-bit element count followed by its bytes, in the order of `visit`.
-// Byte order and struct layout are those of the machine that wrote the file.
+// then every array as a 64-bit element count followed by its bytes, in the order of `visit`,
+// then a 64-bit checksum of everything before it.  The kernels index memory by what the arrays
+// hold, so a file whose contents changed after it was written must not reach them: the loader
+// refuses it.  Byte order and struct layout are those of the machine that wrote the file.
 #include <cstdio>
 #include <cstring>
 #include <string>
@@ -28,6 +30,30 @@ struct Scalars {
     int64_t M, W, T, nnz, sum_dw, n_slots;
 };
 
+// Four interleaved multiply-xor lanes over 64-bit words (one dependent chain would run at a
+// fraction of the disk rate on a 2 GB plan); both sides feed it the same sequence of pieces.
+class Checksum {
+public:
+    void update(const void* p, size_t n) {
+        const unsigned char* b = static_cast<const unsigned char*>(p);
+        for (; n >= 32; n -= 32, b += 32) {
+            uint64_t w[4];
+            std::memcpy(w, b, 32);
+            for (int k = 0; k < 4; ++k) lane_[k] = (lane_[k] ^ w[k]) * kMul + 1;
+        }
+        for (; n; --n, ++b) lane_[0] = (lane_[0] ^ *b) * kMul + 1;
+    }
+    uint64_t value() const {
+        uint64_t h = 0;
+        for (int k = 0; k < 4; ++k) h = (h ^ lane_[k] ^ (lane_[k] >> 29)) * kMul;
+        return h ^ (h >> 32);
+    }
+
+private:
+    static constexpr uint64_t kMul = 0x9e3779b97f4a7c15ull;
+    uint64_t lane_[4] = {1, 2, 3, 4};
+};
+
 class Writer {
 public:
     explicit Writer(const char* path) : f_(std::fopen(path, "wb")) {
@@ -36,6 +62,7 @@ public:
     ~Writer() { if (f_) std::fclose(f_); }
     void bytes(const void* p, size_t n) {
         if (n && std::fwrite(p, 1, n, f_) != n) fail(ACC_SPMM_ERR_INVALID_ARG, "write failed (disk full?)");
+        sum_.update(p, n);
     }
     template <class T> void host(const std::vector<T>& v) {
         const uint64_t n = v.size();
@@ -48,6 +75,8 @@ public:
         host(tmp);
     }
     void close() {
+        const uint64_t sum = sum_.value();
+        bytes(&sum, sizeof sum);
         const int rc = std::fclose(f_);
         f_ = nullptr;
         if (rc != 0) fail(ACC_SPMM_ERR_INVALID_ARG, "write failed on close");
@@ -55,6 +84,7 @@ public:
 
 private:
     std::FILE* f_;
+    Checksum sum_;
 };
 
 class Reader {
@@ -68,6 +98,7 @@ public:
     ~Reader() { std::fclose(f_); }
     void bytes(void* p, size_t n) {
         if (n && std::fread(p, 1, n, f_) != n) fail(ACC_SPMM_ERR_INVALID_ARG, "plan file is truncated");
+        sum_.update(p, n);
     }
     template <class T> void host(std::vector<T>& v) {
         uint64_t n = 0;
@@ -81,10 +112,19 @@ public:
         host(tmp);
         b.upload(tmp.data(), tmp.size());
     }
+    // the stored checksum follows everything read so far and ends the file
+    void close() {
+        const uint64_t expected = sum_.value();
+        uint64_t stored = 0;
+        bytes(&stored, sizeof stored);
+        if (stored != expected) fail(ACC_SPMM_ERR_INVALID_ARG, "plan file is corrupt (checksum mismatch)");
+        if (std::fgetc(f_) != EOF) fail(ACC_SPMM_ERR_INVALID_ARG, "plan file is corrupt (bytes after the checksum)");
+    }
 
 private:
     std::FILE* f_;
     uint64_t size_ = 0;
+    Checksum sum_;
 };
 
 // the arrays of a plan, in file order; A is a Writer or a Reader
@@ -158,6 +198,7 @@ acc_spmm_plan_t* load_plan(const char* path) {
         P.n_hot = s.n_hot;
         P.n_slots = s.n_slots;
         visit(r, P);
+        r.close();
         // consistency of what the kernels index by
         if (f.M != P.stats.M || (int64_t)P.perm.size() != f.M || (int64_t)f.row_window_offset.n != f.W + 1 ||
             (int64_t)f.tc_offset.n != f.T + 1 || (int64_t)f.sparse_a_to_b.n != f.T * f.TW ||

@@ -631,7 +631,9 @@ def test_plan_survives_a_round_trip_through_a_file(tmp_path):
     # a damaged file is refused, not trusted
     blob = open(path, "rb").read()
     for name, data in (("short.bin", blob[: len(blob) // 2]), ("magic.bin", b"XX" + blob[2:]),
-                       ("version.bin", blob[:8] + b"\x09\x00\x00\x00" + blob[12:])):
+                       ("version.bin", blob[:8] + b"\x09\x00\x00\x00" + blob[12:]),
+                       ("flipped.bin", blob[: len(blob) // 2] + bytes([blob[len(blob) // 2] ^ 0x10]) + blob[len(blob) // 2 + 1:]),
+                       ("last.bin", blob[:-1] + bytes([blob[-1] ^ 1])), ("longer.bin", blob + b"\x00")):
         bad = tmp_path / name
         bad.write_bytes(data)
         with pytest.raises(acc.AccSpmmError) as e:

@@ -66,6 +66,27 @@ __device__ __forceinline__ void load_chunk(const uint16_t* p, Chunk<FPL>& c) {
     }
 }
 
+// The same from a 64-bit byte address known to be in global memory.  A pointer made from an
+// integer is a generic one to the compiler, and generic (flat) loads count on both the vector
+// and the scalar/LDS wait counters, so that every wait for a scalar load would also drain the
+// B rows in flight; naming the address space keeps them on the vector counter alone.
+template <int FPL>
+__device__ __forceinline__ void load_chunk_global(uint64_t addr, Chunk<FPL>& c) {
+#define ACC_GLOBAL(T) reinterpret_cast<const __attribute__((address_space(1))) T*>(addr)
+    if constexpr (FPL == 8) {
+        uintx4 v = *ACC_GLOBAL(uintx4);
+        c.d[0] = v.x; c.d[1] = v.y; c.d[2] = v.z; c.d[3] = v.w;
+    } else if constexpr (FPL == 4) {
+        uintx2 v = *ACC_GLOBAL(uintx2);
+        c.d[0] = v.x; c.d[1] = v.y;
+    } else if constexpr (FPL == 2) {
+        c.d[0] = *ACC_GLOBAL(uint32_t);
+    } else {
+        c.d[0] = *ACC_GLOBAL(uint16_t);
+    }
+#undef ACC_GLOBAL
+}
+
 struct TileMeta {       // index words of one tile
     intx4 cols;         // this lane group's four SparseAToB entries
     uint64_t bm[4];     // TCLocalBit (wave-uniform)
@@ -199,27 +220,33 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint16_t* row;
-            if constexpr (ADDR == kAddrHot) {
-                // one 32x32+64-bit multiply-add on top of the lane's two precomputed bases
-                const int32_t e = m.cols[q];
-                const bool hot = e < 0;
-                row = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes +
-                                                        (hot ? hot_base : cold_base));
-            } else if constexpr (ADDR == kAddrWide) {
-                row = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)m.cols[q] * (uint64_t)row_bytes + cold_base);
-            } else {
+            if constexpr (ADDR == kAddrNarrow) {
                 const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
-                row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
-            }
+                const uint16_t* row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                if constexpr (TAIL) {
+                for (int s = 0; s < NS; ++s) {
+                    if constexpr (TAIL) {
 #pragma unroll
-                    for (int k = 0; k < Chunk<FPL>::DW; ++k) d.b[s][q].d[k] = 0;
-                    if (act[s]) load_chunk<FPL>(row + s * SW, d.b[s][q]);
-                } else {
-                    load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                        for (int k = 0; k < Chunk<FPL>::DW; ++k) d.b[s][q].d[k] = 0;
+                        if (act[s]) load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                    } else {
+                        load_chunk<FPL>(row + s * SW, d.b[s][q]);
+                    }
+                }
+            } else {
+                // one 32x32+64-bit multiply-add on top of the lane's precomputed base(s)
+                const int32_t e = m.cols[q];
+                const bool hot = ADDR == kAddrHot && e < 0;
+                const uint64_t row = (uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes + (hot ? hot_base : cold_base);
+#pragma unroll
+                for (int s = 0; s < NS; ++s) {
+                    if constexpr (TAIL) {
+#pragma unroll
+                        for (int k = 0; k < Chunk<FPL>::DW; ++k) d.b[s][q].d[k] = 0;
+                        if (act[s]) load_chunk_global<FPL>(row + (uint64_t)(s * SW * 2), d.b[s][q]);
+                    } else {
+                        load_chunk_global<FPL>(row + (uint64_t)(s * SW * 2), d.b[s][q]);
+                    }
                 }
             }
         }

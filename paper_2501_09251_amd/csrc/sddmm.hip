@@ -66,10 +66,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void sddmm_tiles_kernel(
     const uint64_t y_base = reinterpret_cast<uint64_t>(Y) + (uint64_t)g * 16;
     const uint64_t y_hot_base = reinterpret_cast<uint64_t>(Y_hot) + (uint64_t)g * 16;
     auto load_row = [&](uint64_t base, int32_t row, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
-        const uint16_t* p = reinterpret_cast<const uint16_t*>((uint64_t)(uint32_t)row * (uint64_t)row_bytes + base) +
-                            pass * (NV * 32);
+        // named as global memory: a pointer made from an integer would be a generic one, and generic
+        // loads also count on the wait counter of the scalar loads
+        const uint64_t a = (uint64_t)(uint32_t)row * (uint64_t)row_bytes + base + (uint64_t)(pass * (NV * 64));
 #pragma unroll
-        for (int v = 0; v < NV; ++v) dst[v] = *reinterpret_cast<const uintx4*>(p + v * 32);
+        for (int v = 0; v < NV; ++v)
+            dst[v] = *reinterpret_cast<const __attribute__((address_space(1))) uintx4*>(a + (uint64_t)(v * 64));
     };
     auto load_y = [&](int32_t e, int pass, uintx4 (&dst)[NV]) __attribute__((always_inline)) {
         if constexpr (HOT) {

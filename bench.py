@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per launch of the tile kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by the library's plain copy kernel (summaries under profiles/); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "rmat-2^23-deg32-N128": 58.89e9,
+    "rmat-2^23-deg32-N128": 59.05e9,
 }
 
 

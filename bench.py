@@ -34,6 +34,9 @@ HBM_PEAK_GBS = 8000.0
 # runs scaled by the library's plain copy kernel (summaries under profiles/); None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     "rmat-2^23-deg32-N128": 59.05e9,
+    "rmat-2^20-deg16-sym-N128": 3.09e9,
+    "stencil27-128^3-N64": 1.68e9,
+    "sbm-2^18-c64-N256": 0.99e9,
 }
 
 

@@ -160,6 +160,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int sh = ((c & 3) << 4) | (g << 2);
     const uint64_t below_mask = (1ull << sh) - 1ull;
     const bool w1 = wq >= 1, w2 = wq >= 2, w3 = wq >= 3;
+    // Cooperative fetch: byte-permute selectors, entry (lane & 15) = a pattern of four bits.  Output
+    // half j is half popcount(bits below j) of the lane's four consecutive values if bit j is set
+    // (bytes 2k, 2k+1), else the constant zero (selector byte 0x0c).
+    uint32_t lut_lo = 0, lut_hi = 0;
+    if constexpr (COOP) {
+        const uint32_t pat = (uint32_t)lane & 15u;
+        uint32_t sel[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t k = (uint32_t)__builtin_popcount(pat & ((1u << j) - 1u));
+            sel[j] = ((pat >> j) & 1u) ? (((2u * k + 1u) << 8) | (2u * k)) : 0x0c0cu;
+        }
+        lut_lo = sel[0] | (sel[1] << 16);
+        lut_hi = sel[2] | (sel[3] << 16);
+    }
 
     floatx4 acc[NS][FPL];
 #pragma unroll
@@ -290,36 +305,45 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
     auto operand_a = [&](const TileData<FPL, NS>& d) __attribute__((always_inline)) -> uintx2 {
         const uint32_t nib = d.nib;
-        uint32_t h[4];
         if constexpr (COOP) {
-            uint32_t r[4];
-            r[0] = d.v[3];
-            r[1] = r[0] + (nib & 1u);
-            r[2] = r[1] + ((nib >> 1) & 1u);
-            r[3] = r[2] + ((nib >> 2) & 1u);
+            // This lane's values are halves r0..r0+3 of what the wave loaded (r0 = d.v[3]): they lie in
+            // the dwords j, j+1, j+2 with j = r0 >> 1, each held by lane (dword & 63) of chunk
+            // (dword >> 6).  Fetch the three, shift them down by the odd half, and route half k to the
+            // k-th set bit of nib (zero to the clear bits) with two byte permutes whose selectors come
+            // from a 16-entry table that lanes 0..15 hold.
+            const uint32_t r0 = d.v[3];
+            const uint32_t j = r0 >> 1;
             const int nchunk = __builtin_amdgcn_readfirstlane((int)d.nchunk);
+            uint32_t w[3];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int addr = (int)((r[q] >> 1) << 2);  // source lane * 4; the hardware uses it modulo 64 lanes
+            for (int k = 0; k < 3; ++k) {
+                const uint32_t dw = j + (uint32_t)k;
+                const int addr = (int)(dw << 2);  // source lane * 4; the hardware uses it modulo 64 lanes
                 uint32_t x = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[0]);
                 if (nchunk > 1) {
                     const uint32_t x1 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[1]);
-                    x = ((r[q] >> 7) == 1u) ? x1 : x;
+                    x = ((dw >> 6) == 1u) ? x1 : x;
                 }
                 if (nchunk > 2) {
                     const uint32_t x2 = (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int)d.v[2]);
-                    x = ((r[q] >> 7) == 2u) ? x2 : x;
+                    x = ((dw >> 6) == 2u) ? x2 : x;
                 }
-                h[q] = (r[q] & 1u) ? (x >> 16) : (x & 0xFFFFu);
+                w[k] = x;
             }
+            const uint32_t sh = (r0 & 1u) << 4;
+            const uint32_t lo = __builtin_amdgcn_alignbit(w[1], w[0], sh);  // halves r0, r0+1
+            const uint32_t hi = __builtin_amdgcn_alignbit(w[2], w[1], sh);  // halves r0+2, r0+3
+            const int at = (int)(nib << 2);
+            const uint32_t s_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_lo);
+            const uint32_t s_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_hi);
+            return uintx2{__builtin_amdgcn_perm(hi, lo, s_lo), __builtin_amdgcn_perm(hi, lo, s_hi)};
         } else {
-            h[0] = d.v[0]; h[1] = d.v[1]; h[2] = d.v[2]; h[3] = d.v[3];
+            const uint32_t a0 = (nib & 1u) ? d.v[0] : 0u;
+            const uint32_t a1 = (nib & 2u) ? d.v[1] : 0u;
+            const uint32_t a2 = (nib & 4u) ? d.v[2] : 0u;
+            const uint32_t a3 = (nib & 8u) ? d.v[3] : 0u;
+            return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
         }
-        const uint32_t a0 = (nib & 1u) ? h[0] : 0u;
-        const uint32_t a1 = (nib & 2u) ? h[1] : 0u;
-        const uint32_t a2 = (nib & 4u) ? h[2] : 0u;
-        const uint32_t a3 = (nib & 8u) ? h[3] : 0u;
-        return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
     };
 
     auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) __attribute__((always_inline)) {

@@ -208,3 +208,19 @@ def test_plan_load_refuses_files_that_are_not_plans(tmp_path):
     with pytest.raises(acc.AccSpmmError) as e:
         acc.acc_spmm_plan_load(str(tmp_path / "missing.bin"))
     assert e.value.code == -1
+
+
+def test_autograd_wrapper_has_no_cpu_path():
+    """Without a GPU the wrapper refuses to build a Graph (it never computes on the host), and it
+    checks its arguments before touching the library."""
+    torch = pytest.importorskip("torch")
+    from paper_2501_09251_amd import gnn
+    vals = torch.ones(2, dtype=torch.float16)
+    if not torch.cuda.is_available():
+        with pytest.raises(RuntimeError, match="needs a GPU"):
+            gnn.Graph(2, 2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32), vals)
+    else:
+        with pytest.raises(TypeError):
+            gnn.Graph(2, 2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32), vals.float())
+        with pytest.raises(ValueError):
+            gnn.Graph(3, 2, np.array([0, 1, 2], np.int32), np.array([0, 1], np.int32), vals)

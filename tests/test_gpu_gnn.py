@@ -198,3 +198,36 @@ def test_graph_conv_module_trains_one_step():
         assert float(layer.bias.grad.abs().max()) > 0
     finally:
         g.close()
+
+
+def test_rectangular_and_empty_graphs():
+    rng = np.random.default_rng(17)
+    M, K, N = 120, 70, 32
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.08, empty_row_frac=0.2)
+    B_bits = wl.dense(K, N, 51, "normal", 0.0, 1.0)
+    R_bits = wl.dense(M, N, 52, "normal", 0.0, 1.0)
+    g = gnn().Graph(M, K, rowptr, colidx, half_tensor(vals))
+    try:
+        B = half_tensor(B_bits, grad=True)
+        C = g.aggregate(B)
+        assert C.shape == (M, N)
+        ref, bound = oracle.spmm(rowptr, colidx, vals, B_bits)
+        ok, ratio = oracle.within_bound(C.detach().cpu().numpy(), ref, bound)
+        assert ok, ratio
+        (C * half_tensor(R_bits).float()).sum().backward()
+        t_rowptr, t_colidx, pos = transposed_csr(M, K, rowptr, colidx)
+        ref, bound = oracle.spmm(t_rowptr, t_colidx, vals[pos], R_bits)
+        assert B.grad.shape == (K, N)
+        check_rounded(B.grad, ref, bound)
+    finally:
+        g.close()
+    # no stored entries at all: C is zero and so is the gradient
+    empty = gnn().Graph(M, K, np.zeros(M + 1, np.int32), np.zeros(0, np.int32), torch.zeros(0, dtype=torch.float16))
+    try:
+        B = half_tensor(B_bits, grad=True)
+        C = empty.aggregate(B)
+        assert C.shape == (M, N) and float(C.detach().abs().max()) == 0.0
+        C.sum().backward()
+        assert float(B.grad.abs().max()) == 0.0
+    finally:
+        empty.close()

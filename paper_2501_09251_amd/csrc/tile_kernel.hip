@@ -407,16 +407,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             after_tile(tt);
         }
     } else {
-        // Ring of R = DEPTH+1 buffers; tile x uses slot (x - tb) % R.  vmcnt retires loads in
-        // issue order, so the index words of tile tt+DEPTH+1 are requested *before* the data
-        // of tile tt+DEPTH: waiting for index words then never drains the data behind them,
-        // and DEPTH tiles of B rows stay in flight while tile tt is multiplied.
+        // Ring of R = DEPTH+1 buffers; tile x uses slot (x - tb) % R, for its data and, before
+        // that, for its index words.  vmcnt retires loads in issue order: using the column ids of a
+        // tile waits for every load issued before them.  They are therefore requested DEPTH+1 tiles
+        // before the rows they address (tile tt+2*DEPTH+1 while tile tt is multiplied), so that the
+        // wait leaves the rows of the DEPTH tiles issued since then in flight.
         TileMeta meta[R];
         TileData<FPL, NS> data[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) load_meta(tb + r, meta[r]);
 #pragma unroll
-        for (int r = 0; r < DEPTH; ++r) issue(meta[r], data[r]);
+        for (int r = 0; r < DEPTH; ++r) {
+            issue(meta[r], data[r]);
+            load_meta(tb + R + r, meta[r]);
+        }
         for (int t = tb; t < te; t += R) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
@@ -426,10 +430,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 // with the scalar index loads issued next
                 const uintx2 au = operand_a(data[r]);
                 if constexpr (COOP) __builtin_amdgcn_sched_barrier(0);
-                TileMeta next_meta;
-                load_meta(tt + DEPTH + 1, next_meta);                     // slot r, free since tile tt was issued
-                issue(meta[(r + DEPTH) % R], data[(r + DEPTH) % R]);     // tile tt+DEPTH
-                meta[r] = next_meta;
+                const int s = (r + DEPTH) % R;            // slot of tile tt+DEPTH
+                issue(meta[s], data[s]);
+                load_meta(tt + 2 * DEPTH + 1, meta[s]);   // the slot's next tile
                 multiply(data[r], au);
                 after_tile(tt);
             }

@@ -220,6 +220,16 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_device(int64_t M, int64_t K, int64_t
 ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 
 /*
+ * acc_spmm_execute with C in 16 bits: C is DEVICE row-major M x N in the plan's value type
+ * (IEEE half or bfloat16), each element the fp32 result rounded to nearest even.  The
+ * accumulation is in fp32 as in acc_spmm_execute (the partial sums of split windows too); only
+ * the final store is narrow, which halves the bytes written.  Not an operation of the paper
+ * (its C is fp32): for layers that would round C to 16 bits anyway.  Same arguments, alignment
+ * (C 16-byte aligned), errors and stream behaviour as acc_spmm_execute.
+ */
+ACC_SPMM_API int acc_spmm_execute_c16(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
+
+/*
  * acc_spmm_execute with per-kernel timing, for benchmarks: records HIP events on `stream`
  * around the gather of B (if the plan does one), the tile kernel and the split-window
  * combine kernel, waits for them, and returns the durations in milliseconds (gather_ms and

@@ -427,6 +427,13 @@ int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void
     });
 }
 
+int acc_spmm_execute_c16(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream) {
+    return guarded([&] {
+        if (!plan || !C || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, true);
+    });
+}
+
 int acc_spmm_execute_timed(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream,
                            float* tiles_ms, float* combine_ms, float* gather_ms) {
     return guarded([&] {

@@ -7,6 +7,7 @@ namespace accspmm {
 constexpr int kWavesPerBlock = 4;   // wavefronts (work items) per thread block of the tile kernel
 constexpr int kMaxN = 65536;
 constexpr int kAddrNarrow = 0, kAddrWide = 1, kAddrHot = 2;   // how the tile kernel addresses rows of B
+constexpr int kStoreStreaming = 1, kStoreNarrow = 2;           // bits of store_mode: nontemporal C stores; 16-bit C
 
 struct ExecParams {
     const int32_t* __restrict__ rwo;
@@ -27,7 +28,7 @@ struct ExecParams {
     bool coop;         // cooperative value fetch
     bool tail;         // N is not a whole number of slabs
     bool bf16;         // values are bfloat16
-    int32_t fpl, ns, grid_y, depth, streaming_stores;
+    int32_t fpl, ns, grid_y, depth, store_mode;
 };
 
 // One function per (features per lane, value type); each lives in its own object file,

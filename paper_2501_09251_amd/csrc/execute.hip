@@ -15,19 +15,32 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
 // Sum the partial tiles of each split window and write the rows of C (Section 3.5: the
 // write-back of a window shared by several work items).  One block per split window.
+// narrow = 0: C is fp32.  1 / 2: C holds IEEE half / bfloat16 values (round to nearest even).
+__device__ __forceinline__ uint32_t narrow_bits(float x, int narrow) {
+    if (narrow == 2) {
+        const uint32_t u = __builtin_bit_cast(uint32_t, x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    }
+    return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x);
+}
+
 __global__ __launch_bounds__(256) void combine_split_kernel(const SplitWindow* __restrict__ splits,
                                                             const float* __restrict__ ws,
                                                             const int32_t* __restrict__ perm_pad,
-                                                            float* __restrict__ C, int32_t N) {
+                                                            void* __restrict__ C_any, int32_t N, int32_t narrow) {
     const SplitWindow sw = splits[blockIdx.x];
-    if (N & 3) {  // rows of C are not 16-byte aligned: one float at a time
+    float* const C = static_cast<float*>(C_any);
+    uint16_t* const C16 = static_cast<uint16_t*>(C_any);
+    if (N & 3) {  // rows of C are not 16-byte aligned: one value at a time
         for (int e = threadIdx.x; e < 16 * N; e += blockDim.x) {
             const int r = e / N, j = e - r * N;
             const int row = perm_pad[(size_t)sw.window * 16 + r];
             if (row < 0) continue;
             float s = 0.f;
             for (int slot = sw.slot_begin; slot < sw.slot_end; ++slot) s += ws[((size_t)slot * 16 + r) * (size_t)N + j];
-            __builtin_nontemporal_store(s, C + (size_t)row * (size_t)N + j);
+            if (narrow) C16[(size_t)row * (size_t)N + j] = (uint16_t)narrow_bits(s, narrow);
+            else __builtin_nontemporal_store(s, C + (size_t)row * (size_t)N + j);
         }
         return;
     }
@@ -39,7 +52,14 @@ __global__ __launch_bounds__(256) void combine_split_kernel(const SplitWindow* _
         floatx4 s{0.f, 0.f, 0.f, 0.f};
         for (int slot = sw.slot_begin; slot < sw.slot_end; ++slot)
             s += *reinterpret_cast<const floatx4*>(ws + ((size_t)slot * 16 + r) * (size_t)N + j);
-        __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(C + (size_t)row * (size_t)N + j));
+        if (narrow) {
+            typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+            const uintx2 v{narrow_bits(s[0], narrow) | (narrow_bits(s[1], narrow) << 16),
+                           narrow_bits(s[2], narrow) | (narrow_bits(s[3], narrow) << 16)};
+            *reinterpret_cast<uintx2*>(C16 + (size_t)row * (size_t)N + j) = v;
+        } else {
+            __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(C + (size_t)row * (size_t)N + j));
+        }
     }
 }
 
@@ -79,7 +99,7 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
 }  // namespace
 
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream, float* tiles_ms,
-                    float* combine_ms, float* gather_ms) {
+                    float* combine_ms, float* gather_ms, bool narrow_c) {
     const bool timed = tiles_ms != nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     if (timed) {
@@ -163,7 +183,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     if (!p.tail && p.ns == 2 && p.fpl != 8) p.tail = true;  // shape compiled only in its general form
     const int default_depth = (p.fpl == 8 && p.ns == 1) ? 3 : (p.fpl == 8 ? 2 : 1);
     p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
-    p.streaming_stores = plan.opt.streaming_stores != 0;
+    p.store_mode = (plan.opt.streaming_stores != 0 ? kStoreStreaming : 0) | (narrow_c ? kStoreNarrow : 0);
     p.bf16 = plan.opt.value_type == ACC_SPMM_BF16;
     if (timed) ACC_HIP(hipEventRecord(ev[0], stream));
     if (p.n_items > 0) {
@@ -182,7 +202,8 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     if (timed) ACC_HIP(hipEventRecord(ev[1], stream));
     if (!plan.splits.empty()) {
         hipLaunchKernelGGL(combine_split_kernel, dim3((unsigned)plan.splits.size()), dim3(256), 0, stream,
-                           plan.d_splits.p, plan.workspace.p, plan.d_perm_pad.p, static_cast<float*>(C), N);
+                           plan.d_splits.p, plan.workspace.p, plan.d_perm_pad.p, C, N,
+                           narrow_c ? (plan.opt.value_type == ACC_SPMM_BF16 ? 2 : 1) : 0);
         ACC_HIP(hipGetLastError());
     }
     if (timed) {

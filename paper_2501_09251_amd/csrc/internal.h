@@ -165,9 +165,11 @@ struct Plan {
 };
 
 // execute.hip
-// tiles_ms non-null: time the kernels with events and wait for them
+// tiles_ms non-null: time the kernels with events and wait for them.  narrow_c: C holds 16-bit
+// values of the plan's value type instead of fp32.
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream,
-                    float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr);
+                    float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr,
+                    bool narrow_c = false);
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 // sddmm.hip

@@ -87,6 +87,18 @@ __device__ __forceinline__ void load_chunk_global(uint64_t addr, Chunk<FPL>& c) 
 #undef ACC_GLOBAL
 }
 
+// fp32 -> the 16-bit type of the plan (IEEE half or bfloat16), round to nearest even, as bits
+template <bool BF16>
+__device__ __forceinline__ uint32_t narrow16(float x) {
+    if constexpr (BF16) {
+        const uint32_t u = __builtin_bit_cast(uint32_t, x);
+        if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // nan stays nan
+        return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    } else {
+        return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)x);
+    }
+}
+
 struct TileMeta {       // index words of one tile
     intx4 cols;         // this lane group's four SparseAToB entries
     uint64_t bm[4];     // TCLocalBit (wave-uniform)
@@ -123,7 +135,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
     const WorkItem* __restrict__ g_items, const uint16_t* __restrict__ g_B, const uint16_t* __restrict__ g_Bhot,
     float* __restrict__ g_C, float* __restrict__ g_ws, int32_t n_items, int32_t n_blocks, int32_t N_arg,
-    int32_t streaming_stores) {
+    int32_t store_mode) {
     constexpr int R = DEPTH + 1;
     constexpr int SW = 16 * FPL;  // features per slab
     struct {
@@ -153,7 +165,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     bool act[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) act[s] = !TAIL || (f0 + s * SW < N);
-    const bool nt = streaming_stores != 0;
+    const bool nt = (store_mode & kStoreStreaming) != 0;
+    const bool c16 = (store_mode & kStoreNarrow) != 0;  // C holds 16-bit values of the plan's type
 
     // lane constants of the bitmap decode: bit index of (row c, k 4g) is c*16 + 4g
     const int wq = c >> 2;
@@ -197,6 +210,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 if (row < 0 || !act[s]) continue;
+                if (c16 && !partial) {  // rounded to nearest even; a lane's FPL values are contiguous
+                    uint16_t* dst16 = reinterpret_cast<uint16_t*>(p.C) + (size_t)row * (size_t)N + f0 + s * SW;
+                    uint32_t pk[(FPL + 1) / 2];
+#pragma unroll
+                    for (int m = 0; m < FPL; m += 2) {
+                        pk[m >> 1] = narrow16<BF16>(acc[s][m][r]);
+                        if constexpr (FPL > 1) pk[m >> 1] |= narrow16<BF16>(acc[s][m + 1][r]) << 16;
+                    }
+                    if constexpr (FPL == 8) *reinterpret_cast<uintx4*>(dst16) = uintx4{pk[0], pk[1], pk[2], pk[3]};
+                    else if constexpr (FPL == 4) *reinterpret_cast<uintx2*>(dst16) = uintx2{pk[0], pk[1]};
+                    else if constexpr (FPL == 2) *reinterpret_cast<uint32_t*>(dst16) = pk[0];
+                    else *dst16 = (uint16_t)pk[0];
+                    continue;
+                }
                 float* dst = out_base + (size_t)row * (size_t)N + f0 + s * SW;
                 if constexpr (FPL >= 4) {
 #pragma unroll
@@ -446,7 +473,7 @@ void launch_one(const ExecParams& p, hipStream_t stream) {
     dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
     hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
                        p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items, p.n_blocks, p.N,
-                       p.streaming_stores);
+                       p.store_mode);
 }
 
 template <int FPL, int NS, int DEPTH, int ADDR, bool TAIL, bool BF16>

@@ -9,7 +9,8 @@ operations a message-passing layer is made of, both differentiable:
 Their gradients are the same two operations again: dB = A^T.dC, d(vals) = sddmm(dC, B),
 dX = (A with values d(out)).Y, dY = (A^T with values d(out)).X.  Mixed precision as in the
 forward pass: 16-bit operands (gradients are rounded to the operand type before they enter a
-kernel), fp32 results.
+kernel), fp32 accumulation; results are fp32, except the gradients of 16-bit operands, which
+the kernel rounds to that type as it stores them (acc_spmm_execute_c16).
 
 torch supplies tensors, the current stream, the autograd tape and the index bookkeeping of the
 transpose (a stable sort of the column ids); every product runs in the library's kernels.  There
@@ -20,7 +21,7 @@ from __future__ import annotations
 import numpy as np
 import torch
 
-from . import (ACC_SPMM_BF16, ACC_SPMM_FP16, acc_spmm_destroy, acc_spmm_execute, acc_spmm_plan_device,
+from . import (ACC_SPMM_BF16, ACC_SPMM_FP16, acc_spmm_destroy, acc_spmm_execute, acc_spmm_execute_c16, acc_spmm_plan_device,
                acc_spmm_plan_stats, acc_spmm_sddmm, acc_spmm_update_values, make_options)
 
 _VALUE_TYPES = {torch.float16: ACC_SPMM_FP16, torch.bfloat16: ACC_SPMM_BF16}
@@ -111,15 +112,15 @@ class Graph:
         return vals.contiguous()
 
     # ------------------------------------------------------------------ raw products (no tape)
-    def _spmm(self, vals, B, transposed=False):
+    def _spmm(self, vals, B, transposed=False, narrow=False):
         if transposed:
             self._load_t(vals)
             plan, rows = self._plan_t, self.K
         else:
             self._load(vals)
             plan, rows = self._plan, self.M
-        C = torch.empty((rows, B.shape[1]), dtype=torch.float32, device=self.device)
-        acc_spmm_execute(plan, B, B.shape[1], C, _stream())
+        C = torch.empty((rows, B.shape[1]), dtype=self.dtype if narrow else torch.float32, device=self.device)
+        (acc_spmm_execute_c16 if narrow else acc_spmm_execute)(plan, B, B.shape[1], C, _stream())
         return C
 
     def _sddmm(self, X, Y):
@@ -128,11 +129,12 @@ class Graph:
         return out
 
     # ------------------------------------------------------------------ the two operations
-    def aggregate(self, B, vals=None):
-        """C = A.B as an fp32 M x N tensor; B is K x N in the Graph's dtype.  `vals` (nnz values in
-        CSR order, e.g. attention weights) replaces the values of A for this call and may require
-        a gradient; N must then be a width acc_spmm_sddmm accepts."""
-        return _Aggregate.apply(self, self._values(vals), self._check_operand("B", B, self.K))
+    def aggregate(self, B, vals=None, narrow=False):
+        """C = A.B as an fp32 M x N tensor (narrow=True: in the Graph's 16-bit dtype, rounded once from
+        the fp32 accumulators, which halves the bytes written); B is K x N in the Graph's dtype.
+        `vals` (nnz values in CSR order, e.g. attention weights) replaces the values of A for this
+        call and may require a gradient; N must then be a width acc_spmm_sddmm accepts."""
+        return _Aggregate.apply(self, self._values(vals), self._check_operand("B", B, self.K), bool(narrow))
 
     def edge_scores(self, X, Y):
         """out[p] = <X[i_p], Y[j_p]> for every stored entry p = (i_p, j_p), fp32, CSR order.
@@ -161,10 +163,10 @@ class Graph:
 
 class _Aggregate(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, graph, vals, B):
+    def forward(ctx, graph, vals, B, narrow):
         ctx.graph = graph
         ctx.save_for_backward(vals, B)
-        return graph._spmm(vals, B)
+        return graph._spmm(vals, B, narrow=narrow)
 
     @staticmethod
     def backward(ctx, dC):
@@ -173,10 +175,10 @@ class _Aggregate(torch.autograd.Function):
         d16 = dC.to(graph.dtype).contiguous()
         d_vals = d_B = None
         if ctx.needs_input_grad[2]:
-            d_B = graph._spmm(vals, d16, transposed=True).to(graph.dtype)
+            d_B = graph._spmm(vals, d16, transposed=True, narrow=True)   # a gradient in B's own type
         if ctx.needs_input_grad[1]:
             d_vals = graph._sddmm(d16, B).to(graph.dtype)
-        return None, d_vals, d_B
+        return None, d_vals, d_B, None
 
 
 class _EdgeScores(torch.autograd.Function):
@@ -193,9 +195,9 @@ class _EdgeScores(torch.autograd.Function):
         g16 = d_out.to(graph.dtype).contiguous()
         d_X = d_Y = None
         if ctx.needs_input_grad[1]:
-            d_X = graph._spmm(g16, Y).to(graph.dtype)
+            d_X = graph._spmm(g16, Y, narrow=True)
         if ctx.needs_input_grad[2]:
-            d_Y = graph._spmm(g16, X, transposed=True).to(graph.dtype)
+            d_Y = graph._spmm(g16, X, transposed=True, narrow=True)
         return None, d_X, d_Y
 
 
@@ -210,5 +212,5 @@ class GraphConv(torch.nn.Module):
         self.bias = torch.nn.Parameter(torch.zeros(out_features, device=graph.device)) if bias else None
 
     def forward(self, H, vals=None):
-        out = self.graph.aggregate(self.linear(H), vals)
+        out = self.graph.aggregate(self.linear(H), vals)   # fp32: the bias is added in fp32
         return out if self.bias is None else out + self.bias

@@ -179,6 +179,20 @@ def test_attention_layer_gradients_against_a_dense_fp64_computation(dtype):
         assert err <= tol * float(ref.abs().max()), (name, err, float(ref.abs().max()))
 
 
+def test_narrow_aggregate_is_the_rounded_fp32_one():
+    w = wl.config(2, 6)
+    g = gnn().Graph(w.M, w.K, w.rowptr, w.colidx, half_tensor(w.vals))
+    try:
+        B = half_tensor(wl.dense(w.K, 64, 61, "normal", 0.0, 1.0), grad=True)
+        C32 = g.aggregate(B)
+        C16 = g.aggregate(B, narrow=True)
+        assert C16.dtype == torch.float16 and torch.equal(C16, C32.half())
+        C16.float().sum().backward()                           # the tape runs through the narrow output too
+        assert B.grad is not None and B.grad.dtype == torch.float16 and bool(torch.isfinite(B.grad).all())
+    finally:
+        g.close()
+
+
 def test_graph_conv_module_trains_one_step():
     w = wl.config(3, 6)
     g = gnn().Graph(w.M, w.K, w.rowptr, w.colidx, half_tensor(w.vals))

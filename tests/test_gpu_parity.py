@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2501_09251_amd as acc
 import workloads as wl
-from _util import csr_from_rows, random_csr, f16, bf16
+from _util import csr_from_rows, random_csr, f16, bf16, bf16_to_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -280,6 +280,78 @@ def test_column_order_auto_detects_hubs_at_power_of_two_labels():
     on, skew = applied(M, K, rowptr, np.ascontiguousarray(colidx.reshape(-1).astype(np.int32)),
                        f16(np.ones(M * 8)))
     assert on == 0 and skew < 2.5
+
+
+# ------------------------------------------------------------------ C in 16 bits
+def run_spmm_c16(plan, B_u16, M, N):
+    dev = torch.device("cuda:0")
+    Bd = torch.from_numpy(B_u16.view(np.int16)).to(dev)
+    rows, guard = max(M, 1), 4096
+    buf = torch.full((rows * N + guard,), 0x7fc1, dtype=torch.int16, device=dev)    # a NaN pattern in both types
+    buf[rows * N:] = 12345
+    C = buf[:rows * N].view(rows, N)
+    acc.acc_spmm_execute_c16(plan, Bd, N, C, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert bool((buf[rows * N:] == 12345).all()), "wrote past the end of C"
+    return C[:M].cpu().numpy().view(np.uint16)
+
+
+def check_c16(rowptr, colidx, vals, B, C_bits, value_type):
+    """fp32 accumulation within the usual bound, then one rounding to the 16-bit type: half an
+    ulp of the result (2^-11 relative for binary16, 2^-8 for bfloat16), doubled for slack; results
+    below the type's normal range are compared with the absolute term only."""
+    ref, bound = oracle.spmm(rowptr, colidx, vals, B, value_type=value_type)
+    got = C_bits.view(np.float16).astype(np.float64) if value_type == "f16" else bf16_to_f64(C_bits)
+    ulp = 2.0 ** -10 if value_type == "f16" else 2.0 ** -7
+    tiny = 2.0 ** -24 if value_type == "f16" else 0.0
+    lim = 2e-3 * bound + 1e-5 + ulp * np.abs(ref) + tiny
+    assert np.isfinite(got).all(), "an element of C was not written"
+    err = np.abs(got - ref)
+    assert (err <= lim).all(), f"worst error/limit = {(err / lim).max()}"
+
+
+@pytest.mark.parametrize("N", [7, 16, 40, 64, 96, 128, 256])
+@pytest.mark.parametrize("value_type,lb", [("f16", acc.ACC_SPMM_OFF), ("f16", acc.ACC_SPMM_ON), ("bf16", acc.ACC_SPMM_ON)])
+def test_sixteen_bit_output(N, value_type, lb):
+    """acc_spmm_execute_c16: same plan, same kernels, C rounded once to the plan's 16-bit type;
+    split windows (partial sums stay fp32), empty rows (zeros) and a ragged last window included."""
+    rng = np.random.default_rng(1000 + N)
+    M, K = 333, 500
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.06, empty_row_frac=0.15)
+    if value_type == "bf16":
+        vals = bf16(rng.uniform(-1, 1, len(colidx)))
+        B = bf16(rng.normal(0, 1, (K, N)))
+    else:
+        B = f16(rng.normal(0, 1, (K, N)))
+    opt = acc.make_options(reorder=acc.ACC_SPMM_ON, load_balance=lb, max_tiles_per_item=4,
+                           value_type=acc.ACC_SPMM_BF16 if value_type == "bf16" else acc.ACC_SPMM_FP16)
+    plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals, opt)
+    try:
+        if lb == acc.ACC_SPMM_ON:
+            assert acc.acc_spmm_plan_stats(plan)["num_split_windows"] > 0
+        C16 = run_spmm_c16(plan, B, M, N)
+        check_c16(rowptr, colidx, vals, B, C16, value_type)
+        empty = np.flatnonzero(np.diff(rowptr) == 0)
+        assert len(empty) and not C16[empty].any()
+        # the same call in fp32, rounded here, gives the same bits
+        C32 = run_spmm(plan, B, M, N)
+        expect = f16(C32) if value_type == "f16" else bf16(C32)
+        np.testing.assert_array_equal(C16, expect)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_sixteen_bit_output_on_a_workload_with_column_order():
+    w = wl.config(2, 5)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(reorder=acc.ACC_SPMM_ON, load_balance=acc.ACC_SPMM_ON,
+                                                 column_order=acc.ACC_SPMM_ON, max_tiles_per_item=16))
+    try:
+        C16 = run_spmm_c16(plan, w.B, w.M, w.N)
+        check_c16(w.rowptr, w.colidx, w.vals, w.B, C16, "f16")
+        np.testing.assert_array_equal(C16, f16(run_spmm(plan, w.B, w.M, w.N)))
+    finally:
+        acc.acc_spmm_destroy(plan)
 
 
 # ------------------------------------------------------------------ sampled dense-dense product

@@ -11,6 +11,8 @@ preprocessing over iterative use, Section 4.3.2).  Prints ONE JSON line:
               with HIP events on the launch stream, against 8 TB/s
   cpu_baseline  the fp64 CSR oracle timed on the host cores on a bounded row sample
   naive_gpu   the one-wavefront-per-row CSR kernel on the same inputs
+  execute_c16 the same plan and kernels with C rounded to 16 bits in the store (beside the
+              metric, never part of it: the metric's C is fp32)
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--shrink S]
 """

@@ -52,6 +52,8 @@ def _load():
         L.orc_dendrogram.argtypes = [i64, vp, vp, vp, vp]
         L.orc_ordering.restype = None
         L.orc_ordering.argtypes = [i64, vp, vp, vp, vp, i32, vp, vp, vp, vp]
+        L.orc_set_progress.restype = None
+        L.orc_set_progress.argtypes = [i64]
         L.orc_ibd.restype = ctypes.c_double
         L.orc_ibd.argtypes = [i64, vp]
         _lib = L
@@ -136,6 +138,11 @@ def decode(fmt):
                        _p(fmt["sparse_a_to_b"]), _p(fmt["tc_local_bit"]), _p(fmt["vals"]),
                        _p(rowptr), _p(colidx), _p(vals))
     return rowptr, colidx, vals
+
+
+def set_progress(every):
+    """Step I prints a line on stderr every `every` vertices (0: silent).  For runs that take minutes."""
+    _load().orc_set_progress(int(every))
 
 
 def dendrogram(rowptr, colidx):

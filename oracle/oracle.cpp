@@ -26,6 +26,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdio>
 #include <cstring>
 #include <map>
 #include <utility>
@@ -67,7 +68,14 @@ inline double widen(uint16_t h, int value_type) { return value_type == 1 ? bf2d(
 
 }  // namespace
 
+// Long runs (the full-size reordering takes minutes) can report how far they are: a line on
+// stderr every g_progress_every steps of Step I.  0 (default) prints nothing.  No effect on
+// any result.
+static int64_t g_progress_every = 0;
+
 extern "C" {
+
+void orc_set_progress(int64_t every) { g_progress_every = every > 0 ? every : 0; }
 
 double orc_f16_to_f64(uint16_t h) { return h2d(h); }
 double orc_bf16_to_f64(uint16_t h) { return bf2d(h); }
@@ -286,6 +294,10 @@ void orc_dendrogram(int64_t M, const int32_t* rowptr, const int32_t* colidx, int
     auto root = [&](int32_t x) { while (up[x] != x) { up[x] = up[up[x]]; x = up[x]; } return x; };
     for (int64_t t = 0; t < M; ++t) {
         int32_t v = order[t];
+        if (g_progress_every && t % g_progress_every == 0) {
+            std::fprintf(stderr, "[oracle] dendrogram: vertex %lld of %lld\n", (long long)t, (long long)M);
+            std::fflush(stderr);
+        }
         std::map<int32_t, int64_t> w;
         for (int32_t y : adj[v]) { int32_t ry = root(y); if (ry != v) w[ry] += 1; }
         for (int32_t c : children[v])

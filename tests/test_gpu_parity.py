@@ -4,6 +4,8 @@ Tolerance for C (fp16 inputs, exact fp16 x fp16 products, fp32 accumulation in a
 |C - C_ref| <= 2e-3 * (|A|.|B|) + 1e-5 elementwise.  Format arrays and the permutation are
 compared bit for bit.
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -635,6 +637,60 @@ def test_wide_matrix_uses_64bit_row_offsets():
             acc.acc_spmm_destroy(plan)
 
 
+# (K, N): B of 4 GiB or more, or K >= 2^24, makes execute address rows of B with 64-bit offsets.
+# The widths cover every lane width of that addressing mode: 2, 4 and 8 features per lane, one and
+# two feature slabs per wavefront, whole slabs and masked tails.
+@pytest.mark.parametrize("K,N", [((1 << 24) + 64, 30), ((1 << 24) + 64, 36), ((1 << 24) + 64, 100),
+                                 ((1 << 24) + 64, 128), (1 << 23, 256), (1 << 23, 512)])
+def test_wide_addressing_at_every_lane_width(K, N):
+    """The 64-bit row-offset variants of the tile kernel at the widths real calls use (16-byte
+    lanes, two slabs per wave), with both ways of fetching the packed values, all pipeline depths,
+    split windows, and columns at both ends of K; every element of C against the oracle."""
+    rng = np.random.default_rng(N)
+    M = 301
+    rows = []
+    for i in range(M):
+        n = 330 if i == 37 else 24                       # one heavy row: its window is split
+        cols = set(rng.integers(0, K, n).tolist()) | {K - 1 - i, i, (K // 2) + i}
+        rows.append(sorted(cols))
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    print(f"[wide] generating B {K} x {N}", flush=True)
+    B = wl.dense(K, N, 5, "uniform", -1.0, 1.0)
+    assert K >= (1 << 24) or B.nbytes >= (1 << 32)
+    dev = torch.device("cuda:0")
+    Bd = torch.from_numpy(B.view(np.int16)).to(dev)
+    C_ref, bound = oracle.spmm(rowptr, colidx, vals, B)
+    first = None
+    for fetch in (1, 2):
+        for depth in (0, 1, 2, 3):
+            plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                        acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=4,
+                                                         value_fetch=fetch, pipeline_depth=depth,
+                                                         no_prefetch=int(depth == 0),
+                                                         column_order=acc.ACC_SPMM_OFF))   # B read in place
+            try:
+                assert acc.acc_spmm_plan_stats(plan)["num_split_windows"] >= 1
+                if first is None:
+                    check_format(plan, rowptr, colidx, vals)
+                buf = torch.full((M * N + 4096,), float("nan"), dtype=torch.float32, device=dev)
+                buf[M * N:] = 12345.0
+                C = buf[:M * N].view(M, N)
+                acc.acc_spmm_execute(plan, Bd, N, C, torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                assert bool((buf[M * N:] == 12345.0).all()), "wrote past the end of C"
+                got = C.cpu().numpy()
+            finally:
+                acc.acc_spmm_destroy(plan)
+            ok, ratio = oracle.within_bound(got, C_ref, bound)
+            assert ok, f"fetch {fetch} depth {depth}: outside tolerance, worst error/limit = {ratio}"
+            if first is None:
+                first = got
+            else:
+                np.testing.assert_array_equal(got, first)     # same summation order in every variant
+    del Bd
+
+
 def test_paper_geometry_8x8_format_and_closed_form_size():
     w = wl.config(2, 7)
     plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
@@ -864,8 +920,29 @@ def test_randomised_shapes_and_options(block):
 
 
 # -------------------------------------------------- full size, as the benchmark launches it
+ORACLE_BLOCK_ROWS = 1 << 16
+
+
+def _compare_whole_output(w, C):
+    """Every row of C against the oracle, in blocks of 64 K rows (two fp64 arrays of the whole C
+    would not fit for the largest workload).  Returns the worst error/limit."""
+    worst = 0.0
+    for b in range(0, w.M, ORACLE_BLOCK_ROWS):
+        rows = np.arange(b, min(b + ORACLE_BLOCK_ROWS, w.M), dtype=np.int64)
+        C_ref, bound = oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=rows)
+        ok, ratio = oracle.within_bound(C[b:b + len(rows)], C_ref, bound)
+        assert ok, f"rows {b}..{b + len(rows)}: outside tolerance, worst error/limit = {ratio}"
+        worst = max(worst, ratio)
+        if (b // ORACLE_BLOCK_ROWS) % 16 == 0:
+            print(f"[full-size] rows {b}.. ok, worst error/limit so far {worst:.3g}", flush=True)
+    return worst
+
+
 @pytest.mark.parametrize("cfg", [2, 3, 4, 5])
-def test_full_size_sampled_rows(cfg):
+def test_full_size_whole_output(cfg):
+    """The benchmark's own launch (default options) at the benchmark's sizes: every element of C
+    against the oracle, the plan's structural invariants, and, where the plan reorders and the
+    oracle's reordering finishes in seconds (workloads 2 and 4), the permutation bit for bit."""
     print(f"[full-size] generating workload {cfg}", flush=True)
     w = wl.config(cfg)
     print(f"[full-size] planning {w.name}: M={w.M} nnz={w.nnz}", flush=True)
@@ -880,19 +957,47 @@ def test_full_size_sampled_rows(cfg):
         assert rwo[-1] == st["num_tiles"] and tco[-1] == w.nnz and np.all(np.diff(tco) >= 1)
         items = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_WORK_ITEMS).reshape(-1, 4)
         assert (items[:, 3] - items[:, 2]).sum() == st["num_tiles"]
+        if cfg in (2, 4):
+            assert st["reorder_applied"] == 1
+            print("[full-size] oracle reordering", flush=True)
+            operm, oiperm = oracle.reorder(w.rowptr, w.colidx)
+            np.testing.assert_array_equal(perm, operm)
+            np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_IPERM), oiperm)
+            np.testing.assert_array_equal(acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_DENDROGRAM_PARENT),
+                                          oracle.dendrogram(w.rowptr, w.colidx)[0])
         print("[full-size] executing", flush=True)
         C = run_spmm(plan, w.B, w.M, w.N)
         assert np.isfinite(C).all()
-        rng = np.random.default_rng(cfg)
-        deg = np.diff(w.rowptr)
-        rows = np.unique(np.concatenate([
-            rng.integers(0, w.M, 3000), np.argsort(deg)[-40:], np.arange(64), np.arange(w.M - 64, w.M),
-            np.nonzero(deg == 0)[0][:200]]))
-        print(f"[full-size] checking {len(rows)} rows against the oracle", flush=True)
-        ratio = check_against_oracle(w.rowptr, w.colidx, w.vals, w.B, C, rows=rows)
-        print(f"[full-size] worst error/limit = {ratio:.3g}", flush=True)
+        ratio = _compare_whole_output(w, C)
+        print(f"[full-size] all {w.M} rows within tolerance, worst error/limit = {ratio:.3g}", flush=True)
     finally:
         acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.skipif(os.environ.get("ACC_SPMM_LONG_TESTS") != "1",
+                    reason="the oracle's reordering of the 2^23-vertex graph takes minutes on one host core: "
+                           "run with ACC_SPMM_LONG_TESTS=1 and -s (the oracle then reports its progress)")
+def test_full_size_permutation_of_the_largest_workload():
+    """Workload 5 (8.4 M vertices, scores around 10^17, 8192 concurrent 1024-leaf segments): the
+    plan's dendrogram and permutation against the oracle's, bit for bit."""
+    w = wl.config(5, with_B=False)
+    print(f"[full-size perm] planning {w.name}", flush=True)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(reorder=acc.ACC_SPMM_ON))
+    try:
+        perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
+        parent = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_DENDROGRAM_PARENT)
+        print(f"[full-size perm] plan: {acc.acc_spmm_plan_stats(plan)}", flush=True)
+    finally:
+        acc.acc_spmm_destroy(plan)
+    oracle.set_progress(1 << 19)
+    try:
+        oparent, child_order = oracle.dendrogram(w.rowptr, w.colidx)
+        print("[full-size perm] oracle dendrogram done", flush=True)
+        np.testing.assert_array_equal(parent, oparent)
+        operm, _ = oracle.ordering(w.rowptr, w.colidx, oparent, child_order)
+        np.testing.assert_array_equal(perm, operm)
+    finally:
+        oracle.set_progress(0)
 
 
 @pytest.mark.parametrize("cfg", [2, 5])

@@ -59,7 +59,8 @@ typedef struct {
      * the dendrogram construction, and keeps the identity, once it has visited 8 edge
      * records per graph entry (large uniform meshes, where nothing is gained).
      * Requires M == K; for M != K the dendrogram step is skipped and the order is the
-     * identity. */
+     * identity.  Matrices with nnz >= 2^30 are not reordered: ON returns
+     * ACC_SPMM_ERR_UNSUPPORTED for them (before the arrays are read), AUTO keeps the input order. */
     int32_t reorder;
     /* Load balancing (Section 3.5).  OFF: one work item per row window.  ON: always split
      * heavy windows / pack light ones.  AUTO: apply iff IBD (Eq. 3) > ibd_threshold. */
@@ -284,6 +285,8 @@ ACC_SPMM_API int acc_spmm_permute_rows(const acc_spmm_plan_t* plan, const void* 
  */
 ACC_SPMM_API int acc_spmm_execute_csr_naive(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 
+/* Releases a plan and its device memory (utility call, no passage of the paper).  NULL is
+ * allowed.  The caller must have waited for every execute that uses the plan. */
 ACC_SPMM_API void acc_spmm_destroy(acc_spmm_plan_t* plan);
 
 /*
@@ -300,7 +303,7 @@ ACC_SPMM_API int acc_spmm_plan_save(const acc_spmm_plan_t* plan, const char* pat
 ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_load(const char* path);
 
 /* Message of the calling thread's last failure; returns its status code (0 if none).
- * buf may be NULL. */
+ * buf may be NULL.  (Utility call, no passage of the paper.) */
 ACC_SPMM_API int acc_spmm_last_error(char* buf, size_t len);
 
 ACC_SPMM_API int acc_spmm_plan_stats(const acc_spmm_plan_t* plan, acc_spmm_stats* out);
@@ -314,8 +317,11 @@ ACC_SPMM_API int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, i
                           int64_t* c_bytes, int64_t* mfma_flops);
 
 /*
- * Copy one of the plan's arrays to HOST memory.  Pass host_dst == NULL to get the size in
- * bytes through *bytes; otherwise *bytes must be at least that size.
+ * Copy one of the plan's arrays to HOST memory: the four index arrays and the packed values of
+ * the tile format (Section 3.3), the row permutation and the dendrogram (Section 3.2, Algorithm
+ * 1), the work items (Section 3.5) and the column order: what the parity tests compare.
+ * Pass host_dst == NULL to get the size in bytes through *bytes; otherwise *bytes must be at
+ * least that size.
  * Work items are 4 x int32 {w_begin, w_end, t_begin, t_end}:
  *   w_end >  w_begin : the item owns windows [w_begin, w_end) completely
  *                      (t_begin, t_end are their first and one-past-last tile);
@@ -353,6 +359,28 @@ ACC_SPMM_API void acc_spmm_mtx_close(acc_spmm_mtx_t* mtx);
  * SpMM kernels.
  */
 ACC_SPMM_API int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/*
+ * Measurement aid: the memory pattern of the tile kernel's gather of B rows and nothing else
+ * (Section 3.4 names this gather as where the time goes).  For every 16 entries of `index` (one
+ * "tile") a wavefront reads those 16 rows of `table`, 16 bytes per lane and 256 contiguous bytes
+ * per 16 lanes, four tiles in flight; the data is folded into `sink`.  With write_rows > 0 every
+ * wavefront also streams write_rows rows of 2 * row_bytes (the fp32 image of a row) to `out` after
+ * every write_every tiles, as the tile kernel writes the rows of a window of C after its tiles.
+ *   table        DEVICE, rows x row_bytes, row_bytes a multiple of 16
+ *   index        DEVICE int32[n_index], every entry in [0, rows) (not checked: it lives on the
+ *                device), n_index a multiple of 16
+ *   sink         DEVICE, at least 16 MiB, overwritten
+ *   out          DEVICE, needed when write_rows > 0: at least W * ceil(ceil(T / W) / write_every)
+ *                * write_rows * 2 * row_bytes bytes for T = n_index / 16 tiles and
+ *                W = 4 * min(ceil(T / 4), 4096) wavefronts (the call checks out_bytes against
+ *                this and says how many are needed); write_every a multiple of 4
+ * All pointers 16-byte aligned.  Timed by the caller (events on `stream`): the rate of this call
+ * is the ceiling the tile kernel's gather can reach on the machine at hand.
+ */
+ACC_SPMM_API int acc_spmm_calibration_gather(const void* table, int64_t rows, int64_t row_bytes, const int32_t* index,
+                                             int64_t n_index, void* sink, size_t sink_bytes, void* out, size_t out_bytes,
+                                             int32_t write_every, int32_t write_rows, void* stream);
 
 /*
  * The two host-side stages of acc_spmm_plan, callable on their own (no GPU needed).

@@ -35,7 +35,7 @@ _ARRAY_DTYPES = {
 EXPORTED_SYMBOLS = [
     "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_plan_device", "acc_spmm_execute", "acc_spmm_execute_c16", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
-    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values", "acc_spmm_plan_save", "acc_spmm_plan_load",
+    "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_calibration_gather", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values", "acc_spmm_plan_save", "acc_spmm_plan_load",
     "acc_spmm_mtx_open", "acc_spmm_mtx_shape", "acc_spmm_mtx_csr", "acc_spmm_mtx_close",
 ]
 
@@ -137,6 +137,8 @@ def load():
     L.acc_spmm_plan_export.argtypes = [vp, ctypes.c_int, vp, ctypes.POINTER(ctypes.c_size_t)]
     L.acc_spmm_calibration_copy.restype = ctypes.c_int
     L.acc_spmm_calibration_copy.argtypes = [vp, vp, ctypes.c_size_t, vp]
+    L.acc_spmm_calibration_gather.restype = ctypes.c_int
+    L.acc_spmm_calibration_gather.argtypes = [vp, i64, i64, vp, i64, vp, ctypes.c_size_t, vp, ctypes.c_size_t, i32, i32, vp]
     L.acc_spmm_dendrogram_host.restype = i64
     L.acc_spmm_dendrogram_host.argtypes = [i64, vp, vp, i32, vp, vp, vp, ctypes.POINTER(ctypes.c_double)]
     L.acc_spmm_schedule_host.restype = i64
@@ -278,6 +280,13 @@ def acc_spmm_permute_rows(plan, src, dst, row_bytes, to_caller=0, stream=None):
 
 def acc_spmm_calibration_copy(dst, src, nbytes, stream=None):
     if load().acc_spmm_calibration_copy(_dev_ptr(dst), _dev_ptr(src), nbytes, stream) != 0:
+        _raise()
+
+
+def acc_spmm_calibration_gather(table, rows, row_bytes, index, n_index, sink, sink_bytes, out=None, out_bytes=0,
+                                write_every=0, write_rows=0, stream=None):
+    if load().acc_spmm_calibration_gather(_dev_ptr(table), rows, row_bytes, _dev_ptr(index), n_index, _dev_ptr(sink),
+                                          sink_bytes, _dev_ptr(out), out_bytes, write_every, write_rows, stream) != 0:
         _raise()
 
 

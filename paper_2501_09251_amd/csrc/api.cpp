@@ -120,6 +120,11 @@ bool validate_csr(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, cons
     return unsorted;
 }
 
+// The graph build of the reordering numbers the 2*nnz directed edge keys, and their run heads,
+// with 32-bit positions: beyond this many entries the reordering is not available (ON is
+// refused, AUTO keeps the input order).
+constexpr int64_t kReorderMaxNnz = ((int64_t)1 << 30) - 1;
+
 struct RowOrderInfo {
     bool applied = false;
     int64_t tiles_identity = -1;   // tile count in the input order, if it was counted
@@ -135,7 +140,7 @@ void choose_row_order(Plan& P, int64_t M, int64_t K, int64_t nnz, const int32_t*
     std::vector<int32_t> identity(M);
     for (int64_t i = 0; i < M; ++i) identity[i] = (int32_t)i;
     d_perm.upload(identity.data(), M);
-    if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0) {
+    if (opt.reorder != ACC_SPMM_OFF && M == K && M > 0 && nnz > 0 && nnz <= kReorderMaxNnz) {
         const double r0 = now_s();
         // AUTO gives up on inputs whose dendrogram is expensive to build (large uniform
         // meshes), where the identity order is kept anyway; ON always completes.
@@ -241,6 +246,10 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.value_fetch < 0 || opt.value_fetch > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "value_fetch must be 0, 1 or 2");
     if (opt.value_type != ACC_SPMM_FP16 && opt.value_type != ACC_SPMM_BF16)
         fail(ACC_SPMM_ERR_INVALID_ARG, "value_type must be ACC_SPMM_FP16 or ACC_SPMM_BF16");
+
+    if (opt.reorder == ACC_SPMM_ON && M == K && nnz > kReorderMaxNnz)
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "reorder = ON needs nnz < 2^30 (the pattern graph is indexed with 32 bits); "
+                                       "use reorder = AUTO or OFF, which keep the input order for such a matrix");
 
     std::vector<int32_t> fixed_col;
     std::vector<uint16_t> fixed_val;
@@ -527,6 +536,15 @@ int acc_spmm_plan_traffic(const acc_spmm_plan_t* plan, int32_t N, int64_t* a_byt
 
 int acc_spmm_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
     return guarded([&] { launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)); });
+}
+
+int acc_spmm_calibration_gather(const void* table, int64_t rows, int64_t row_bytes, const int32_t* index, int64_t n_index,
+                                void* sink, size_t sink_bytes, void* out, size_t out_bytes, int32_t write_every,
+                                int32_t write_rows, void* stream) {
+    return guarded([&] {
+        launch_calibration_gather(table, rows, row_bytes, index, n_index, sink, sink_bytes, out, out_bytes, write_every,
+                                  write_rows, static_cast<hipStream_t>(stream));
+    });
 }
 
 int64_t acc_spmm_dendrogram_host(int64_t M, const int64_t* graph_rowptr, const int32_t* graph_adj,

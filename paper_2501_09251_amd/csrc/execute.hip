@@ -96,7 +96,77 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
         dst[i] = src[i];
 }
 
+// Measurement aid: nothing but the memory pattern of the tile kernel's B gather.  A wavefront walks
+// its share of `index` sixteen entries (one "tile") at a time; each 16-lane group reads four of the
+// sixteen rows, 16 bytes per lane, so that sixteen lanes cover 256 contiguous bytes of a row (wider
+// rows in further steps of 256 bytes).  Four tiles are requested before the first is consumed.  With
+// write_rows > 0 the wave also writes write_rows rows of row_u4 * 32 bytes (the fp32 image of a
+// row) after every write_every tiles, as the tile kernel writes a window of C after its tiles.
+__global__ __launch_bounds__(256) void calibration_gather_kernel(const uintx4* __restrict__ table, int64_t row_u4,
+                                                                 const int32_t* __restrict__ index, int64_t n_tiles,
+                                                                 uintx4* __restrict__ sink, uintx4* __restrict__ out,
+                                                                 int32_t write_every, int32_t write_rows) {
+    const int lane = threadIdx.x & 63, g = lane >> 4, c = lane & 15;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6), n_waves = (int64_t)gridDim.x * 4;
+    const int64_t per_wave = (n_tiles + n_waves - 1) / n_waves;
+    const int64_t t_begin = wave * per_wave, t_end = t_begin + per_wave < n_tiles ? t_begin + per_wave : n_tiles;
+    typedef int32_t intx4 __attribute__((ext_vector_type(4)));
+    uintx4 acc{0u, 0u, 0u, 0u};
+    int64_t written = 0;
+    for (int64_t t = t_begin; t < t_end; t += 4) {
+        intx4 ids[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int64_t tt = t + k < t_end ? t + k : t_end - 1;
+            ids[k] = *reinterpret_cast<const intx4*>(index + tt * 16 + 4 * g);
+        }
+        for (int64_t u = c; u < row_u4; u += 16) {
+            uintx4 v[16];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[4 * k + q] = table[(int64_t)ids[k][q] * row_u4 + u];
+#pragma unroll
+            for (int k = 0; k < 16; ++k) acc ^= v[k];
+        }
+        if (write_rows > 0 && (t - t_begin) % write_every == 0) {   // write_every is a multiple of 4
+            // rows of the output stream owned by this wave, consecutive, each row_u4 * 2 units of 16 bytes
+            const int64_t units = (int64_t)write_rows * row_u4 * 2;
+            uintx4* dst = out + (wave * ((per_wave + write_every - 1) / write_every) * (int64_t)write_rows * row_u4 * 2) + written;
+            for (int64_t e = lane; e < units; e += 64) dst[e] = acc;
+            written += units;
+        }
+    }
+    sink[(int64_t)blockIdx.x * 256 + threadIdx.x] = acc;   // keeps the loads alive; 16 bytes per lane
+}
+
 }  // namespace
+
+void launch_calibration_gather(const void* table, int64_t rows, int64_t row_bytes, const int32_t* index, int64_t n_index,
+                               void* sink, size_t sink_bytes, void* out, size_t out_bytes, int32_t write_every,
+                               int32_t write_rows, hipStream_t stream) {
+    if (!table || !index || !sink || rows <= 0 || row_bytes <= 0 || (row_bytes & 15) || n_index <= 0 || (n_index & 15) ||
+        ((reinterpret_cast<uintptr_t>(table) | reinterpret_cast<uintptr_t>(index) | reinterpret_cast<uintptr_t>(sink) |
+          reinterpret_cast<uintptr_t>(out)) & 15))
+        fail(ACC_SPMM_ERR_INVALID_ARG, "calibration gather needs 16-byte aligned pointers, rows of a multiple of 16 bytes "
+                                       "and a multiple of 16 index entries");
+    const int64_t n_tiles = n_index / 16;
+    const unsigned blocks = (unsigned)std::min<int64_t>((n_tiles + 3) / 4, 256 * 16);
+    if (sink_bytes < (size_t)blocks * 256 * 16) fail(ACC_SPMM_ERR_INVALID_ARG, "calibration gather: sink smaller than 16 MiB");
+    if (write_rows > 0) {
+        if (!out || write_every <= 0 || (write_every & 3))
+            fail(ACC_SPMM_ERR_INVALID_ARG, "calibration gather: with write_rows, out must be given and write_every a positive multiple of 4");
+        const int64_t n_waves = (int64_t)blocks * 4, per_wave = (n_tiles + n_waves - 1) / n_waves;
+        const int64_t bursts = (per_wave + write_every - 1) / write_every;
+        const size_t need = (size_t)n_waves * (size_t)bursts * (size_t)write_rows * (size_t)row_bytes * 2;
+        if (out_bytes < need)
+            fail(ACC_SPMM_ERR_INVALID_ARG, "calibration gather: out must hold " + std::to_string(need) + " bytes");
+    }
+    hipLaunchKernelGGL(calibration_gather_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const uintx4*>(table),
+                       row_bytes / 16, index, n_tiles, static_cast<uintx4*>(sink), static_cast<uintx4*>(out), write_every,
+                       write_rows);
+    ACC_HIP(hipGetLastError());
+}
 
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream, float* tiles_ms,
                     float* combine_ms, float* gather_ms, bool narrow_c) {

@@ -171,6 +171,9 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
                     float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr,
                     bool narrow_c = false);
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+void launch_calibration_gather(const void* table, int64_t rows, int64_t row_bytes, const int32_t* index, int64_t n_index,
+                               void* sink, size_t sink_bytes, void* out, size_t out_bytes, int32_t write_every,
+                               int32_t write_rows, hipStream_t stream);
 void launch_csr_naive(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream);
 // sddmm.hip
 void launch_update_values(const Plan& plan, const void* csr_vals, hipStream_t stream);

@@ -80,6 +80,16 @@ def test_invalid_input_is_reported_not_crashed():
     assert e.value.code == -1
     code, msg = acc.acc_spmm_last_error()
     assert code == -1 and "struct_size" in msg
+    # a forced reordering of a matrix with 2^30 or more entries is refused before any array is read
+    # (its pattern graph is indexed with 32 bits), so tiny placeholder arrays are enough here
+    L = acc.load()
+    one = np.zeros(4, np.int32)
+    for nnz, expect in ((1 << 30, -3), ((1 << 31) - 1, -3)):
+        h = L.acc_spmm_plan_ex(1 << 20, 1 << 20, nnz, one.ctypes.data, one.ctypes.data, one.ctypes.data,
+                               ctypes.byref(acc.make_options(reorder=acc.ACC_SPMM_ON)))
+        assert not h
+        code, msg = acc.acc_spmm_last_error()
+        assert code == expect and "2^30" in msg
 
 
 @pytest.mark.skipif(_has_gpu(), reason="only meaningful on a machine without a GPU")

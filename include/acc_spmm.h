@@ -216,7 +216,9 @@ ACC_SPMM_API acc_spmm_plan_t* acc_spmm_plan_device(int64_t M, int64_t K, int64_t
  * Returns without waiting for the GPU.  Calls on one plan must not overlap in time on
  * different streams when the plan has split windows or gathers rows of B (they share the
  * plan's partial-sum workspace and its buffer for the gathered rows, which the first call
- * with a larger N (re)allocates).
+ * with a larger N (re)allocates).  A call that would have to (re)allocate while `stream` is
+ * being captured into a HIP graph allocates nothing and returns ACC_SPMM_ERR_INVALID_ARG:
+ * make one call at that N before the capture, or use acc_spmm_execute_static.
  */
 ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 
@@ -229,6 +231,24 @@ ACC_SPMM_API int acc_spmm_execute(const acc_spmm_plan_t* plan, const void* B, in
  * (C 16-byte aligned), errors and stream behaviour as acc_spmm_execute.
  */
 ACC_SPMM_API int acc_spmm_execute_c16(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
+
+/*
+ * acc_spmm_execute for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result (bit for bit) and
+ * kernels as acc_spmm_execute, but the call's two temporary device buffers (the partial tiles of
+ * split row windows, num_partial_slots x 16 x N fp32, and, when the plan gathers rows of B, the
+ * num_hot_columns x N gathered rows) are carved out of one array of
+ * ACC_SPMM_STATIC_SCRATCH_BYTES that the library holds in device memory of every GPU it runs on
+ * from load time until the process ends.  It calls no hipMalloc / hipFree and no allocating
+ * library routine.  A plan whose two buffers at this N (the first rounded up to 256 bytes) exceed
+ * that size is refused with ACC_SPMM_ERR_UNSUPPORTED and a message that gives both sizes;
+ * acc_spmm_execute serves it.  Nothing in the array has to be cleared between calls: every
+ * element a call reads was written earlier in the same call.  All calls on one GPU, from any plan
+ * and any stream, share the array, so calls that overlap in time on one GPU race: order them on
+ * one stream, or with events.
+ */
+#define ACC_SPMM_STATIC_SCRATCH_BYTES (64u << 20)
+ACC_SPMM_API int acc_spmm_execute_static(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream);
 
 /*
  * acc_spmm_execute with per-kernel timing, for benchmarks: records HIP events on `stream`

@@ -33,7 +33,7 @@ _ARRAY_DTYPES = {
 }
 
 EXPORTED_SYMBOLS = [
-    "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_plan_device", "acc_spmm_execute", "acc_spmm_execute_c16", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
+    "acc_spmm_plan", "acc_spmm_plan_ex", "acc_spmm_plan_device", "acc_spmm_execute", "acc_spmm_execute_c16", "acc_spmm_execute_static", "acc_spmm_execute_timed", "acc_spmm_execute_csr_naive", "acc_spmm_destroy",
     "acc_spmm_last_error", "acc_spmm_plan_stats", "acc_spmm_plan_traffic", "acc_spmm_plan_export",
     "acc_spmm_dendrogram_host", "acc_spmm_schedule_host", "acc_spmm_calibration_copy", "acc_spmm_calibration_gather", "acc_spmm_permute_rows", "acc_spmm_sddmm", "acc_spmm_update_values", "acc_spmm_plan_save", "acc_spmm_plan_load",
     "acc_spmm_mtx_open", "acc_spmm_mtx_shape", "acc_spmm_mtx_csr", "acc_spmm_mtx_close",
@@ -103,6 +103,8 @@ def load():
     L.acc_spmm_execute.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_execute_c16.restype = ctypes.c_int
     L.acc_spmm_execute_c16.argtypes = [vp, vp, i32, vp, vp]
+    L.acc_spmm_execute_static.restype = ctypes.c_int
+    L.acc_spmm_execute_static.argtypes = [vp, vp, i32, vp, vp]
     L.acc_spmm_execute_timed.restype = ctypes.c_int
     L.acc_spmm_execute_timed.argtypes = [vp, vp, i32, vp, vp] + [ctypes.POINTER(ctypes.c_float)] * 3
     L.acc_spmm_mtx_open.restype = vp
@@ -220,6 +222,15 @@ def acc_spmm_execute_c16(plan, B, N, C, stream=None):
     """Enqueue C = A.B with C in the plan's 16-bit value type (fp32 accumulation, one rounding)."""
     if load().acc_spmm_execute_c16(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
         _raise()
+
+
+def acc_spmm_execute_static(plan, B, N, C, stream=None):
+    """acc_spmm_execute that allocates nothing: its temporary buffers live in the library's static device array."""
+    if load().acc_spmm_execute_static(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
+        _raise()
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 def acc_spmm_execute_timed(plan, B, N, C, stream=None):

@@ -267,6 +267,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     Plan& P = handle->plan;
     try {
         ACC_HIP(hipGetDevice(&P.device));
+        prepare_static_scratch();
         P.opt = opt;
         const int32_t WH = opt.window_height, TW = opt.tile_width;
 
@@ -440,6 +441,13 @@ int acc_spmm_execute_c16(const acc_spmm_plan_t* plan, const void* B, int32_t N, 
     return guarded([&] {
         if (!plan || !C || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
         launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, true);
+    });
+}
+
+int acc_spmm_execute_static(const acc_spmm_plan_t* plan, const void* B, int32_t N, void* C, void* stream) {
+    return guarded([&] {
+        if (!plan || !C || (!B && plan->plan.fmt.nnz > 0)) fail(ACC_SPMM_ERR_INVALID_ARG, "null argument");
+        launch_execute(plan->plan, B, N, C, static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, false, true);
     });
 }
 

@@ -7,6 +7,12 @@
 
 #include "execute.h"
 
+// Device memory for acc_spmm_execute_static: the partial tiles of split row windows and the
+// gathered most used rows of B of one call.  One copy per GPU, held from the time the library
+// is loaded until the process ends; host code reaches it only through the address that
+// hipGetSymbolAddress returns for the current device (static_scratch_base below).
+static __device__ __align__(256) unsigned char scratch[ACC_SPMM_STATIC_SCRATCH_BYTES];
+
 namespace accspmm {
 namespace {
 
@@ -96,6 +102,35 @@ __global__ __launch_bounds__(256) void calibration_copy_kernel(uintx4* __restric
         dst[i] = src[i];
 }
 
+// Address of `scratch` on device `dev`, which must be the current device.  Every GPU has its own
+// copy of the array at its own address; it is looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_base[kMaxDevices] = {};
+
+unsigned char* static_scratch_base(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) fail(ACC_SPMM_ERR_UNSUPPORTED, "device index beyond the static scratch table");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_base[dev]) {
+        void* ptr = nullptr;
+        ACC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) fail(ACC_SPMM_ERR_HIP, "hipGetSymbolAddress returned no address for the static scratch array");
+        g_scratch_base[dev] = static_cast<unsigned char*>(ptr);
+    }
+    return g_scratch_base[dev];
+}
+
+// A call that would have to allocate while its stream is being captured into a graph fails
+// instead: hipMalloc / hipFree are not legal there, and hipFree would wait for the device.
+void refuse_allocation_under_capture(hipStream_t stream, const char* what) {
+    if (!stream) return;
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &status) != hipSuccess || status != hipStreamCaptureStatusNone)
+        fail(ACC_SPMM_ERR_INVALID_ARG,
+             std::string("the stream is being captured and this call would have to allocate ") + what +
+                 ": run one call at this N outside the capture first, or use acc_spmm_execute_static");
+}
+
 // Measurement aid: nothing but the memory pattern of the tile kernel's B gather.  A wavefront walks
 // its share of `index` sixteen entries (one "tile") at a time; each 16-lane group reads four of the
 // sixteen rows, 16 bytes per lane, so that sixteen lanes cover 256 contiguous bytes of a row (wider
@@ -168,8 +203,14 @@ void launch_calibration_gather(const void* table, int64_t rows, int64_t row_byte
     ACC_HIP(hipGetLastError());
 }
 
+void prepare_static_scratch() {
+    int dev = -1;
+    ACC_HIP(hipGetDevice(&dev));
+    (void)static_scratch_base(dev);
+}
+
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream, float* tiles_ms,
-                    float* combine_ms, float* gather_ms, bool narrow_c) {
+                    float* combine_ms, float* gather_ms, bool narrow_c, bool static_scratch) {
     const bool timed = tiles_ms != nullptr;
     hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
     if (timed) {
@@ -192,28 +233,44 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     int dev = -1;
     ACC_HIP(hipGetDevice(&dev));
     if (dev != plan.device) fail(ACC_SPMM_ERR_INVALID_ARG, "the plan lives on another device than the current one");
-    if (plan.n_slots > 0) {
-        // grown only when a wider N arrives; hipFree inside alloc() waits for kernels still using the old buffer
-        std::lock_guard<std::mutex> lock(plan.workspace_mutex);
-        if (plan.workspace_N < N) {
-            plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
-            plan.workspace_N = N;
-        }
-    }
     // Column order with B in the caller's order: gather the most used rows and read the rest in place,
     // unless the plan also kept plain entries and this call's rows are narrow (the gathered copy needs
     // 64-bit addressing, which costs more than it gains at N <= 64 on plans of that size).
     const bool hot_entries = plan.d_col_order.p != nullptr && plan.opt.operand_order == 0 && f.nnz > 0;
     const bool gather = hot_entries && !(plan.a2b_plain.p != nullptr && N <= 64);
-    if (gather && plan.n_hot > 0) {
+    float* ws = nullptr;          // partial tiles of split windows, n_slots x 16 x N
+    uint16_t* b_hot = nullptr;    // gathered most used rows of B, n_hot x N
+    const size_t ws_bytes = (size_t)plan.n_slots * 16 * (size_t)N * sizeof(float);
+    const size_t hot_bytes = (gather && plan.n_hot > 0) ? (size_t)plan.n_hot * (size_t)N * sizeof(uint16_t) : 0;
+    if (static_scratch) {
+        // both buffers inside the library's static device array; nothing is allocated
+        const size_t ws_span = (ws_bytes + 255) & ~(size_t)255;
+        if (ws_span + hot_bytes > (size_t)ACC_SPMM_STATIC_SCRATCH_BYTES)
+            fail(ACC_SPMM_ERR_UNSUPPORTED,
+                 "acc_spmm_execute_static: this plan at this N needs " + std::to_string(ws_span + hot_bytes) +
+                     " bytes of scratch memory (split-window partial tiles + gathered rows of B), the static buffer holds " +
+                     std::to_string((size_t)ACC_SPMM_STATIC_SCRATCH_BYTES) + "; use acc_spmm_execute");
+        unsigned char* base = static_scratch_base(dev);
+        ws = reinterpret_cast<float*>(base);
+        b_hot = reinterpret_cast<uint16_t*>(base + ws_span);
+    } else {
+        // grown only when a wider N arrives; hipFree inside alloc() waits for kernels still using the old buffer
         std::lock_guard<std::mutex> lock(plan.workspace_mutex);
-        if (plan.b_hot_N < N) {
+        if (plan.n_slots > 0 && plan.workspace_N < N) {
+            refuse_allocation_under_capture(stream, "the partial-tile workspace of the split row windows");
+            plan.workspace.alloc((size_t)plan.n_slots * 16 * (size_t)N);
+            plan.workspace_N = N;
+        }
+        if (hot_bytes > 0 && plan.b_hot_N < N) {
+            refuse_allocation_under_capture(stream, "the buffer for the gathered rows of B");
             plan.b_hot.alloc((size_t)plan.n_hot * (size_t)N);
             plan.b_hot_N = N;
         }
+        ws = plan.workspace.p;
+        b_hot = plan.b_hot.p;
     }
     if (timed) ACC_HIP(hipEventRecord(ev[3], stream));
-    if (gather) launch_permute_rows(plan.d_col_order.p, plan.n_hot, B, plan.b_hot.p, (int64_t)N * 2, false, stream);
+    if (gather) launch_permute_rows(plan.d_col_order.p, plan.n_hot, B, b_hot, (int64_t)N * 2, false, stream);
     ExecParams p;
     p.rwo = f.row_window_offset.p;
     p.tco = f.tc_offset.p;
@@ -224,7 +281,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.items = plan.d_items.p;
     p.B = static_cast<const uint16_t*>(B);
     p.C = static_cast<float*>(C);
-    p.ws = plan.workspace.p;
+    p.ws = ws;
     p.n_items = (int32_t)plan.items.size();
     p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
     // Cooperative value fetch (see the file header) where it measured faster: dense tiles at any
@@ -235,7 +292,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     const bool narrow_rows = N >= 32 && N <= 64 && plan.stats.num_tiles >= 16384;
     p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && (dense_tiles || narrow_rows));
     p.N = N;
-    p.B_hot = plan.b_hot.p;
+    p.B_hot = b_hot;
     p.addr = gather ? kAddrHot
                     : ((plan.stats.K >= (1 << 24) || (int64_t)plan.stats.K * N * 2 >= ((int64_t)1 << 32)) ? kAddrWide
                                                                                                         : kAddrNarrow);
@@ -272,7 +329,7 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     if (timed) ACC_HIP(hipEventRecord(ev[1], stream));
     if (!plan.splits.empty()) {
         hipLaunchKernelGGL(combine_split_kernel, dim3((unsigned)plan.splits.size()), dim3(256), 0, stream,
-                           plan.d_splits.p, plan.workspace.p, plan.d_perm_pad.p, C, N,
+                           plan.d_splits.p, ws, plan.d_perm_pad.p, C, N,
                            narrow_c ? (plan.opt.value_type == ACC_SPMM_BF16 ? 2 : 1) : 0);
         ACC_HIP(hipGetLastError());
     }

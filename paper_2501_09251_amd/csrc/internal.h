@@ -166,10 +166,16 @@ struct Plan {
 
 // execute.hip
 // tiles_ms non-null: time the kernels with events and wait for them.  narrow_c: C holds 16-bit
-// values of the plan's value type instead of fp32.
+// values of the plan's value type instead of fp32.  static_scratch: the call's temporary device
+// buffers live in the library's static device array instead of buffers of the plan, and nothing
+// is allocated.
 void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStream_t stream,
                     float* tiles_ms = nullptr, float* combine_ms = nullptr, float* gather_ms = nullptr,
-                    bool narrow_c = false);
+                    bool narrow_c = false, bool static_scratch = false);
+// Looks up, once per device, the address of the static device array behind acc_spmm_execute_static
+// on the current device (done when a plan is created, so that the execute call itself has no
+// set-up left to do).
+void prepare_static_scratch();
 void launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 void launch_calibration_gather(const void* table, int64_t rows, int64_t row_bytes, const int32_t* index, int64_t n_index,
                                void* sink, size_t sink_bytes, void* out, size_t out_bytes, int32_t write_every,

@@ -188,6 +188,7 @@ acc_spmm_plan_t* load_plan(const char* path) {
     Plan& P = handle->plan;
     try {
         ACC_HIP(hipGetDevice(&P.device));
+        prepare_static_scratch();
         r.bytes(&P.opt, sizeof P.opt);
         r.bytes(&P.stats, sizeof P.stats);
         Scalars s{};

@@ -1,26 +1,32 @@
 #!/usr/bin/env python3
 """Benchmark of the SpMM hot path on one MI355X.
 
-One "step" is one acc_spmm_execute (tile kernel + split-window combine) on a workload whose
-plan was built once beforehand; plan time is reported separately (the paper amortises its
-preprocessing over iterative use, Section 4.3.2).  Prints ONE JSON line:
+One "step" is one acc_spmm_execute (gather of the most used rows of B where the plan does one +
+tile kernel + split-window combine) on a workload whose plan was built once beforehand; plan time
+is reported separately (the paper amortises its preprocessing over iterative use, Section 4.3.2).
+Prints ONE JSON line.  The headline is workload 5 (the configuration the metric is quoted on):
 
   value       effective GFLOP/s = 2*nnz*N / t_step, inputs resident in HBM
   roofline    algorithmic bytes of the tile kernel (A values + A indices + each window's
               distinct B rows + C, counted from the plan) / its average duration measured
-              with HIP events on the launch stream, against 8 TB/s
+              with HIP events on the launch stream, against 8 TB/s; beside it the lower bracket
+              (B read once) and, when a counter summary under profiles/ covers the workload, the
+              bytes that missed in L2 (`traffic`)
+  ceilings    what the machine delivers, in this run, for the tile kernel's memory pattern alone
+              (the library's measurement aids: row gather, row gather with bursts of writes, copy)
+  workloads   the same figures for workloads 1-4 (each planned and run in this process)
   cpu_baseline  the fp64 CSR oracle timed on the host cores on a bounded row sample
   naive_gpu   the one-wavefront-per-row CSR kernel on the same inputs
-  execute_c16 with --c16: the same plan and kernels with C rounded to 16 bits in the store
-              (beside the metric, never part of it: the metric's C is fp32)
 
 Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--shrink S]
 """
 from __future__ import annotations
 
 import argparse
+import glob
 import json
 import os
+import re
 import sys
 import time
 
@@ -32,25 +38,33 @@ sys.path.insert(0, ROOT)
 PAPER_CONTEXT = ("paper reports speedups over cuSPARSE only (avg 2.52x RTX 4090, 1.91x A800, 1.58x H100, TF32); "
                  "no absolute throughput is published")
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes per launch of the tile kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs scaled by the library's plain copy kernel (summaries under profiles/); None = not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "rmat-2^23-deg32-N128": 59.05e9,
-    "rmat-2^20-deg16-sym-N128": 3.09e9,
-    "stencil27-128^3-N64": 1.68e9,
-    "sbm-2^18-c64-N256": 0.99e9,
-}
+TRAFFIC_KIND = ("bytes that missed in L2 and went to the fabric (FETCH_SIZE scaled by a plain copy + WRITE_SIZE); "
+                "hits in the memory-side cache are included, no counter on this machine separates HBM from it")
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload_name):
+    """L2-miss bytes per launch of the tile kernel with library defaults, from the counter summaries
+    under profiles/ (lines `TRAFFIC workload=... fetch_bytes=... write_bytes=... commit=...`, written
+    when the counters were read).  None if no summary covers the workload."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*l2_miss_traffic*.txt"))):
+        with open(path) as f:
+            for line in f:
+                if not line.startswith("TRAFFIC "):
+                    continue
+                kv = dict(item.split("=", 1) for item in line.split()[1:])
+                if kv.get("workload") == workload_name:
+                    return {"fetch_bytes": float(kv["fetch_bytes"]), "write_bytes": float(kv["write_bytes"]),
+                            "file": os.path.relpath(path, ROOT), "measured_at_commit": kv.get("commit")}
+    return None
+
+
 def gpu_clocks():
     """Current clocks of the first GPU, read from the driver's sysfs files (the figures rocm-smi
     --showclocks prints; no child process is started).  None if the files are not there."""
-    import glob
-    import re
     clocks = {}
     for card in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
         for name, fname in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk")):
@@ -67,72 +81,67 @@ def gpu_clocks():
     return clocks or None
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=5, help="workload 1..5 of the benchmark set (default: 5, the configuration the metric is quoted on)")
-    ap.add_argument("--shrink", type=int, default=0, help="divide the row count by 2^shrink (debugging)")
-    ap.add_argument("--reorder", choices=["off", "on", "auto"], default="auto")
-    ap.add_argument("--load-balance", choices=["off", "on", "auto"], default="auto")
-    ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
-    ap.add_argument("--no-prefetch", action="store_true")
-    ap.add_argument("--streaming-stores", action="store_true")
-    ap.add_argument("--mtx", default=None, metavar="FILE",
-                    help="instead of a synthetic workload: A from this Matrix Market file, B = N(0,1) with --mtx-n columns")
-    ap.add_argument("--mtx-n", type=int, default=128)
-    ap.add_argument("--column-order", choices=("off", "on", "auto"), default="auto")
-    ap.add_argument("--b-in-plan-order", action="store_true",
-                    help="hand B over in the plan's column order (permuted once, outside the timed region) "
-                         "instead of letting every step gather it")
-    ap.add_argument("--c16", action="store_true", help="also time acc_spmm_execute_c16 (C rounded to 16 bits)")
-    ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2),
-                    help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-naive", action="store_true")
-    ap.add_argument("--no-vendor", action="store_true", help="skip the torch.sparse.mm (hipSPARSE) comparison")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also launch the library's plain copy kernel on 1 GiB (for scaling rocprofv3 --pmc counters)")
-    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target CPU time of the oracle sample")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
-              file=sys.stderr)
-        return 2
+def event_ms(torch, fn, reps):
+    """Average duration of fn() over `reps` calls, HIP events on the stream fn launches on."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
 
-    import torch
-    import paper_2501_09251_amd as acc
-    import workloads as wl
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
-        return 2
-    acc.load()
+def measure_ceilings(torch, acc, table, rows, row_bytes, stream):
+    """The library's measurement aids on a table of this workload's B (same size, same row length):
+    random row gather, the same with a burst of writes per 28 tiles (a window of C per window's
+    tiles, as on workload 5), and a plain copy."""
+    dev = table.device
+    n_index = 1 << 26
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    index = torch.randint(0, rows, (n_index,), dtype=torch.int32, device=dev, generator=gen)
+    sink = torch.empty(16 << 20, dtype=torch.uint8, device=dev)
+    n_tiles = n_index // 16
+    waves = 4 * min((n_tiles + 3) // 4, 4096)
+    per_wave = -(-n_tiles // waves)
+    write_every, write_rows = 28, 16
+    out_bytes = waves * -(-per_wave // write_every) * write_rows * 2 * row_bytes
+    out = torch.empty(out_bytes, dtype=torch.uint8, device=dev)
+    t_gather = event_ms(torch, lambda: acc.acc_spmm_calibration_gather(table, rows, row_bytes, index, n_index, sink,
+                                                                       sink.numel(), None, 0, 0, 0, stream), 3)
+    t_mixed = event_ms(torch, lambda: acc.acc_spmm_calibration_gather(table, rows, row_bytes, index, n_index, sink,
+                                                                      sink.numel(), out, out_bytes, write_every,
+                                                                      write_rows, stream), 3)
+    gathered = n_index * row_bytes + n_index * 4
+    del index, out
+    src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    t_copy = event_ms(torch, lambda: acc.acc_spmm_calibration_copy(dst, src, src.numel(), stream), 3)
+    del src, dst, sink
+    torch.cuda.empty_cache()
+    return {
+        "kind": "library measurement aids timed in this run with HIP events; GB/s of bytes requested",
+        "table_bytes": rows * row_bytes, "row_bytes": row_bytes, "rows_gathered": n_index,
+        "gather_rows_GBps": gathered / (t_gather * 1e-3) / 1e9,
+        "gather_rows_with_write_bursts_GBps": (gathered + out_bytes) / (t_mixed * 1e-3) / 1e9,
+        "gather_rows_with_write_bursts": {"read_bytes": gathered, "written_bytes": out_bytes, "ms": t_mixed,
+                                          "tiles_per_burst": write_every, "rows_per_burst": write_rows},
+        "copy_read_plus_write_GBps": 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9,
+    }
+
+
+def run_workload(torch, acc, oracle, w, args, opt_kw, headline):
+    """Plan, time and check one workload; returns the figures as a dict."""
     dev = torch.device("cuda:0")
-    mode = {"off": acc.ACC_SPMM_OFF, "on": acc.ACC_SPMM_ON, "auto": acc.ACC_SPMM_AUTO}
-
     t0 = time.time()
-    if args.mtx:
-        M, K, rowptr, colidx, vals = acc.read_matrix_market(args.mtx)
-        w = wl.Workload(name=f"{os.path.basename(args.mtx)}-N{args.mtx_n}", M=M, K=K, N=args.mtx_n, rowptr=rowptr,
-                        colidx=colidx, vals=vals, B=wl.dense(K, args.mtx_n, wl.SEED_BASE, "normal", 0.0, 1.0))
-    else:
-        w = wl.config(args.config, args.shrink)
-    t_gen = time.time() - t0
-    log(f"[bench] workload {w.name}: M={w.M} nnz={w.nnz} N={w.N} generated in {t_gen:.1f}s")
-
-    t0 = time.time()
-    opt = acc.make_options(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
-                           max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
-                           no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores),
-                           value_fetch=args.value_fetch, column_order=mode[args.column_order],
-                           operand_order=int(args.b_in_plan_order))
-    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(**opt_kw))
     t_plan = time.time() - t0
     st = acc.acc_spmm_plan_stats(plan)
     tr = acc.acc_spmm_plan_traffic(plan, w.N)
-    log(f"[bench] plan built in {t_plan:.1f}s: tiles={st['num_tiles']} items={st['num_items']} "
+    log(f"[bench] {w.name}: plan built in {t_plan:.1f}s: tiles={st['num_tiles']} items={st['num_items']} "
         f"split={st['num_split_windows']} ibd={st['ibd']:.2f} reorder={st['reorder_applied']} lb={st['load_balance_applied']}")
 
     B = torch.from_numpy(w.B.view(np.int16)).to(dev)
@@ -144,7 +153,7 @@ def main() -> int:
         acc.acc_spmm_permute_rows(plan, B_caller, B, w.N * 2, 0, stream)
     torch.cuda.synchronize()
 
-    if args.calibrate_copy:
+    if args.calibrate_copy and headline:
         src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)       # 1 GiB
         dst = torch.empty_like(src)
         for _ in range(3):
@@ -197,7 +206,7 @@ def main() -> int:
     # ---- on request, the same call with C rounded to 16 bits in the store (not the metric: reported
     # beside it; off by default so that a kernel trace of the default run holds fp32 launches only)
     c16 = None
-    if args.c16:
+    if args.c16 and headline:
         C16 = torch.empty((max(w.M, 1), w.N), dtype=torch.int16, device=dev)
         for _ in range(args.warmup):
             acc.acc_spmm_execute_c16(plan, B, w.N, C16, stream)
@@ -210,18 +219,23 @@ def main() -> int:
         c16 = {"ms_per_step": t_c16 * 1e3, "value": flops / t_c16 / 1e9, "unit": "GFLOP/s",
                "kind": "same plan and kernels, C rounded to the 16-bit value type in the store"}
         del C16
-    clocks = gpu_clocks()
     alg_bytes = tr["a_bytes"] + tr["b_bytes"] + tr["c_bytes"]
-    achieved = alg_bytes / (tiles_avg * 1e-3) / 1e9 if tiles_avg > 0 else 0.0
+    lower_bytes = tr["a_bytes"] + 2 * w.K * w.N + tr["c_bytes"]
+    kernel_s = tiles_avg * 1e-3
+    achieved = alg_bytes / kernel_s / 1e9 if tiles_avg > 0 else 0.0
 
     # ---- spot check of the timed result against the oracle (sampled rows)
-    import oracle
     rng = np.random.default_rng(1)
     rows = np.unique(np.concatenate([rng.integers(0, w.M, 512), np.argsort(np.diff(w.rowptr))[-8:]]))
     C_rows = C[torch.from_numpy(rows).to(dev)].cpu().numpy()
     C_ref, bound = oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=rows)
     ok, ratio = oracle.within_bound(C_rows, C_ref, bound)
-    log(f"[bench] parity spot check on {len(rows)} rows: ok={ok} worst error/limit={ratio:.3g}")
+    log(f"[bench] {w.name}: parity spot check on {len(rows)} rows: ok={ok} worst error/limit={ratio:.3g}")
+
+    # ---- what the memory system gives for this access pattern alone (headline only)
+    ceilings = None
+    if headline and not args.no_ceilings and w.K > 0 and (w.N * 2) % 16 == 0:
+        ceilings = measure_ceilings(torch, acc, B_caller, w.K, w.N * 2, stream)
 
     # ---- naive GPU baseline
     naive = None
@@ -237,10 +251,9 @@ def main() -> int:
         naive = {"value": flops / t_naive / 1e9, "unit": "GFLOP/s", "ms": t_naive * 1e3,
                  "kind": "one wavefront per CSR row, fp32 FMA"}
 
-    # ---- the vendor library as PyTorch reaches it, for context (the paper's own headline is a speedup
-    #      over the vendor library of its GPUs).  hipSPARSE has no fp16 SpMM, so this leg runs in fp32.
+    # ---- on request, the vendor library as PyTorch reaches it (hipSPARSE has no fp16 SpMM: fp32)
     vendor = None
-    if not args.no_vendor and w.nnz > 0:
+    if args.vendor and headline and w.nnz > 0:
         try:
             import warnings
             with warnings.catch_warnings():
@@ -266,14 +279,15 @@ def main() -> int:
 
     # ---- CPU baseline: the oracle as it stands, on a bounded sample of rows
     cpu = None
+    cpu_seconds = args.cpu_seconds if headline else min(args.cpu_seconds, 3.0)
     if not args.no_cpu_baseline:
         threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-        probe = rng.integers(0, w.M, 4096).astype(np.int64)
+        probe = rng.integers(0, w.M, min(4096, w.M)).astype(np.int64)
         t0 = time.perf_counter()
         oracle.spmm(w.rowptr, w.colidx, w.vals, w.B, rows=probe, want_bound=False)
         dt = max(time.perf_counter() - t0, 1e-4)
         per_row = dt / len(probe)
-        n_rows = int(min(w.M, max(4096, args.cpu_seconds / per_row)))
+        n_rows = int(min(w.M, max(4096, cpu_seconds / per_row)))
         sample = np.sort(rng.choice(w.M, n_rows, replace=False)).astype(np.int64) if n_rows < w.M else np.arange(w.M, dtype=np.int64)
         nnz_s = int((w.rowptr[sample + 1] - w.rowptr[sample]).sum())
         t0 = time.perf_counter()
@@ -283,32 +297,36 @@ def main() -> int:
                "sample": f"{n_rows} random rows ({nnz_s} nnz) of the same workload, fp64 CSR SpMM, {dt:.1f}s"}
 
     acc.acc_spmm_destroy(plan)
-    traffic = (MEASURED_TRAFFIC_BYTES.get(w.name)
-               if (args.reorder, args.load_balance, args.column_order) == ("auto", "auto", "auto") and not args.mtx else None)
-    out = {
-        "metric": "SpMM effective GFLOP/s (2·nnz·N/t) + achieved HBM GB/s vs roofline, 1 MI355X",
-        "value": value, "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": t_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16", "data": "A from a user file, B synthetic" if args.mtx else "synthetic",
-        "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
-                   "reorder": args.reorder, "load_balance": args.load_balance, "column_order": args.column_order,
-                   "B_order": "plan" if args.b_in_plan_order else "caller"},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic,
-                     # the same kernel time against the measured bytes instead of the algorithmic ones
-                     "traffic_GBps": traffic / (tiles_avg * 1e-3) / 1e9 if traffic and tiles_avg > 0 else None,
-                     "traffic_frac": traffic / (tiles_avg * 1e-3) / 1e9 / HBM_PEAK_GBS if traffic and tiles_avg > 0 else None,
-                     "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
-                     "kernel_ms_median": float(np.median(tiles_ms)),
-                     "combine_ms_avg": float(np.mean(combine_ms)), "gather_B_ms_avg": float(np.mean(gather_ms)),
-                     "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"],
-                     "c_bytes": tr["c_bytes"], "b_bytes_upper_nnzN2": 2 * w.nnz * w.N, "b_bytes_lower_KN2": 2 * w.K * w.N,
-                     "mfma_flops_issued": tr["mfma_flops"]},
-        "cpu_baseline": cpu,
-        "naive_gpu": naive,
-        "vendor_library": vendor,
-        "plan": {"seconds": t_plan, "validate_s": st["t_validate_s"], "reorder_s": st["t_reorder_s"],
+    del B, B_caller, C
+    torch.cuda.empty_cache()
+
+    defaults = (args.reorder, args.load_balance, args.column_order) == ("auto", "auto", "auto") and not args.mtx \
+        and not args.shrink and not args.b_in_plan_order and not args.cap and not args.value_fetch
+    tm = measured_traffic(w.name) if defaults else None
+    traffic = tm["fetch_bytes"] + tm["write_bytes"] if tm else None
+    roofline = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        # bytes that missed in L2, per launch, when a counter summary under profiles/ covers this workload
+        "traffic": traffic,
+        "traffic_kind": TRAFFIC_KIND if tm else None,
+        "traffic_source": {"file": tm["file"], "measured_at_commit": tm["measured_at_commit"]} if tm else None,
+        "traffic_GBps": traffic / kernel_s / 1e9 if traffic and tiles_avg > 0 else None,
+        "traffic_frac": traffic / kernel_s / 1e9 / HBM_PEAK_GBS if traffic and tiles_avg > 0 else None,
+        "kernel": "spmm_tiles_kernel", "kernel_ms_avg": tiles_avg, "kernel_ms_min": float(np.min(tiles_ms)),
+        "kernel_ms_median": float(np.median(tiles_ms)),
+        "combine_ms_avg": float(np.mean(combine_ms)), "gather_B_ms_avg": float(np.mean(gather_ms)),
+        # `achieved` counts every window's distinct B rows once per window; rows that several windows
+        # share and that hit in L2 never reach the fabric, so this figure can exceed the peak.  The
+        # bound that cannot be beaten reads B once: the kernel's bytes over time lie between the two.
+        "algorithmic_bytes": alg_bytes, "a_bytes": tr["a_bytes"], "b_bytes": tr["b_bytes"], "c_bytes": tr["c_bytes"],
+        "lower_bound_bytes_B_read_once": lower_bytes,
+        "lower_bound_GBps": lower_bytes / kernel_s / 1e9 if tiles_avg > 0 else None,
+        "lower_bound_frac": lower_bytes / kernel_s / 1e9 / HBM_PEAK_GBS if tiles_avg > 0 else None,
+        "b_bytes_upper_nnzN2": 2 * w.nnz * w.N, "b_bytes_lower_KN2": 2 * w.K * w.N,
+        "mfma_flops_issued": tr["mfma_flops"],
+        "ceilings": ceilings,
+    }
+    plan_info = {"seconds": t_plan, "validate_s": st["t_validate_s"], "reorder_s": st["t_reorder_s"],
                  "reorder_graph_s": st["t_graph_s"], "reorder_dendrogram_s": st["t_dendrogram_s"],
                  "reorder_ordering_s": st["t_ordering_s"], "reorder_work_ratio": st["reorder_work_ratio"],
                  "encode_s": st["t_encode_s"], "schedule_s": st["t_schedule_s"],
@@ -317,17 +335,133 @@ def main() -> int:
                  "split_windows": st["num_split_windows"], "partial_slots": st["num_partial_slots"],
                  "reorder_applied": st["reorder_applied"], "load_balance_applied": st["load_balance_applied"],
                  "column_order_applied": st["column_order_applied"], "hub_label_skew": st["hub_label_skew"],
-                 "column_order_s": st["t_column_order_s"]},
+                 "column_order_s": st["t_column_order_s"]}
+    return {
+        "value": value, "unit": "GFLOP/s", "ms_per_step": t_step * 1e3,
+        "config": {"workload": w.name, "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
+                   "reorder": args.reorder, "load_balance": args.load_balance, "column_order": args.column_order,
+                   "B_order": "plan" if args.b_in_plan_order else "caller"},
+        "roofline": roofline, "cpu_baseline": cpu, "naive_gpu": naive, "vendor_library": vendor, "plan": plan_info,
         "parity_spot_check": {"rows": int(len(rows)), "ok": bool(ok), "worst_error_over_limit": ratio},
-        "execute_c16": c16,
-        "back_to_back_100_launches_us": back_to_back_us,
+        "execute_c16": c16, "back_to_back_100_launches_us": back_to_back_us,
         "hip_graph_of_100_launches_us_per_launch": graph_replay_us,
-        "clocks": clocks,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, help="workload 1..5 of the benchmark set (default: 5, the configuration the metric is quoted on)")
+    ap.add_argument("--shrink", type=int, default=0, help="divide the row count by 2^shrink (debugging)")
+    ap.add_argument("--reorder", choices=["off", "on", "auto"], default="auto")
+    ap.add_argument("--load-balance", choices=["off", "on", "auto"], default="auto")
+    ap.add_argument("--cap", type=int, default=0, help="max tiles per work item (0 = library default)")
+    ap.add_argument("--no-prefetch", action="store_true")
+    ap.add_argument("--streaming-stores", action="store_true")
+    ap.add_argument("--mtx", default=None, metavar="FILE",
+                    help="instead of a synthetic workload: A from this Matrix Market file, B = N(0,1) with --mtx-n columns")
+    ap.add_argument("--mtx-n", type=int, default=128)
+    ap.add_argument("--column-order", choices=("off", "on", "auto"), default="auto")
+    ap.add_argument("--b-in-plan-order", action="store_true",
+                    help="hand B over in the plan's column order (permuted once, outside the timed region) "
+                         "instead of letting every step gather it")
+    ap.add_argument("--c16", action="store_true", help="also time acc_spmm_execute_c16 (C rounded to 16 bits)")
+    ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2),
+                    help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-naive", action="store_true")
+    ap.add_argument("--vendor", action="store_true",
+                    help="also time torch.sparse.mm (hipSPARSE, fp32) on the headline workload, as context")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the gather / copy measurement aids")
+    ap.add_argument("--only", action="store_true", help="run the --config workload only, not the other four beside it")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel on 1 GiB (for scaling rocprofv3 --pmc counters)")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import oracle
+    import paper_2501_09251_amd as acc
+    import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        return 2
+    acc.load()
+    mode = {"off": acc.ACC_SPMM_OFF, "on": acc.ACC_SPMM_ON, "auto": acc.ACC_SPMM_AUTO}
+    opt_kw = dict(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
+                  max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
+                  no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores),
+                  value_fetch=args.value_fetch, column_order=mode[args.column_order],
+                  operand_order=int(args.b_in_plan_order))
+
+    t0 = time.time()
+    if args.mtx:
+        M, K, rowptr, colidx, vals = acc.read_matrix_market(args.mtx)
+        w = wl.Workload(name=f"{os.path.basename(args.mtx)}-N{args.mtx_n}", M=M, K=K, N=args.mtx_n, rowptr=rowptr,
+                        colidx=colidx, vals=vals, B=wl.dense(K, args.mtx_n, wl.SEED_BASE, "normal", 0.0, 1.0))
+    else:
+        w = wl.config(args.config, args.shrink)
+    t_gen = time.time() - t0
+    log(f"[bench] workload {w.name}: M={w.M} nnz={w.nnz} N={w.N} generated in {t_gen:.1f}s")
+    head = run_workload(torch, acc, oracle, w, args, opt_kw, headline=True)
+    del w
+
+    # the other workloads of the set beside the headline, same process, same options
+    others = []
+    if not args.only and not args.mtx:
+        for cfg in (1, 2, 3, 4, 5):
+            if cfg == args.config:
+                continue
+            t0 = time.time()
+            wk = wl.config(cfg, args.shrink)
+            log(f"[bench] workload {wk.name}: M={wk.M} nnz={wk.nnz} N={wk.N} generated in {time.time() - t0:.1f}s")
+            r = run_workload(torch, acc, oracle, wk, args, opt_kw, headline=False)
+            rf = r["roofline"]
+            others.append({"workload": r["config"]["workload"], "M": wk.M, "N": wk.N, "nnz": wk.nnz,
+                           "value": r["value"], "unit": "GFLOP/s", "ms_per_step": r["ms_per_step"],
+                           "kernel_ms_avg": rf["kernel_ms_avg"], "combine_ms_avg": rf["combine_ms_avg"],
+                           "gather_B_ms_avg": rf["gather_B_ms_avg"], "algorithmic_bytes": rf["algorithmic_bytes"],
+                           "roofline_frac": rf["frac"], "lower_bound_bytes_B_read_once": rf["lower_bound_bytes_B_read_once"],
+                           "lower_bound_frac": rf["lower_bound_frac"], "traffic": rf["traffic"],
+                           "traffic_frac": rf["traffic_frac"], "traffic_source": rf["traffic_source"],
+                           "mfma_flops_issued": rf["mfma_flops_issued"],
+                           "naive_gpu_ms": r["naive_gpu"]["ms"] if r["naive_gpu"] else None,
+                           "cpu_baseline": r["cpu_baseline"], "parity_spot_check": r["parity_spot_check"],
+                           "plan_seconds": r["plan"]["seconds"], "plan": r["plan"],
+                           "back_to_back_100_launches_us": r["back_to_back_100_launches_us"],
+                           "hip_graph_of_100_launches_us_per_launch": r["hip_graph_of_100_launches_us_per_launch"]})
+            del wk
+
+    out = {
+        "metric": "SpMM effective GFLOP/s (2·nnz·N/t) + achieved HBM GB/s vs roofline, 1 MI355X",
+        "value": head["value"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "A from a user file, B synthetic" if args.mtx else "synthetic",
+        "config": head["config"],
+        "roofline": head["roofline"],
+        "cpu_baseline": head["cpu_baseline"],
+        "naive_gpu": head["naive_gpu"],
+        "workloads": others,
+        "vendor_library": head["vendor_library"],
+        "plan": head["plan"],
+        "parity_spot_check": head["parity_spot_check"],
+        "execute_c16": head["execute_c16"],
+        "back_to_back_100_launches_us": head["back_to_back_100_launches_us"],
+        "hip_graph_of_100_launches_us_per_launch": head["hip_graph_of_100_launches_us_per_launch"],
+        "clocks": gpu_clocks(),
         "generate_s": t_gen,
         "paper_context": PAPER_CONTEXT,
     }
     print(json.dumps(out))
-    return 0 if ok else 1
+    all_ok = head["parity_spot_check"]["ok"] and all(o["parity_spot_check"]["ok"] for o in others)
+    return 0 if all_ok else 1
 
 
 if __name__ == "__main__":

@@ -125,6 +125,11 @@ typedef struct {
     /* 1: keep, for every packed value, the index of its CSR entry (4 bytes per entry), which
      * acc_spmm_sddmm needs. */
     int32_t keep_entry_map;
+    /* Step I of the reordering (Algorithm 1, dendrogram construction) runs on the GPU, in rounds that
+     * reproduce the sequential result; 1 runs its sequential host form instead (same result; for
+     * comparison).  The library switches to the host form by itself when the input does not suit the
+     * device form (acc_spmm_stats.dendrogram_on_device tells which one ran). */
+    int32_t dendrogram_on_host;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */
@@ -153,6 +158,9 @@ typedef struct {
                                 /* relative to an even spread (0 if not computed: column_order */
                                 /* OFF or K < 65536)                                           */
     double t_column_order_s;
+    int32_t dendrogram_on_device; /* 1: Step I of the reordering ran in its device form          */
+    int32_t pad_;
+    int64_t dendrogram_rounds;    /* rounds of that form (0 for the host form)                  */
 } acc_spmm_stats;
 
 /* Arrays acc_spmm_plan_export can copy out (element type, element count). */

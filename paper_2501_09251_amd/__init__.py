@@ -51,6 +51,7 @@ class acc_spmm_options(ctypes.Structure):
         ("column_order", ctypes.c_int32),
         ("operand_order", ctypes.c_int32),
         ("keep_entry_map", ctypes.c_int32),
+        ("dendrogram_on_host", ctypes.c_int32),
     ]
 
 
@@ -71,6 +72,7 @@ class acc_spmm_stats(ctypes.Structure):
         ("t_graph_s", ctypes.c_double), ("t_dendrogram_s", ctypes.c_double), ("t_ordering_s", ctypes.c_double),
         ("column_order_applied", ctypes.c_int32), ("num_hot_columns", ctypes.c_int32),
         ("hub_label_skew", ctypes.c_double), ("t_column_order_s", ctypes.c_double),
+        ("dendrogram_on_device", ctypes.c_int32), ("pad_", ctypes.c_int32), ("dendrogram_rounds", ctypes.c_int64),
     ]
 
     def as_dict(self):

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 OUT = os.path.join(HERE, "libaccspmm.so")
-SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "mtx.cpp", "serialize.cpp", "encode.hip", "graph.hip", "ordering.hip", "colorder.hip", "sddmm.hip", "execute.hip"]
+SOURCES = ["api.cpp", "reorder.cpp", "schedule.cpp", "mtx.cpp", "serialize.cpp", "encode.hip", "graph.hip", "dendrogram.hip", "ordering.hip", "colorder.hip", "sddmm.hip", "execute.hip"]
 # tile_kernel.hip is compiled once per (features per lane, value type) into its own object
 TILE_VARIANTS = [(fpl, bf16) for bf16 in (0, 1) for fpl in (8, 4, 2, 1)]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

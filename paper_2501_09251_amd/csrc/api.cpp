@@ -129,6 +129,8 @@ struct RowOrderInfo {
     bool applied = false;
     int64_t tiles_identity = -1;   // tile count in the input order, if it was counted
     double work_ratio = 0.0, t_graph = 0.0, t_dendrogram = 0.0, t_ordering = 0.0, t_total = 0.0;
+    bool on_device = false;        // Step I ran in its device form
+    int64_t rounds = 0;            // rounds of that form
 };
 
 // Row order of the plan (Section 3.2): d_perm / P.perm / P.iperm get the data-affinity order if
@@ -150,11 +152,28 @@ void choose_row_order(Plan& P, int64_t M, int64_t K, int64_t nnz, const int32_t*
         bool complete;
         {
             const double g0 = now_s();
-            HostGraph graph;
+            DeviceGraph graph;
             build_graph_on_device(M, nnz, P.d_rowptr.p, P.d_colidx.p, graph);
             const double g1 = now_s();
-            complete = build_dendrogram_host(M, graph.ptr, graph.adj, opt.segment_length, budget, P.parent, seq, seg_start,
-                                             &info.work_ratio);
+            // Step I on the GPU; its host form takes over if the device form reports that this input
+            // does not suit it (memory pools exhausted, or rounds that advance by a few vertices only)
+            std::vector<int32_t> order;
+            int how = opt.dendrogram_on_host ? kDendrogramUseHost
+                                             : build_dendrogram_on_device(graph, budget, P.parent, order, &info.work_ratio, &info.rounds);
+            if (how == kDendrogramUseHost) {
+                HostGraph host_graph;
+                copy_graph_to_host(graph, host_graph);
+                graph.adj.release();
+                graph.ptr.release();
+                info.on_device = false;
+                info.rounds = 0;
+                complete = build_dendrogram_host(M, host_graph.ptr, host_graph.adj, opt.segment_length, budget, P.parent, seq,
+                                                 seg_start, &info.work_ratio);
+            } else {
+                info.on_device = true;
+                complete = how == kDendrogramDone;
+                if (complete) leaf_sequence_from_parents(M, P.parent, order, opt.segment_length, seq, seg_start);
+            }
             info.t_graph = g1 - g0;
             info.t_dendrogram = now_s() - g1;
         }
@@ -244,6 +263,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.ibd_threshold == 0.f) opt.ibd_threshold = kDefaultIbdThreshold;
     if (opt.pipeline_depth < 0 || opt.pipeline_depth > 3) fail(ACC_SPMM_ERR_INVALID_ARG, "pipeline_depth must be 0..3");
     if (opt.value_fetch < 0 || opt.value_fetch > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "value_fetch must be 0, 1 or 2");
+    if (opt.dendrogram_on_host < 0 || opt.dendrogram_on_host > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "dendrogram_on_host must be 0 or 1");
     if (opt.value_type != ACC_SPMM_FP16 && opt.value_type != ACC_SPMM_BF16)
         fail(ACC_SPMM_ERR_INVALID_ARG, "value_type must be ACC_SPMM_FP16 or ACC_SPMM_BF16");
 
@@ -352,6 +372,8 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         st.reorder_work_ratio = ro.work_ratio;
         st.t_graph_s = ro.t_graph;
         st.t_dendrogram_s = ro.t_dendrogram;
+        st.dendrogram_on_device = ro.on_device;
+        st.dendrogram_rounds = ro.rounds;
         st.t_ordering_s = ro.t_ordering;
         st.t_validate_s = t1 - t0;
         st.t_reorder_s = ro.t_total;

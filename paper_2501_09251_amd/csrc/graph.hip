@@ -2,8 +2,9 @@
 // row/column index, an undirected unit-weight edge {i,j}, i != j, wherever A_ij or A_ji is
 // stored.  Built on the GPU: both directions of every off-diagonal entry become 64-bit keys
 // (i, j), a radix sort brings duplicates together, run heads are the directed edges, and a
-// binary search per vertex gives the row pointers.  The result is copied to pinned host
-// memory, where the sequential dendrogram step reads it.
+// binary search per vertex gives the row pointers.  The result stays in device memory for the
+// dendrogram step; copy_graph_to_host brings it to pinned host memory for the host form of
+// that step.
 #include "device_util.h"
 
 namespace accspmm {
@@ -57,11 +58,12 @@ HostGraph::~HostGraph() {
     if (adj) (void)hipHostFree(adj);
 }
 
-void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx, HostGraph& g) {
+void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx, DeviceGraph& g) {
     g.M = M;
-    ACC_HIP(hipHostMalloc((void**)&g.ptr, sizeof(int64_t) * (M + 1), hipHostMallocDefault));
+    g.two_m = 0;
+    g.ptr.alloc(M + 1);
     if (nnz == 0) {
-        std::memset(g.ptr, 0, sizeof(int64_t) * (M + 1));
+        ACC_HIP(hipMemset(g.ptr.p, 0, sizeof(int64_t) * (M + 1)));
         return;
     }
     const int vbits = bits_for(M);
@@ -80,20 +82,26 @@ void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, cons
     ACC_HIP(hipMemset(head.p + n, 0, sizeof(int32_t)));
     hipLaunchKernelGGL(mark_heads_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, 0, n, sorted.p, head.p);
     exclusive_scan_i32(tmp, head.p, head_excl.p, n + 1);
-    // row pointers; gptr[M] counts the distinct real keys (the dropped key, if any, sorts last)
-    DevBuf<int64_t> gptr;
-    gptr.alloc(M + 1);
+    // row pointers; ptr[M] counts the distinct real keys (the dropped key, if any, sorts last)
     hipLaunchKernelGGL(vertex_starts_kernel, dim3(blocks_for(M + 1, 256)), dim3(256), 0, 0, M, n, sorted.p, head_excl.p,
-                       vbits, gptr.p);
-    ACC_HIP(hipMemcpy(g.ptr, gptr.p, sizeof(int64_t) * (M + 1), hipMemcpyDeviceToHost));
-    const int64_t two_m = g.ptr[M];
-    if (two_m > 0) {
-        DevBuf<int32_t> adj;
-        adj.alloc(two_m);
+                       vbits, g.ptr.p);
+    ACC_HIP(hipMemcpy(&g.two_m, g.ptr.p + M, sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (g.two_m > 0) {
+        g.adj.alloc(g.two_m);
         hipLaunchKernelGGL(compact_edges_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, 0, n, sorted.p, head.p, head_excl.p,
-                           dropped, ((uint64_t)1 << vbits) - 1, adj.p);
-        ACC_HIP(hipHostMalloc((void**)&g.adj, sizeof(int32_t) * two_m, hipHostMallocDefault));
-        ACC_HIP(hipMemcpy(g.adj, adj.p, sizeof(int32_t) * two_m, hipMemcpyDeviceToHost));
+                           dropped, ((uint64_t)1 << vbits) - 1, g.adj.p);
+        ACC_HIP(hipGetLastError());
+        ACC_HIP(hipDeviceSynchronize());
+    }
+}
+
+void copy_graph_to_host(const DeviceGraph& d, HostGraph& g) {
+    g.M = d.M;
+    ACC_HIP(hipHostMalloc((void**)&g.ptr, sizeof(int64_t) * (d.M + 1), hipHostMallocDefault));
+    ACC_HIP(hipMemcpy(g.ptr, d.ptr.p, sizeof(int64_t) * (d.M + 1), hipMemcpyDeviceToHost));
+    if (d.two_m > 0) {
+        ACC_HIP(hipHostMalloc((void**)&g.adj, sizeof(int32_t) * d.two_m, hipHostMallocDefault));
+        ACC_HIP(hipMemcpy(g.adj, d.adj.p, sizeof(int32_t) * d.two_m, hipMemcpyDeviceToHost));
     }
 }
 

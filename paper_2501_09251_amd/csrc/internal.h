@@ -97,8 +97,31 @@ struct HostGraph {
     ~HostGraph();
 };
 
-// graph.hip: the pattern graph of A + A^T (no diagonal) from the device CSR.
-void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx, HostGraph& g);
+// The same graph in device memory.
+struct DeviceGraph {
+    int64_t M = 0, two_m = 0;   // two_m = directed entries = ptr[M]
+    DevBuf<int64_t> ptr;        // M+1
+    DevBuf<int32_t> adj;        // two_m
+};
+
+// graph.hip: the pattern graph of A + A^T (no diagonal) from the device CSR, and its copy to the host.
+void build_graph_on_device(int64_t M, int64_t nnz, const int32_t* d_rowptr, const int32_t* d_colidx, DeviceGraph& g);
+void copy_graph_to_host(const DeviceGraph& d, HostGraph& g);
+
+// dendrogram.hip: Step I of Algorithm 1 on the GPU (same result as build_dendrogram_host, bit for
+// bit).  parent gets M entries (-1 for roots), order the vertices in visiting order (ascending
+// degree, ties by id).  work_budget as for build_dendrogram_host.  Returns kDendrogramDone,
+// kDendrogramOverBudget (AUTO gives up; outputs unspecified) or kDendrogramUseHost (the device
+// form ran out of its memory pools or advances too slowly on this input: the caller runs the host
+// form instead).
+constexpr int kDendrogramDone = 0, kDendrogramOverBudget = 1, kDendrogramUseHost = 2;
+int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::vector<int32_t>& parent,
+                               std::vector<int32_t>& order, double* work_ratio, int64_t* rounds);
+
+// reorder.cpp: the leaf sequence of a dendrogram given as parent[] plus the visiting order (a
+// vertex's children in merge order are its children in visiting order), cut into segments.
+void leaf_sequence_from_parents(int64_t M, const std::vector<int32_t>& parent, const std::vector<int32_t>& order,
+                                int32_t seg_len, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start);
 
 // reorder.cpp: Step I of Algorithm 1 on the host, and the dendrogram's leaf sequence.
 // gptr / gadj: the symmetric adjacency (HostGraph layout).  parent gets M entries (-1 for

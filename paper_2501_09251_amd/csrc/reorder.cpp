@@ -226,19 +226,14 @@ bool build_dendrogram(int64_t M, const int64_t* gptr, const int32_t* gadj,
 
 }  // namespace
 
-bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, int32_t seg_len, double work_budget,
-                           std::vector<int32_t>& parent, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start,
-                           double* work_ratio) {
-    std::vector<int32_t> first_child, next_sibling;
-    const int64_t graph_size = gptr[M] + M;
-    int64_t work = 0;
-    const bool complete = build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling,
-                                           work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0, work);
-    if (work_ratio) *work_ratio = graph_size ? (double)work / (double)graph_size : 0.0;
-    if (!complete) return false;
+namespace {
 
-    // leaf sequence: roots by ascending id; a root, then its children's subtrees in merge
-    // order; each tree's sequence is cut into segments of at most seg_len leaves
+// leaf sequence: roots by ascending id; a root, then its children's subtrees in merge
+// order; each tree's sequence is cut into segments of at most seg_len leaves.  The child lists
+// (first_child / next_sibling) run from the last merged child to the first.
+void leaf_sequence(int64_t M, const std::vector<int32_t>& parent, const std::vector<int32_t>& first_child,
+                   const std::vector<int32_t>& next_sibling, int32_t seg_len, std::vector<int32_t>& seq,
+                   std::vector<int64_t>& seg_start) {
     seq.clear();
     seg_start.clear();
     seq.reserve(M);
@@ -258,7 +253,36 @@ bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, 
         for (int64_t s = tree_begin; s < (int64_t)seq.size(); s += seg_len) seg_start.push_back(s);
     }
     seg_start.push_back(M);
+}
+
+}  // namespace
+
+bool build_dendrogram_host(int64_t M, const int64_t* gptr, const int32_t* gadj, int32_t seg_len, double work_budget,
+                           std::vector<int32_t>& parent, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start,
+                           double* work_ratio) {
+    std::vector<int32_t> first_child, next_sibling;
+    const int64_t graph_size = gptr[M] + M;
+    int64_t work = 0;
+    const bool complete = build_dendrogram(M, gptr, gadj, parent, first_child, next_sibling,
+                                           work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0, work);
+    if (work_ratio) *work_ratio = graph_size ? (double)work / (double)graph_size : 0.0;
+    if (!complete) return false;
+    leaf_sequence(M, parent, first_child, next_sibling, seg_len, seq, seg_start);
     return true;
+}
+
+void leaf_sequence_from_parents(int64_t M, const std::vector<int32_t>& parent, const std::vector<int32_t>& order,
+                                int32_t seg_len, std::vector<int32_t>& seq, std::vector<int64_t>& seg_start) {
+    // a vertex is merged at its own turn, so visiting order is merge order: pushing each child at the
+    // front of its parent's list leaves the lists running from the last merged child to the first
+    std::vector<int32_t> first_child(M, -1), next_sibling(M, -1);
+    for (int64_t k = 0; k < M; ++k) {
+        const int32_t v = order[k], p = parent[v];
+        if (p < 0) continue;
+        next_sibling[v] = first_child[p];
+        first_child[p] = v;
+    }
+    leaf_sequence(M, parent, first_child, next_sibling, seg_len, seq, seg_start);
 }
 
 }  // namespace accspmm

@@ -536,7 +536,7 @@ def test_reordering_is_invisible_in_C():
 
 @pytest.mark.parametrize("seg_len", [3, 64, 1024, 3000])
 def test_permutation_is_bit_exact_for_all_segment_lengths(seg_len):
-    """Reordering (host dendrogram + GPU ordering kernel) against the oracle's permutation."""
+    """Reordering (dendrogram rounds and ordering kernel on the GPU) against the oracle's permutation."""
     from _util import random_sym_csr
     rng = np.random.default_rng(seg_len)
     graphs = [random_sym_csr(rng, 700, 6.0)[:2], random_csr(rng, 500, 500, 0.02, empty_row_frac=0.2)[:2]]
@@ -553,12 +553,55 @@ def test_permutation_is_bit_exact_for_all_segment_lengths(seg_len):
             perm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_PERM)
             iperm = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_IPERM)
             parent = acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_DENDROGRAM_PARENT)
+            assert acc.acc_spmm_plan_stats(plan)["dendrogram_on_device"] == 1
         finally:
             acc.acc_spmm_destroy(plan)
         operm, oiperm = oracle.reorder(rowptr, colidx, seg_len)
         np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0])
         np.testing.assert_array_equal(perm, operm)
         np.testing.assert_array_equal(iperm, oiperm)
+
+
+def _dendrogram_of(rowptr, colidx, **opt):
+    M = len(rowptr) - 1
+    plan = acc.acc_spmm_plan_ex(M, M, len(colidx), rowptr, colidx, np.zeros(len(colidx), np.uint16),
+                                acc.make_options(reorder=acc.ACC_SPMM_ON, **opt))
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        return acc.acc_spmm_plan_export(plan, acc.ACC_SPMM_ARR_DENDROGRAM_PARENT), st
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_dendrogram_rounds_on_special_graphs():
+    """Step I in rounds on the GPU against the oracle on graphs that stress the rounds: a star (all
+    leaves join one hub in the same rounds), a path and a ring (every vertex depends on its
+    predecessor: rounds of one vertex), a clique, two cliques joined by an edge, isolated vertices,
+    a hub with more neighbours than one wavefront decides (the multi-block path), and hubs that
+    are each other's neighbours."""
+    from _util import csr_from_edges
+    rng = np.random.default_rng(11)
+    graphs = {}
+    n = 5000
+    graphs["star"] = csr_from_edges(n, [(0, i) for i in range(1, n)])[:2]
+    graphs["path"] = csr_from_edges(600, [(i, i + 1) for i in range(599)])[:2]
+    graphs["ring"] = csr_from_edges(500, [(i, (i + 1) % 500) for i in range(500)])[:2]
+    graphs["clique"] = csr_from_edges(60, [(i, j) for i in range(60) for j in range(i)])[:2]
+    graphs["two cliques"] = csr_from_edges(40, [(i, j) for i in range(20) for j in range(i)] +
+                                           [(20 + i, 20 + j) for i in range(20) for j in range(i)] + [(0, 20)])[:2]
+    graphs["isolated"] = csr_from_edges(100, [(1, 2), (50, 51)])[:2]
+    hubs = [(h, int(x)) for h in range(4) for x in rng.choice(np.arange(4, 20000), 3000, replace=False)]
+    hubs += [(a, b) for a in range(4) for b in range(a)]
+    hubs += [(int(a), int(b)) for a, b in rng.integers(4, 20000, (30000, 2)) if a != b]
+    graphs["hubs"] = csr_from_edges(20000, hubs)[:2]
+    for name, (rowptr, colidx) in graphs.items():
+        print(f"[dendrogram] {name}", flush=True)
+        parent, st = _dendrogram_of(rowptr, colidx)
+        assert st["dendrogram_on_device"] == 1 and st["dendrogram_rounds"] >= 1, name
+        np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0], err_msg=name)
+        host_parent, st = _dendrogram_of(rowptr, colidx, dendrogram_on_host=1)
+        assert st["dendrogram_on_device"] == 0
+        np.testing.assert_array_equal(host_parent, parent, err_msg=name)
 
 
 def test_linearity_in_B_exact_on_small_integers():

@@ -36,10 +36,15 @@ constexpr int kSlots = 2048;          // most vertices decided per round
 constexpr int kRowWords = kSlots / 32;
 constexpr int kSmallRecords = 512;    // a slot with at most this many edge records is decided by one wavefront
 constexpr int kHashSize = 1024;       // entries of that wavefront's hash table in LDS
-constexpr int kUnit = 4096;           // edge records per thread block for larger slots
-constexpr int kLargeBlocks = 1024;    // grid of the kernels that walk those units
+constexpr int kUnit = 512;            // edge records per thread block for larger slots
+constexpr int kLargeBlocks = 2048;    // grid of the kernels that walk those units
 constexpr int kMaxDense = 64;         // larger slots per round (each owns a weight array over all vertices)
-constexpr int kDescPerBlock = 8;      // chunk descriptors per directory block
+// A target's chunks are listed in directory blocks inside one pool of 32-bit words.  A block is
+// {next block or -1, descriptors in use, capacity, records in its chunks} followed by `capacity`
+// descriptors of three words (chunk offset low, high, length).  A target's first block holds 4
+// descriptors, each further one twice as many up to 32, and the newest block heads the chain.
+// Blocks are referred to by their word offset divided by 4 (all block sizes are multiples of 4).
+constexpr int kDirHeader = 4, kDirFirstCap = 4, kDirMaxCap = 32;
 constexpr long long kAdjacencyFlag = 1ll << 62;
 
 constexpr int kClassNone = 0, kClassSmall = 1, kClassLarge = 2, kClassSkipped = 3;
@@ -59,9 +64,8 @@ struct Ctl {                 // round control, lives in device memory
     int n_prepared, n_eval;  // slots of this round; those among them that got the memory they need
     int n_units;
     int last_cut;            // slots the last commit kept
-    int blk_used;
     int overflow;            // a memory pool was exhausted: nothing more is committed
-    int pad;
+    long long dir_used;      // words of the directory pool in use
 };
 
 struct DS {
@@ -73,12 +77,11 @@ struct DS {
     int32_t* parent;
     int32_t* up;
     long long* dsum;
-    int32_t* head;
-    int32_t* blk_next;
-    int32_t* blk_count;
-    long long* blk_off;
-    int32_t* blk_len;
-    int32_t blk_cap;
+    int32_t* head;        // per vertex: its newest directory block, -1 if none
+    int32_t* tot_rec;     // per vertex: records in all its chunks
+    int32_t* tot_desc;    // per vertex: number of its chunks
+    int32_t* dir;         // the directory pool
+    long long dir_cap;    // its size in words
     Rec* arena;
     long long arena_cap;
     Ctl* ctl;
@@ -150,7 +153,7 @@ __device__ __forceinline__ Best best_wave_reduce(Best b) {
 
 __global__ void init_state_kernel(long long M, const long long* __restrict__ gptr, const int32_t* __restrict__ order,
                                   int32_t* idx, int32_t* parent, int32_t* up, long long* dsum, int32_t* head,
-                                  int32_t* slot_of) {
+                                  int32_t* slot_of, int32_t* tot_rec, int32_t* tot_desc) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
     idx[order[i]] = (int32_t)i;
@@ -159,6 +162,8 @@ __global__ void init_state_kernel(long long M, const long long* __restrict__ gpt
     dsum[i] = gptr[i + 1] - gptr[i];
     head[i] = -1;
     slot_of[i] = -1;
+    tot_rec[i] = 0;
+    tot_desc[i] = 0;
 }
 
 __global__ void degree_keys_kernel(long long M, const long long* __restrict__ gptr, uint32_t* key, int32_t* id) {
@@ -174,34 +179,43 @@ __global__ void compress_paths_kernel(long long M, int32_t* up) {
     if (i < M) up[i] = find_root(up, (int32_t)i);
 }
 
-// exclusive prefix sum over the block's 1024 threads; `total` gets the sum
+// exclusive prefix sum over the block's 1024 threads; `total` gets the sum (sh: 16 entries)
 __device__ __forceinline__ long long block_scan_1024(long long x, long long* sh, long long& total) {
-    const int t = threadIdx.x;
-    sh[t] = x;
-    __syncthreads();
-    for (int o = 1; o < 1024; o <<= 1) {
-        const long long y = t >= o ? sh[t - o] : 0;
-        __syncthreads();
-        sh[t] += y;
-        __syncthreads();
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    long long incl = x;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const long long y = __shfl_up(incl, o);
+        if (lane >= o) incl += y;
     }
-    const long long incl = sh[t];
-    total = sh[1023];
+    if (lane == 63) sh[wave] = incl;
     __syncthreads();
-    return incl - x;
+    long long before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const long long y = sh[w];
+        if (w < wave) before += y;
+        all += y;
+    }
+    total = all;
+    __syncthreads();
+    return before + incl - x;
 }
 
 // Round step 1 (one block of 1024 threads, two consecutive slots per thread): the round's vertices,
-// the size of their edge lists, and, in slot order, the memory the larger slots need.
+// the size of their edge lists, and, in slot order, the memory the larger slots need; then, one
+// wavefront per larger slot, the slot's descriptors (its adjacency and its chunks, with their first
+// record's position in the slot's list) and its work units.
 __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
-    __shared__ long long sh[1024];
-    __shared__ int first_unfit;
-    const int t = threadIdx.x;
+    __shared__ long long sh[16];
+    __shared__ int first_unfit, n_large;
+    __shared__ int large_list[kMaxDense];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     Ctl* const ctl = d.ctl;
     const long long pos = ctl->pos;
     const int P = ctl->P;
     const int n = (int)(d.M - pos < (long long)P ? d.M - pos : (long long)P);
-    if (t == 0) first_unfit = n;
+    if (t == 0) { first_unfit = n; n_large = 0; }
     int v[2], nrec[2], ndesc[2], cls[2];
     for (int k = 0; k < 2; ++k) {
         const int i = 2 * t + k;
@@ -212,16 +226,9 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
         d.slot_of[x] = i;
         d.s_v[i] = x;
         const long long deg = d.gptr[x + 1] - d.gptr[x];
-        long long records = deg;
-        int descs = deg > 0 ? 1 : 0;
-        int guard = 0;
-        for (int32_t b = d.head[x]; b >= 0 && guard <= d.blk_cap; b = d.blk_next[b], ++guard) {
-            const int c = d.blk_count[b];
-            for (int e = 0; e < c; ++e) records += d.blk_len[(long long)b * kDescPerBlock + e];
-            descs += c;
-        }
+        const long long records = deg + d.tot_rec[x];
         nrec[k] = (int)records;
-        ndesc[k] = descs;
+        ndesc[k] = (deg > 0 ? 1 : 0) + d.tot_desc[x];
         cls[k] = records <= kSmallRecords ? kClassSmall : kClassLarge;
     }
     // what the larger slots need, as exclusive prefix sums in slot order
@@ -261,7 +268,6 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
         d.s_nt[i] = 0;
         d.s_store[i] = 0;
         if (cls[k] != kClassLarge) continue;
-        const int32_t x = v[k];
         const int nunits = (nrec[k] + kUnit - 1) / kUnit;
         d.s_dense[i] = (int)pre[0][k];
         d.s_cand_off[i] = pre[1][k];
@@ -270,28 +276,7 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
         d.s_unit0[i] = (int)pre[3][k];
         d.s_nunits[i] = nunits;
         units_total += nunits;
-        for (int u = 0; u < nunits; ++u) d.unit_slot[pre[3][k] + u] = i;
-        // descriptors: the vertex's own adjacency first, then its chunks
-        long long j = pre[2][k], start = 0;
-        const long long deg = d.gptr[x + 1] - d.gptr[x];
-        if (deg > 0) {
-            d.d_off[j] = d.gptr[x] | kAdjacencyFlag;
-            d.d_len[j] = (int)deg;
-            d.d_start[j] = 0;
-            start = deg;
-            ++j;
-        }
-        int guard = 0;
-        for (int32_t b = d.head[x]; b >= 0 && guard <= d.blk_cap; b = d.blk_next[b], ++guard) {
-            const int c = d.blk_count[b];
-            for (int e = 0; e < c; ++e) {
-                d.d_off[j] = d.blk_off[(long long)b * kDescPerBlock + e];
-                d.d_len[j] = d.blk_len[(long long)b * kDescPerBlock + e];
-                d.d_start[j] = start;
-                start += d.d_len[j];
-                ++j;
-            }
-        }
+        large_list[atomicAdd(&n_large, 1)] = i;
     }
     long long all_units;
     (void)block_scan_1024(units_total, sh, all_units);
@@ -300,21 +285,71 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
         ctl->n_eval = n_eval;
         ctl->n_units = (int)all_units;
     }
+    // descriptors and units of the larger slots, one wavefront per slot
+    for (int q = wave; q < n_large; q += 16) {
+        const int i = large_list[q];
+        const int32_t x = d.s_v[i];
+        const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
+        for (int u = lane; u < nu; u += 64) d.unit_slot[u0 + u] = i;
+        long long j = d.s_desc_off[i], start = 0;
+        const long long deg = d.gptr[x + 1] - d.gptr[x];
+        if (deg > 0) {
+            if (lane == 0) {
+                d.d_off[j] = d.gptr[x] | kAdjacencyFlag;
+                d.d_len[j] = (int)deg;
+                d.d_start[j] = 0;
+            }
+            start = deg;
+            ++j;
+        }
+        long long guard = d.dir_cap / 4;
+        for (int32_t b = d.head[x]; b >= 0 && guard > 0; --guard) {
+            const int32_t* blk = d.dir + (long long)b * 4;
+            const int c = blk[1];                       // at most kDirMaxCap = 32 descriptors
+            long long off = 0;
+            int len = 0;
+            if (lane < c) {
+                const int32_t* w = blk + kDirHeader + 3 * lane;
+                off = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
+                len = w[2];
+            }
+            long long incl = len;
+#pragma unroll
+            for (int o = 1; o < 32; o <<= 1) {
+                const long long y = __shfl_up(incl, o);
+                if (lane >= o) incl += y;
+            }
+            if (lane < c) {
+                d.d_off[j + lane] = off;
+                d.d_len[j + lane] = len;
+                d.d_start[j + lane] = start + incl - len;
+            }
+            start += blk[3];
+            j += c;
+            b = blk[0];
+        }
+    }
 }
 
-// Round step 2a: one wavefront (a block of 64 threads) decides one small slot.  The weights towards
-// the neighbouring communities are summed in a hash table in LDS.
-__global__ __launch_bounds__(64) void decide_small_kernel(DS d) {
+// Round step 2 (blocks of 256 threads).  The first kSlots blocks decide one small slot each: the
+// weights towards the neighbouring communities are summed in a hash table in LDS, and the block
+// finds the best and the runner-up.  The other blocks walk the edge records of the larger slots,
+// kUnit per block: summed per community in the same kind of table first (late in the procedure
+// most records of a hub lead to a few large communities), then added to the slot's weight array
+// over all vertices; the communities met for the first time go to the slot's candidate list.
+__global__ __launch_bounds__(256) void decide_round_kernel(DS d) {
     __shared__ int32_t hkey[kHashSize];
     __shared__ uint32_t hval[kHashSize];
-    const int i = blockIdx.x, lane = threadIdx.x;
-    if (i >= d.ctl->n_eval || d.s_class[i] != kClassSmall) return;
-    const int32_t v = d.s_v[i];
-    for (int e = lane; e < kHashSize; e += 64) { hkey[e] = -1; hval[e] = 0; }
-    __syncthreads();
+    __shared__ long long sh_s[4], sh_second[4];
+    __shared__ int32_t sh_r[4];
+    __shared__ int count_sh, dirty_sh;
+    __shared__ long long sd_off[kSmallRecords];
+    __shared__ int sd_len[kSmallRecords], sd_start[kSmallRecords + 1];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    int32_t self = -1;
     auto add = [&](int32_t to, uint32_t w) {
         const int32_t r = find_root(d.up, to);
-        if (r == v) return;
+        if (r == self) return;
         uint32_t h = ((uint32_t)r * 2654435761u) >> 22;   // 10 bits
         for (int probe = 0; probe < kHashSize; ++probe) {
             const int32_t k = atomicCAS(&hkey[h], -1, r);
@@ -322,63 +357,91 @@ __global__ __launch_bounds__(64) void decide_small_kernel(DS d) {
             h = (h + 1) & (kHashSize - 1);
         }
     };
-    const long long gb = d.gptr[v], ge = d.gptr[v + 1];
-    for (long long p = gb + lane; p < ge; p += 64) add(d.gadj[p], 1u);
-    int guard = 0;
-    for (int32_t b = d.head[v]; b >= 0 && guard <= d.blk_cap; b = d.blk_next[b], ++guard) {
-        const int c = d.blk_count[b];
-        for (int e = 0; e < c; ++e) {
-            const Rec* list = d.arena + d.blk_off[(long long)b * kDescPerBlock + e];
-            const int len = d.blk_len[(long long)b * kDescPerBlock + e];
-            for (int q = lane; q < len; q += 64) add(list[q].to, list[q].w);
+    if (blockIdx.x < kSlots) {
+        const int i = blockIdx.x;
+        if (i >= d.ctl->n_eval || d.s_class[i] != kClassSmall) return;
+        const int32_t v = d.s_v[i];
+        self = v;
+        for (int e = t; e < kHashSize; e += 256) { hkey[e] = -1; hval[e] = 0; }
+        if (t == 0) { count_sh = 0; dirty_sh = 0; }
+        __syncthreads();
+        const long long gb = d.gptr[v], ge = d.gptr[v + 1];
+        for (long long p = gb + t; p < ge; p += 256) add(d.gadj[p], 1u);
+        // chunks: their descriptors are staged in LDS (a small slot has at most kSmallRecords of them),
+        // then every thread takes records of the concatenated lists
+        int nd = 0;
+        long long guard = d.dir_cap / 4;
+        for (int32_t b = d.head[v]; b >= 0 && guard > 0 && nd + kDirMaxCap <= kSmallRecords + kDirMaxCap; --guard) {
+            const int32_t* blk = d.dir + (long long)b * 4;
+            const int c = blk[1];
+            if (t < c && nd + t < kSmallRecords) {
+                const int32_t* w = blk + kDirHeader + 3 * t;
+                sd_off[nd + t] = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
+                sd_len[nd + t] = w[2];
+            }
+            nd += c;
+            b = blk[0];
         }
-    }
-    __syncthreads();
-    const long long dv = d.dsum[v];
-    Best best{kNoScore, kNoScore, -1};
-    int count = 0;
-    bool dirty = false;
-    Rec* const out = d.scand + (long long)i * kSmallRecords;
-    for (int e0 = 0; e0 < kHashSize; e0 += 64) {
-        const int32_t r = hkey[e0 + lane];
-        const bool have = r >= 0;
-        const uint32_t w = hval[e0 + lane];
-        if (have) {
+        if (nd > kSmallRecords) nd = kSmallRecords;
+        __syncthreads();
+        if (t == 0) {
+            int acc = 0;
+            for (int e = 0; e < nd; ++e) { sd_start[e] = acc; acc += sd_len[e]; }
+            sd_start[nd] = acc;
+        }
+        __syncthreads();
+        const int chunk_records = sd_start[nd];
+        for (int q = t; q < chunk_records; q += 256) {
+            int lo = 0, hi = nd - 1;          // last chunk that starts at or before q
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (sd_start[mid] <= q) lo = mid; else hi = mid - 1;
+            }
+            const Rec r = d.arena[sd_off[lo] + (q - sd_start[lo])];
+            add(r.to, r.w);
+        }
+        __syncthreads();
+        const long long dv = d.dsum[v];
+        Best best{kNoScore, kNoScore, -1};
+        Rec* const out = d.scand + (long long)i * kSmallRecords;
+        for (int e = t; e < kHashSize; e += 256) {
+            const int32_t r = hkey[e];
+            if (r < 0) continue;
+            const uint32_t w = hval[e];
             best_add(best, (long long)w * d.two_m - d.dsum[r] * dv, r);
             const int j = d.slot_of[r];
-            if (j >= 0) { atomicOr(&d.bits[(long long)i * kRowWords + (j >> 5)], 1u << (j & 31)); dirty = true; }
+            if (j >= 0) { atomicOr(&d.bits[(long long)i * kRowWords + (j >> 5)], 1u << (j & 31)); dirty_sh = 1; }
+            out[atomicAdd(&count_sh, 1)] = Rec{r, w};
         }
-        const unsigned long long m = __ballot(have);
-        if (have) out[count + __popcll(m & ((1ull << lane) - 1ull))] = Rec{r, w};
-        count += __popcll(m);
+        best = best_wave_reduce(best);
+        if (lane == 0) { sh_s[wave] = best.s; sh_second[wave] = best.second; sh_r[wave] = best.r; }
+        __syncthreads();
+        if (t == 0) {
+            Best all{sh_s[0], sh_second[0], sh_r[0]};
+            for (int w2 = 1; w2 < 4; ++w2) best_join(all, Best{sh_s[w2], sh_second[w2], sh_r[w2]});
+            if (dirty_sh) d.row_dirty[i] = 1;
+            d.s_nt[i] = count_sh;
+            d.s_best[i] = all.r;
+            d.s_score[i] = all.s;
+            d.s_second[i] = all.second;
+            d.s_dv[i] = dv;
+        }
+        return;
     }
-    best = best_wave_reduce(best);
-    if (__ballot(dirty) && lane == 0) d.row_dirty[i] = 1;
-    if (lane == 0) {
-        d.s_nt[i] = count;
-        d.s_best[i] = best.r;
-        d.s_score[i] = best.s;
-        d.s_second[i] = best.second;
-        d.s_dv[i] = dv;
-    }
-}
-
-// Round step 2b: the edge records of the larger slots, kUnit per block, summed into the slot's
-// weight array over all vertices; the communities met for the first time are appended to the
-// slot's candidate list.
-__global__ __launch_bounds__(256) void accumulate_large_kernel(DS d) {
     const int n_units = d.ctl->n_units;
-    for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+    for (int u = blockIdx.x - kSlots; u < n_units; u += gridDim.x - kSlots) {
         const int i = d.unit_slot[u];
         const int k = u - d.s_unit0[i];
-        const int32_t v = d.s_v[i];
+        self = d.s_v[i];
         const int nrec = d.s_nrec[i];
         const long long dbase = d.s_desc_off[i];
         const int nd = d.s_ndesc[i];
         uint32_t* const weight = d.dense + (long long)d.s_dense[i] * d.M;
         Rec* const cand = d.cand + d.s_cand_off[i];
         const int p_end = (k + 1) * kUnit < nrec ? (k + 1) * kUnit : nrec;
-        for (int p = k * kUnit + (int)threadIdx.x; p < p_end; p += 256) {
+        for (int e = t; e < kHashSize; e += 256) { hkey[e] = -1; hval[e] = 0; }
+        __syncthreads();
+        for (int p = k * kUnit + t; p < p_end; p += 256) {
             int lo = 0, hi = nd - 1;          // last descriptor that starts at or before p
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
@@ -386,14 +449,16 @@ __global__ __launch_bounds__(256) void accumulate_large_kernel(DS d) {
             }
             const long long q = p - d.d_start[dbase + lo];
             const long long off = d.d_off[dbase + lo];
-            int32_t to;
-            uint32_t w;
-            if (off & kAdjacencyFlag) { to = d.gadj[(off & ~kAdjacencyFlag) + q]; w = 1u; }
-            else { const Rec r = d.arena[off + q]; to = r.to; w = r.w; }
-            const int32_t r = find_root(d.up, to);
-            if (r == v) continue;
-            if (atomicAdd(&weight[r], w) == 0u) cand[atomicAdd(&d.s_nt[i], 1)].to = r;
+            if (off & kAdjacencyFlag) add(d.gadj[(off & ~kAdjacencyFlag) + q], 1u);
+            else { const Rec r = d.arena[off + q]; add(r.to, r.w); }
         }
+        __syncthreads();
+        for (int e = t; e < kHashSize; e += 256) {
+            const int32_t r = hkey[e];
+            if (r < 0) continue;
+            if (atomicAdd(&weight[r], hval[e]) == 0u) cand[atomicAdd(&d.s_nt[i], 1)].to = r;
+        }
+        __syncthreads();
     }
 }
 
@@ -439,39 +504,49 @@ __global__ __launch_bounds__(256) void score_large_kernel(DS d) {
     }
 }
 
-// ascending bitonic sort of 2048 keys in LDS by 1024 threads
-__device__ __forceinline__ void bitonic_sort_2048(unsigned long long* key) {
+// ascending bitonic sort of the first n2 keys (a power of two, at most 2048) in LDS
+template <int T>
+__device__ __forceinline__ void bitonic_sort_lds(unsigned long long* key, int n2) {
     const int t = threadIdx.x;
-    for (int size = 2; size <= kSlots; size <<= 1) {
+    for (int size = 2; size <= n2; size <<= 1) {
         for (int stride = size >> 1; stride > 0; stride >>= 1) {
             __syncthreads();
-            const int lo = ((t & ~(stride - 1)) << 1) | (t & (stride - 1));
-            const int hi = lo + stride;
-            const bool up = (lo & size) == 0;
-            const unsigned long long a = key[lo], b = key[hi];
-            if ((a > b) == up) { key[lo] = b; key[hi] = a; }
+            for (int c = t; c < (n2 >> 1); c += T) {
+                const int lo = ((c & ~(stride - 1)) << 1) | (c & (stride - 1));
+                const int hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const unsigned long long a = key[lo], b = key[hi];
+                if ((a > b) == up) { key[lo] = b; key[hi] = a; }
+            }
         }
     }
     __syncthreads();
 }
 
-// inclusive sums of val inside runs (a run starts where head is set); 2048 positions, two per thread
-__device__ __forceinline__ void segmented_scan_2048(long long* val, uint8_t* flag, const uint8_t* head) {
+// inclusive sums of val inside runs (a run starts where head is set) over the first n2 positions
+template <int T>
+__device__ __forceinline__ void segmented_scan_lds(long long* val, uint8_t* flag, const uint8_t* head, int n2) {
+    constexpr int kPer = kSlots / T;
     const int t = threadIdx.x;
-    for (int k = 0; k < 2; ++k) flag[t + k * 1024] = head[t + k * 1024];
+    for (int p = t; p < n2; p += T) flag[p] = head[p];
     __syncthreads();
-    for (int o = 1; o < kSlots; o <<= 1) {
-        long long add[2];
-        uint8_t f[2];
-        for (int k = 0; k < 2; ++k) {
-            const int p = t + k * 1024;
+    for (int o = 1; o < n2; o <<= 1) {
+        long long add[kPer];
+        uint8_t f[kPer];
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int p = t + k * T;
             add[k] = 0;
+            f[k] = 0;
+            if (p >= n2) continue;
             f[k] = flag[p];
             if (p >= o && !flag[p]) { add[k] = val[p - o]; f[k] = flag[p - o]; }
         }
         __syncthreads();
-        for (int k = 0; k < 2; ++k) {
-            const int p = t + k * 1024;
+#pragma unroll
+        for (int k = 0; k < kPer; ++k) {
+            const int p = t + k * T;
+            if (p >= n2) continue;
             val[p] += add[k];
             flag[p] = f[k];
         }
@@ -479,29 +554,101 @@ __device__ __forceinline__ void segmented_scan_2048(long long* val, uint8_t* fla
     }
 }
 
-// Round step 3 (one block of 1024 threads): which slots stand, and the commit of those.
-__global__ __launch_bounds__(1024) void commit_round_kernel(DS d) {
+template <int T>
+__device__ __forceinline__ long long block_sum_commit(long long x, long long* sh16) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) x += __shfl_xor(x, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh16[threadIdx.x >> 6] = x;
+    __syncthreads();
+    long long all = 0;
+#pragma unroll
+    for (int w = 0; w < T / 64; ++w) all += sh16[w];
+    return all;
+}
+
+constexpr int kQuadratic = 128;   // rounds of at most this many slots compare all pairs of slots instead of sorting
+
+// Directory words that appending one more chunk to `target` takes: a new block where the target has
+// none or its newest one is full.
+__device__ __forceinline__ int dir_words_for_append(const DS& d, int32_t target) {
+    const int32_t b = d.head[target];
+    const int32_t* blk = b >= 0 ? d.dir + (long long)b * 4 : nullptr;
+    if (blk && blk[1] < blk[2]) return 0;
+    int cap = blk ? 2 * blk[2] : kDirFirstCap;
+    if (cap > kDirMaxCap) cap = kDirMaxCap;
+    return kDirHeader + 3 * cap;
+}
+
+// Takes `total` records of the arena as a new chunk of `target` and lists it in the target's
+// directory; returns the chunk's offset.  One thread per target and round calls this, after the
+// round's needs were checked against the pools.
+__device__ __forceinline__ long long append_chunk(const DS& d, int32_t target, long long total) {
+    Ctl* const ctl = d.ctl;
+    const long long base = (long long)atomicAdd((unsigned long long*)&ctl->arena_used, (unsigned long long)total);
+    int32_t b = d.head[target];
+    int32_t* blk = b >= 0 ? d.dir + (long long)b * 4 : nullptr;
+    if (!blk || blk[1] == blk[2]) {
+        int cap = blk ? 2 * blk[2] : kDirFirstCap;
+        if (cap > kDirMaxCap) cap = kDirMaxCap;
+        const long long at = (long long)atomicAdd((unsigned long long*)&ctl->dir_used, (unsigned long long)(kDirHeader + 3 * cap));
+        int32_t* nb = d.dir + at;
+        nb[0] = b;
+        nb[1] = 0;
+        nb[2] = cap;
+        nb[3] = 0;
+        d.head[target] = (int32_t)(at >> 2);
+        blk = nb;
+    }
+    const int c = blk[1];
+    int32_t* w = blk + kDirHeader + 3 * c;
+    w[0] = (int32_t)(uint32_t)(base & 0xffffffffll);
+    w[1] = (int32_t)(base >> 32);
+    w[2] = (int32_t)total;
+    blk[1] = c + 1;
+    blk[3] += (int32_t)total;
+    d.tot_rec[target] += (int32_t)total;
+    d.tot_desc[target] += 1;
+    return base;
+}
+
+// Round step 3 (one block of T threads): which slots stand, and the commit of those.
+//
+// Merging slots are grouped by target, in slot order inside a group: the degree that earlier slots
+// of the round add to a slot's target is a prefix sum inside its group (test (c)), and the lists
+// that the committed slots of a group keep form one chunk, each list at its prefix offset.  Rounds of
+// more than kQuadratic slots sort (target, slot) keys and scan the sorted runs.  Smaller rounds, the
+// great majority, let every slot look at the slots before it directly, with a handful of barriers
+// instead of a hundred.
+template <int T>
+__global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
+    constexpr int kPer = kSlots / T;
     __shared__ unsigned long long key[kSlots];
     __shared__ long long val[kSlots];
-    __shared__ long long aux[kSlots];            // reductions (first 1024 entries), then the runs' arena offsets
+    __shared__ long long run_base[kSlots];       // arena offset of a group's chunk, at the group's first position
+    __shared__ long long sh16[16];
     __shared__ uint32_t mmask[kRowWords];
     __shared__ uint8_t inv[kSlots], head[kSlots], flag[kSlots];
-    __shared__ int16_t pos_of_slot[kSlots], hpos[kSlots];   // sorted position of a slot; first position of a position's run
+    __shared__ int16_t pos_of_slot[kSlots], hpos[kSlots];
+    __shared__ int32_t tg[kQuadratic], want[kQuadratic];
     __shared__ int cut_sh, overflow_sh;
-    long long* const red = aux;
-    long long* const run_base = aux;
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     Ctl* const ctl = d.ctl;
     const int n_prepared = ctl->n_prepared, n_eval = ctl->n_eval;
     if (n_prepared == 0) return;
+    const long long pos = ctl->pos;
+    const bool direct = n_eval <= kQuadratic;
+    int n2 = 64;
+    while (n2 < n_eval) n2 <<= 1;
     if (t < kRowWords) mmask[t] = 0;
     if (t == 0) { cut_sh = n_eval; overflow_sh = 0; }
+    for (int i = t; i < n2; i += T) inv[i] = 0;
     __syncthreads();
     // results of the larger slots from their blocks' partial results; who merges
-    for (int k = 0; k < 2; ++k) {
-        const int i = t + k * 1024;
-        inv[i] = 0;
+    for (int i = t; i < n2; i += T) {
         key[i] = ~0ull;
+        val[i] = 0;
+        if (i < kQuadratic) { tg[i] = -1; want[i] = 0; }
         if (i >= n_eval) continue;
         if (d.s_class[i] == kClassLarge) {
             Best all{kNoScore, kNoScore, -1};
@@ -512,21 +659,29 @@ __global__ __launch_bounds__(1024) void commit_round_kernel(DS d) {
             d.s_second[i] = all.second;
             d.s_dv[i] = d.dsum[d.s_v[i]];
         }
-        if (d.s_best[i] >= 0 && d.s_score[i] > 0) {
+        const int32_t best = d.s_best[i];
+        if (best >= 0 && d.s_score[i] > 0) {
             atomicOr(&mmask[i >> 5], 1u << (i & 31));
-            key[i] = ((unsigned long long)(uint32_t)d.s_best[i] << 11) | (unsigned long long)i;
+            key[i] = ((unsigned long long)(uint32_t)best << 11) | (unsigned long long)i;
+            val[i] = d.s_dv[i];
+            if (direct) {
+                tg[i] = best;
+                want[i] = (long long)d.idx[best] > pos + i ? d.s_nt[i] : 0;   // the list is kept if the target's turn is ahead
+                const int s = d.slot_of[best];
+                if (s > i && s < n_eval) inv[s] = 1;                          // (b), see below
+            }
         }
     }
     __syncthreads();
     // (b) an earlier slot merges into this slot's vertex
-    for (int k = 0; k < 2; ++k) {
-        const int j = t + k * 1024;
-        if (j >= n_eval || key[j] == ~0ull) continue;
-        const int s = d.slot_of[d.s_best[j]];
-        if (s > j && s < n_eval) inv[s] = 1;
-    }
+    if (!direct)
+        for (int j = t; j < n_eval; j += T) {
+            if (key[j] == ~0ull) continue;
+            const int s = d.slot_of[d.s_best[j]];
+            if (s > j && s < n_eval) inv[s] = 1;
+        }
     // (a) a candidate community is the vertex of an earlier slot that merges
-    for (int i = wave; i < n_eval; i += 16) {
+    for (int i = wave; i < n_eval; i += T / 64) {
         if (!d.row_dirty[i]) continue;
         const uint32_t word = d.bits[(long long)i * kRowWords + lane];
         const uint32_t below = lane < (i >> 5) ? 0xffffffffu : (lane == (i >> 5) ? ((1u << (i & 31)) - 1u) : 0u);
@@ -534,145 +689,168 @@ __global__ __launch_bounds__(1024) void commit_round_kernel(DS d) {
         d.bits[(long long)i * kRowWords + lane] = 0u;
         if (lane == 0) d.row_dirty[i] = 0;
     }
-    // (c) degree that earlier slots add to the chosen community: merging slots sorted by (target, slot)
-    bitonic_sort_2048(key);
-    for (int k = 0; k < 2; ++k) {
-        const int p = t + k * 1024;
-        const unsigned long long kk = key[p];
-        head[p] = p == 0 || (kk >> 11) != (key[p - 1] >> 11);
-        val[p] = kk == ~0ull ? 0 : d.s_dv[(int)(kk & (kSlots - 1))];
-        if (kk != ~0ull) pos_of_slot[(int)(kk & (kSlots - 1))] = (int16_t)p;
-    }
-    __syncthreads();
-    // first position of every position's run: running maximum of the head positions
-    for (int k = 0; k < 2; ++k) { const int p = t + k * 1024; hpos[p] = head[p] ? (int16_t)p : (int16_t)0; }
-    __syncthreads();
-    for (int o = 1; o < kSlots; o <<= 1) {
-        int16_t m[2];
-        for (int k = 0; k < 2; ++k) { const int p = t + k * 1024; m[k] = p >= o && hpos[p - o] > hpos[p] ? hpos[p - o] : hpos[p]; }
-        __syncthreads();
-        for (int k = 0; k < 2; ++k) hpos[t + k * 1024] = m[k];
-        __syncthreads();
-    }
-    segmented_scan_2048(val, flag, head);
-    for (int k = 0; k < 2; ++k) {
-        const int p = t + k * 1024;
-        const unsigned long long kk = key[p];
-        if (kk == ~0ull) continue;
-        const int i = (int)(kk & (kSlots - 1));
-        const long long dv = d.s_dv[i];
-        const long long before = val[p] - dv;      // degree added to the target by earlier slots
-        if (before > 0) {
-            const long long adjusted = d.s_score[i] - before * dv;
-            if (!(adjusted > 0 && adjusted > d.s_second[i])) inv[i] = 1;
-        }
-    }
-    __syncthreads();
-    for (int k = 0; k < 2; ++k) {
-        const int i = t + k * 1024;
-        if (i < n_eval && inv[i]) atomicMin(&cut_sh, i);
-    }
-    __syncthreads();
-    int cut = cut_sh;
-    // edge lists to keep: those of committed merges whose target has its turn still ahead
-    __syncthreads();
-    long long my_store = 0, my_runs = 0;
-    for (int k = 0; k < 2; ++k) {
-        const int p = t + k * 1024;
-        const unsigned long long kk = key[p];
-        long long len = 0;
-        if (kk != ~0ull) {
-            const int i = (int)(kk & (kSlots - 1));
-            const int32_t target = (int32_t)(kk >> 11);
-            if (i < cut && d.idx[target] > d.idx[d.s_v[i]]) len = d.s_nt[i];
-        }
-        val[p] = len;
-        my_store += len;
-        my_runs += (kk != ~0ull && head[p]) ? 1 : 0;
-    }
-    red[t] = my_store;
-    __syncthreads();
-    for (int o = 512; o > 0; o >>= 1) { if (t < o) red[t] += red[t + o]; __syncthreads(); }
-    const long long total_store = red[0];
-    __syncthreads();
-    red[t] = my_runs;
-    __syncthreads();
-    for (int o = 512; o > 0; o >>= 1) { if (t < o) red[t] += red[t + o]; __syncthreads(); }
-    const long long total_runs = red[0];
-    __syncthreads();
-    if (t == 0 && (ctl->arena_used + total_store > d.arena_cap || (long long)ctl->blk_used + total_runs > (long long)d.blk_cap))
-        overflow_sh = 1;
-    __syncthreads();
-    if (overflow_sh) cut = 0;          // nothing is committed; the host gives up on this form
-    if (!overflow_sh) {
-        segmented_scan_2048(val, flag, head);
-        // the last position of a run knows the run's total: it takes the arena space and links the chunk
-        for (int k = 0; k < 2; ++k) {
-            const int p = t + k * 1024;
-            const unsigned long long kk = key[p];
-            if (kk == ~0ull) continue;
-            const bool last = p == kSlots - 1 || key[p + 1] == ~0ull || (key[p + 1] >> 11) != (kk >> 11);
-            if (!last) continue;
-            const long long total = val[p];
-            const int hp = hpos[p];
-            long long base = -1;
-            if (total > 0) {
-                const int32_t target = (int32_t)(kk >> 11);
-                base = (long long)atomicAdd((unsigned long long*)&ctl->arena_used, (unsigned long long)total);
-                int32_t b = d.head[target];
-                if (b < 0 || d.blk_count[b] == kDescPerBlock) {
-                    const int32_t nb = atomicAdd(&ctl->blk_used, 1);
-                    d.blk_next[nb] = b;
-                    d.blk_count[nb] = 0;
-                    d.head[target] = nb;
-                    b = nb;
-                }
-                const int c = d.blk_count[b];
-                d.blk_off[(long long)b * kDescPerBlock + c] = base;
-                d.blk_len[(long long)b * kDescPerBlock + c] = (int32_t)total;
-                d.blk_count[b] = c + 1;
+    long long work_round = 0;
+    int cut;
+    if (direct) {
+        // ---- small round: slot i looks at the slots before it
+        long long offset_in_chunk = 0;     // records that earlier slots of the group keep
+        int first = -1;                    // the group's first slot
+        int32_t my_tg = -1;
+        if (t < n_eval && (my_tg = tg[t]) >= 0) {
+            long long before = 0;
+            first = t;
+#pragma unroll 8
+            for (int j = 0; j < t; ++j) {
+                const bool same = tg[j] == my_tg;
+                before += same ? val[j] : 0;
+                offset_in_chunk += same ? want[j] : 0;
+                first = same && j < first ? j : first;
             }
-            run_base[hp] = base;
+            if (before > 0) {   // (c)
+                const long long adjusted = d.s_score[t] - before * val[t];
+                if (!(adjusted > 0 && adjusted > d.s_second[t])) inv[t] = 1;
+            }
         }
+        __syncthreads();
+        if (t < n_eval && inv[t]) atomicMin(&cut_sh, t);
+        __syncthreads();
+        cut = cut_sh;
+        // a group's first slot sums what the group's committed slots keep and takes the space
+        long long total = 0;
+        int words = 0;
+        const bool leader = my_tg >= 0 && first == t && t < cut;
+        if (leader) {
+            for (int j = t; j < cut; ++j) total += tg[j] == my_tg ? want[j] : 0;
+            if (total > 0) words = dir_words_for_append(d, my_tg);
+        }
+        const long long total_store = block_sum_commit<T>(total, sh16);
+        const long long total_words = block_sum_commit<T>(words, sh16);
+        if (t == 0 && (ctl->arena_used + total_store > d.arena_cap || ctl->dir_used + total_words > d.dir_cap)) overflow_sh = 1;
+        __syncthreads();
+        if (overflow_sh) cut = 0;
+        if (leader && total > 0 && !overflow_sh) run_base[t] = append_chunk(d, my_tg, total);
         __syncthreads();
         long long my_work = 0;
-        for (int k = 0; k < 2; ++k) {
-            const int i = t + k * 1024;
-            if (i >= cut) continue;
-            my_work += d.s_nrec[i] + 1;
-            if (!(d.s_best[i] >= 0 && d.s_score[i] > 0)) continue;
-            const int32_t v = d.s_v[i], target = d.s_best[i];
-            d.parent[v] = target;
-            d.up[v] = target;
-            atomicAdd((unsigned long long*)&d.dsum[target], (unsigned long long)d.s_dv[i]);
-            const int p = pos_of_slot[i];
-            const int hp = hpos[p];
-            const long long len = d.idx[target] > d.idx[v] ? (long long)d.s_nt[i] : 0;
-            if (len > 0) {
-                d.s_store[i] = 1;
-                d.s_chunk_off[i] = run_base[hp] + (val[p] - len);
+        if (t < cut) {
+            my_work = d.s_nrec[t] + 1;
+            if (my_tg >= 0) {
+                const int32_t v = d.s_v[t];
+                d.parent[v] = my_tg;
+                d.up[v] = my_tg;
+                atomicAdd((unsigned long long*)&d.dsum[my_tg], (unsigned long long)val[t]);
+                if (want[t] > 0) {
+                    d.s_store[t] = 1;
+                    d.s_chunk_off[t] = run_base[first] + offset_in_chunk;
+                }
             }
         }
-        __syncthreads();               // run_base has been read; its memory now holds the work sum
-        red[t] = my_work;
+        work_round = block_sum_commit<T>(my_work, sh16);
+    } else {
+        // ---- large round: merging slots sorted by (target, slot)
+        bitonic_sort_lds<T>(key, n2);
+        for (int p = t; p < n2; p += T) {
+            const unsigned long long kk = key[p];
+            head[p] = p == 0 || (kk >> 11) != (key[p - 1] >> 11);
+            val[p] = kk == ~0ull ? 0 : d.s_dv[(int)(kk & (kSlots - 1))];
+            if (kk != ~0ull) pos_of_slot[(int)(kk & (kSlots - 1))] = (int16_t)p;
+        }
         __syncthreads();
-        for (int o = 512; o > 0; o >>= 1) { if (t < o) red[t] += red[t + o]; __syncthreads(); }
+        // first position of every position's run: running maximum of the head positions
+        for (int p = t; p < n2; p += T) hpos[p] = head[p] ? (int16_t)p : (int16_t)0;
+        __syncthreads();
+        for (int o = 1; o < n2; o <<= 1) {
+            int16_t m[kPer];
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) {
+                const int p = t + k * T;
+                m[k] = 0;
+                if (p < n2) m[k] = p >= o && hpos[p - o] > hpos[p] ? hpos[p - o] : hpos[p];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int k = 0; k < kPer; ++k) if (t + k * T < n2) hpos[t + k * T] = m[k];
+            __syncthreads();
+        }
+        segmented_scan_lds<T>(val, flag, head, n2);
+        for (int p = t; p < n2; p += T) {     // (c)
+            const unsigned long long kk = key[p];
+            if (kk == ~0ull) continue;
+            const int i = (int)(kk & (kSlots - 1));
+            const long long dv = d.s_dv[i];
+            const long long before = val[p] - dv;      // degree added to the target by earlier slots
+            if (before > 0) {
+                const long long adjusted = d.s_score[i] - before * dv;
+                if (!(adjusted > 0 && adjusted > d.s_second[i])) inv[i] = 1;
+            }
+        }
+        __syncthreads();
+        for (int i = t; i < n_eval; i += T)
+            if (inv[i]) atomicMin(&cut_sh, i);
+        __syncthreads();
+        cut = cut_sh;
+        // lists to keep: those of committed merges whose target has its turn still ahead; val becomes the
+        // list's length and then the inclusive prefix of the lengths inside the run
+        long long my_store = 0;
+        for (int p = t; p < n2; p += T) {
+            const unsigned long long kk = key[p];
+            long long len = 0;
+            if (kk != ~0ull) {
+                const int i = (int)(kk & (kSlots - 1));
+                if (i < cut && (long long)d.idx[(int32_t)(kk >> 11)] > pos + i) len = d.s_nt[i];
+            }
+            val[p] = len;
+            my_store += len;
+        }
+        const long long total_store = block_sum_commit<T>(my_store, sh16);
+        segmented_scan_lds<T>(val, flag, head, n2);
+        // a run's last position holds the run's total: it takes the arena space and links the chunk
+        auto last_of_run = [&](int p) { return p == n2 - 1 || key[p + 1] == ~0ull || (key[p + 1] >> 11) != (key[p] >> 11); };
+        long long my_words = 0;
+        for (int p = t; p < n2; p += T) {
+            const unsigned long long kk = key[p];
+            if (kk == ~0ull || val[p] == 0 || !last_of_run(p)) continue;
+            my_words += dir_words_for_append(d, (int32_t)(kk >> 11));
+        }
+        const long long total_words = block_sum_commit<T>(my_words, sh16);
+        if (t == 0 && (ctl->arena_used + total_store > d.arena_cap || ctl->dir_used + total_words > d.dir_cap)) overflow_sh = 1;
+        __syncthreads();
+        if (overflow_sh) cut = 0;          // nothing is committed; the host gives up on this form
+        if (!overflow_sh) {
+            for (int p = t; p < n2; p += T) {
+                const unsigned long long kk = key[p];
+                if (kk == ~0ull || val[p] == 0 || !last_of_run(p)) continue;
+                run_base[hpos[p]] = append_chunk(d, (int32_t)(kk >> 11), val[p]);
+            }
+            __syncthreads();
+            long long my_work = 0;
+            for (int i = t; i < cut; i += T) {
+                my_work += d.s_nrec[i] + 1;
+                if (!(d.s_best[i] >= 0 && d.s_score[i] > 0)) continue;
+                const int32_t v = d.s_v[i], target = d.s_best[i];
+                d.parent[v] = target;
+                d.up[v] = target;
+                atomicAdd((unsigned long long*)&d.dsum[target], (unsigned long long)d.s_dv[i]);
+                const int p = pos_of_slot[i];
+                const long long len = (long long)d.idx[target] > pos + i ? (long long)d.s_nt[i] : 0;
+                if (len > 0) {
+                    d.s_store[i] = 1;
+                    d.s_chunk_off[i] = run_base[hpos[p]] + (val[p] - len);
+                }
+            }
+            work_round = block_sum_commit<T>(my_work, sh16);
+        }
     }
     // the round's vertices leave the slot table
-    for (int k = 0; k < 2; ++k) {
-        const int i = t + k * 1024;
-        if (i < n_prepared) d.slot_of[d.s_v[i]] = -1;
-    }
+    for (int i = t; i < n_prepared; i += T) d.slot_of[d.s_v[i]] = -1;
     if (t == 0) {
         ctl->last_cut = cut;
         ctl->rounds += 1;
         if (overflow_sh) {
             ctl->overflow = 1;
         } else {
-            const long long work_round = red[0];
-            if (ctl->pos + cut == d.M && cut > 0) ctl->work_at_last = ctl->work + work_round - (d.s_nrec[cut - 1] + 1);
+            if (pos + cut == d.M && cut > 0) ctl->work_at_last = ctl->work + work_round - (d.s_nrec[cut - 1] + 1);
             ctl->work += work_round;
-            ctl->pos += cut;
+            ctl->pos = pos + cut;
             const int P = ctl->P;
             int next = cut == n_prepared ? 2 * P : 2 * cut + 16;
             if (next < 32) next = 32;
@@ -720,9 +898,10 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     if (two_m >= ((int64_t)1 << 31)) return kDendrogramUseHost;
 
     Scratch tmp;
-    DevBuf<int32_t> d_order, d_idx, d_parent, d_up, d_head, d_slot_of;
+    DevBuf<int32_t> d_order, d_idx, d_parent, d_up, d_head, d_slot_of, d_tot_rec, d_tot_desc;
     DevBuf<long long> d_dsum;
     d_order.alloc(M); d_idx.alloc(M); d_parent.alloc(M); d_up.alloc(M); d_head.alloc(M); d_slot_of.alloc(M);
+    d_tot_rec.alloc(M); d_tot_desc.alloc(M);
     d_dsum.alloc(M);
     {   // visiting order: stable sort of the ids by degree
         DevBuf<uint32_t> key, key_sorted;
@@ -736,23 +915,22 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     }
     hipLaunchKernelGGL(init_state_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, 0, (long long)M,
                        reinterpret_cast<const long long*>(g.ptr.p), d_order.p, d_idx.p, d_parent.p, d_up.p, d_dsum.p,
-                       d_head.p, d_slot_of.p);
+                       d_head.p, d_slot_of.p, d_tot_rec.p, d_tot_desc.p);
     ACC_HIP(hipGetLastError());
 
     // memory pools
-    const int64_t blk_cap = M + 16;
+    const int64_t dir_cap = 24 * M + 4096;   // words: a first block per vertex (16 words) and room for the larger ones
     const int64_t arena_cap = 3 * two_m + M + 1024;
     const int64_t cand_cap = two_m + 1024;
     const int64_t desc_cap = M + 16;
     const int64_t unit_cap = two_m / kUnit + kSlots + 16;
     const int n_dense = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxDense, ((int64_t)4 << 30) / (4 * M)));
-    DevBuf<int32_t> blk_next, blk_count, blk_len, d_len, unit_slot, u_best, row_dirty, sI[11];
-    DevBuf<long long> blk_off, d_off, d_start, u_score, u_second, sL[5];
+    DevBuf<int32_t> dir, d_len, unit_slot, u_best, row_dirty, sI[11];
+    DevBuf<long long> d_off, d_start, u_score, u_second, sL[5];
     DevBuf<Rec> arena, scand, cand;
     DevBuf<uint32_t> bits, dense;
     DevBuf<Ctl> ctl;
-    blk_next.alloc(blk_cap); blk_count.alloc(blk_cap);
-    blk_off.alloc(blk_cap * kDescPerBlock); blk_len.alloc(blk_cap * kDescPerBlock);
+    dir.alloc(dir_cap);
     arena.alloc(arena_cap);
     scand.alloc((size_t)kSlots * kSmallRecords);
     cand.alloc(cand_cap);
@@ -775,7 +953,8 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     d.M = M; d.two_m = two_m;
     d.gptr = reinterpret_cast<const long long*>(g.ptr.p); d.gadj = g.adj.p; d.order = d_order.p; d.idx = d_idx.p;
     d.parent = d_parent.p; d.up = d_up.p; d.dsum = d_dsum.p; d.head = d_head.p;
-    d.blk_next = blk_next.p; d.blk_count = blk_count.p; d.blk_off = blk_off.p; d.blk_len = blk_len.p; d.blk_cap = (int32_t)blk_cap;
+    d.tot_rec = d_tot_rec.p; d.tot_desc = d_tot_desc.p;
+    d.dir = dir.p; d.dir_cap = dir_cap;
     d.arena = arena.p; d.arena_cap = arena_cap; d.ctl = ctl.p; d.slot_of = d_slot_of.p;
     d.s_v = sI[0].p; d.s_nrec = sI[1].p; d.s_class = sI[2].p; d.s_dense = sI[3].p; d.s_desc_off = sI[4].p; d.s_ndesc = sI[5].p;
     d.s_unit0 = sI[6].p; d.s_nunits = sI[7].p; d.s_nt = sI[8].p; d.s_best = sI[9].p; d.s_store = sI[10].p;
@@ -792,12 +971,13 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     int status = -1;
     const int64_t max_groups = 4 * M + 64;     // every round advances by at least one vertex
     for (int64_t gi = 0; gi < max_groups && status < 0; ++gi) {
+        const bool wide = h.P > kQuadratic;   // the commit kernel's block size follows the last round size seen
         for (int r = 0; r < group; ++r) {
             hipLaunchKernelGGL(prepare_round_kernel, dim3(1), dim3(1024), 0, 0, d);
-            hipLaunchKernelGGL(decide_small_kernel, dim3(kSlots), dim3(64), 0, 0, d);
-            hipLaunchKernelGGL(accumulate_large_kernel, dim3(kLargeBlocks), dim3(256), 0, 0, d);
+            hipLaunchKernelGGL(decide_round_kernel, dim3(kSlots + kLargeBlocks), dim3(256), 0, 0, d);
             hipLaunchKernelGGL(score_large_kernel, dim3(kLargeBlocks), dim3(256), 0, 0, d);
-            hipLaunchKernelGGL(commit_round_kernel, dim3(1), dim3(1024), 0, 0, d);
+            if (wide) hipLaunchKernelGGL(commit_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, d);
+            else hipLaunchKernelGGL(commit_round_kernel<256>, dim3(1), dim3(256), 0, 0, d);
             hipLaunchKernelGGL(keep_lists_kernel, dim3(kSlots / 4 + kLargeBlocks), dim3(256), 0, 0, d);
         }
         hipLaunchKernelGGL(compress_paths_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, 0, (long long)M, d_up.p);

@@ -70,10 +70,11 @@ typedef struct {
      * device's wave slots (12 per compute unit), between 32 and 1024
      * (acc_spmm_stats.max_tiles_per_item reports it). */
     int32_t max_tiles_per_item;
-    /* Tile geometry: rows per row window and condensed columns per tile.  0 = default
-     * (16,16), the geometry the execute kernel runs.  (8,8), the paper's geometry
-     * (Section 3.3), is accepted for building and exporting the format only:
-     * acc_spmm_execute returns ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
+    /* Tile geometry: rows per row window (8, 16, 32 or 64) and condensed columns per tile (8, 16
+     * or 32).  0 = default (16,16), the geometry the execute kernel runs.  The others, among them
+     * the paper's (8,8) (Section 3.3), are accepted for building, exporting and measuring the
+     * format only (acc_spmm_plan_stats, acc_spmm_plan_traffic): acc_spmm_execute returns
+     * ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
     int32_t window_height;
     int32_t tile_width;
     /* Leaves per segment in the ordering step's candidate search.  0 = default 1024; at

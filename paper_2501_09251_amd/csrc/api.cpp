@@ -255,8 +255,11 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
         fail(ACC_SPMM_ERR_INVALID_ARG, "reorder / load_balance must be OFF, ON or AUTO");
     if (opt.window_height == 0) opt.window_height = 16;
     if (opt.tile_width == 0) opt.tile_width = 16;
-    if (!((opt.window_height == 16 && opt.tile_width == 16) || (opt.window_height == 8 && opt.tile_width == 8)))
-        fail(ACC_SPMM_ERR_UNSUPPORTED, "tile geometry must be 16x16 or 8x8");
+    {
+        const int32_t wh = opt.window_height, tw = opt.tile_width;
+        const bool ok = (wh == 8 || wh == 16 || wh == 32 || wh == 64) && (tw == 8 || tw == 16 || tw == 32);
+        if (!ok) fail(ACC_SPMM_ERR_UNSUPPORTED, "window_height must be 8, 16, 32 or 64 and tile_width 8, 16 or 32");
+    }
     if (opt.max_tiles_per_item < 0) fail(ACC_SPMM_ERR_INVALID_ARG, "max_tiles_per_item must not be negative");
     if (opt.segment_length == 0) opt.segment_length = kDefaultSegLen;
     if (opt.segment_length < 1) fail(ACC_SPMM_ERR_INVALID_ARG, "segment_length must be positive");

@@ -66,6 +66,7 @@ struct Ctl {                 // round control, lives in device memory
     int last_cut;            // slots the last commit kept
     int overflow;            // a memory pool was exhausted: nothing more is committed
     long long dir_used;      // words of the directory pool in use
+    long long large_slots;   // larger slots prepared so far (the host sizes the prepare kernel's block by their rate)
 };
 
 struct DS {
@@ -179,8 +180,9 @@ __global__ void compress_paths_kernel(long long M, int32_t* up) {
     if (i < M) up[i] = find_root(up, (int32_t)i);
 }
 
-// exclusive prefix sum over the block's 1024 threads; `total` gets the sum (sh: 16 entries)
-__device__ __forceinline__ long long block_scan_1024(long long x, long long* sh, long long& total) {
+// exclusive prefix sum over the block's T threads; `total` gets the sum (sh: 16 entries)
+template <int T>
+__device__ __forceinline__ long long block_scan(long long x, long long* sh, long long& total) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     long long incl = x;
 #pragma unroll
@@ -192,7 +194,7 @@ __device__ __forceinline__ long long block_scan_1024(long long x, long long* sh,
     __syncthreads();
     long long before = 0, all = 0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) {
+    for (int w = 0; w < T / 64; ++w) {
         const long long y = sh[w];
         if (w < wave) before += y;
         all += y;
@@ -202,18 +204,20 @@ __device__ __forceinline__ long long block_scan_1024(long long x, long long* sh,
     return before + incl - x;
 }
 
-// Round step 1 (one block of 1024 threads, two consecutive slots per thread): the round's vertices,
+// Round step 1 (one block of T threads, two consecutive slots per thread; a round has at most 2 T
+// slots, so the small block serves the small rounds that make up most of the procedure): the round's vertices,
 // the size of their edge lists, and, in slot order, the memory the larger slots need; then, one
 // wavefront per larger slot, the slot's descriptors (its adjacency and its chunks, with their first
 // record's position in the slot's list) and its work units.
-__global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
+template <int T>
+__global__ __launch_bounds__(T) void prepare_round_kernel(DS d) {
     __shared__ long long sh[16];
     __shared__ int first_unfit, n_large;
     __shared__ int large_list[kMaxDense];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     Ctl* const ctl = d.ctl;
     const long long pos = ctl->pos;
-    const int P = ctl->P;
+    const int P = ctl->P < 2 * T ? ctl->P : 2 * T;
     const int n = (int)(d.M - pos < (long long)P ? d.M - pos : (long long)P);
     if (t == 0) { first_unfit = n; n_large = 0; }
     int v[2], nrec[2], ndesc[2], cls[2];
@@ -244,7 +248,7 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
     long long pre[4][2], tot[4];
     for (int what = 0; what < 4; ++what) {
         const long long a = need(0, what), b = need(1, what);
-        const long long ex = block_scan_1024(a + b, sh, tot[what]);
+        const long long ex = block_scan<T>(a + b, sh, tot[what]);
         pre[what][0] = ex;
         pre[what][1] = ex + a;
     }
@@ -279,14 +283,15 @@ __global__ __launch_bounds__(1024) void prepare_round_kernel(DS d) {
         large_list[atomicAdd(&n_large, 1)] = i;
     }
     long long all_units;
-    (void)block_scan_1024(units_total, sh, all_units);
+    (void)block_scan<T>(units_total, sh, all_units);
     if (t == 0) {
         ctl->n_prepared = n;
         ctl->n_eval = n_eval;
         ctl->n_units = (int)all_units;
+        ctl->large_slots += n_large;
     }
     // descriptors and units of the larger slots, one wavefront per slot
-    for (int q = wave; q < n_large; q += 16) {
+    for (int q = wave; q < n_large; q += T / 64) {
         const int i = large_list[q];
         const int32_t x = d.s_v[i];
         const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
@@ -642,7 +647,7 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     while (n2 < n_eval) n2 <<= 1;
     if (t < kRowWords) mmask[t] = 0;
     if (t == 0) { cut_sh = n_eval; overflow_sh = 0; }
-    for (int i = t; i < n2; i += T) inv[i] = 0;
+    for (int i = t; i < n2; i += T) { inv[i] = 0; flag[i] = i < n_eval ? (uint8_t)d.row_dirty[i] : (uint8_t)0; }
     __syncthreads();
     // results of the larger slots from their blocks' partial results; who merges
     for (int i = t; i < n2; i += T) {
@@ -682,7 +687,7 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
         }
     // (a) a candidate community is the vertex of an earlier slot that merges
     for (int i = wave; i < n_eval; i += T / 64) {
-        if (!d.row_dirty[i]) continue;
+        if (!flag[i]) continue;
         const uint32_t word = d.bits[(long long)i * kRowWords + lane];
         const uint32_t below = lane < (i >> 5) ? 0xffffffffu : (lane == (i >> 5) ? ((1u << (i & 31)) - 1u) : 0u);
         if (__ballot((word & mmask[lane] & below) != 0u) && lane == 0) inv[i] = 1;
@@ -969,11 +974,20 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     // Rounds are enqueued in groups without waiting; the control block is read back after each group.
     int group = 4;
     int status = -1;
+    long long large_before = 0, rounds_before = 0, pos_before = 0;
+    constexpr double kMaxRemainingRounds = 300000.0;   // some twenty seconds of rounds
     const int64_t max_groups = 4 * M + 64;     // every round advances by at least one vertex
     for (int64_t gi = 0; gi < max_groups && status < 0; ++gi) {
-        const bool wide = h.P > kQuadratic;   // the commit kernel's block size follows the last round size seen
+        // block sizes follow what the last group of rounds looked like: large rounds sort in the commit
+        // kernel, and rounds with larger slots write their descriptors one wavefront per slot
+        const bool wide = h.P > kQuadratic;
+        const bool wide_prepare = wide || h.large_slots - large_before >= h.rounds - rounds_before;
+        large_before = h.large_slots;
+        rounds_before = h.rounds;
+        pos_before = h.pos;
         for (int r = 0; r < group; ++r) {
-            hipLaunchKernelGGL(prepare_round_kernel, dim3(1), dim3(1024), 0, 0, d);
+            if (wide_prepare) hipLaunchKernelGGL(prepare_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, d);
+            else hipLaunchKernelGGL(prepare_round_kernel<256>, dim3(1), dim3(256), 0, 0, d);
             hipLaunchKernelGGL(decide_round_kernel, dim3(kSlots + kLargeBlocks), dim3(256), 0, 0, d);
             hipLaunchKernelGGL(score_large_kernel, dim3(kLargeBlocks), dim3(256), 0, 0, d);
             if (wide) hipLaunchKernelGGL(commit_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, d);
@@ -987,7 +1001,12 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
         else if (h.pos >= M) {
             status = (work_limit > 0 && h.work_at_last > work_limit) ? kDendrogramOverBudget : kDendrogramDone;
         } else if (work_limit > 0 && h.work > work_limit) status = kDendrogramOverBudget;
-        else if (h.rounds >= 65536 && h.pos / h.rounds < 4 && (M - h.pos) > 262144) status = kDendrogramUseHost;   // crawling
+        else if (h.rounds >= 1024) {
+            // crawling: at the rate of the last group the rest would take more rounds than the host form
+            // needs time for (chains of vertices that each depend on the one before, as in banded matrices)
+            const double rate = (double)(h.pos - pos_before) / (double)std::max<long long>(1, h.rounds - rounds_before);
+            if ((double)(M - h.pos) / std::max(rate, 1e-3) > kMaxRemainingRounds) status = kDendrogramUseHost;
+        }
         if (group < 64) group *= 2;
     }
     if (status < 0) status = kDendrogramUseHost;

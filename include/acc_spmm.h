@@ -131,6 +131,12 @@ typedef struct {
      * comparison).  The library switches to the host form by itself when the input does not suit the
      * device form (acc_spmm_stats.dendrogram_on_device tells which one ran). */
     int32_t dendrogram_on_host;
+    /* Comparison switch: 1 stages the gathered rows of B through a double buffer in LDS, as the
+     * paper's Algorithm 2 does (global memory -> LDS for tile k+1 while tile k is multiplied), instead
+     * of the register ring, which measured as fast or faster everywhere and is the default.  Same
+     * result bit for bit.  fp16 plans, N = 32, 64, 128 or 384; other calls return
+     * ACC_SPMM_ERR_UNSUPPORTED. */
+    int32_t lds_staging;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */

@@ -52,6 +52,7 @@ class acc_spmm_options(ctypes.Structure):
         ("operand_order", ctypes.c_int32),
         ("keep_entry_map", ctypes.c_int32),
         ("dendrogram_on_host", ctypes.c_int32),
+        ("lds_staging", ctypes.c_int32),
     ]
 
 

@@ -28,6 +28,7 @@ struct ExecParams {
     bool coop;         // cooperative value fetch
     bool tail;         // N is not a whole number of slabs
     bool bf16;         // values are bfloat16
+    bool lds;          // B rows staged through an LDS double buffer instead of the register ring
     int32_t fpl, ns, grid_y, depth, store_mode;
 };
 

@@ -312,6 +312,13 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
     p.store_mode = (plan.opt.streaming_stores != 0 ? kStoreStreaming : 0) | (narrow_c ? kStoreNarrow : 0);
     p.bf16 = plan.opt.value_type == ACC_SPMM_BF16;
+    p.lds = plan.opt.lds_staging != 0;
+    if (p.lds) {
+        // the comparison form exists for whole slabs of at least two features per lane, one slab per wave
+        if (p.fpl < 2 || p.ns != 1 || p.tail || p.bf16 || plan.opt.no_prefetch)
+            fail(ACC_SPMM_ERR_UNSUPPORTED, "lds_staging runs fp16 plans at N = 32, 64 or an odd multiple of 128 up to 384, with prefetch");
+        p.depth = 1;   // a double buffer: one tile ahead
+    }
     if (timed) ACC_HIP(hipEventRecord(ev[0], stream));
     if (p.n_items > 0) {
         switch (p.fpl * 2 + (p.bf16 ? 1 : 0)) {

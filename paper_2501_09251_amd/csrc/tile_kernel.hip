@@ -26,6 +26,11 @@
 // values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
 // words of tile t+DEPTH+1 are requested one step before they are needed for addresses.
 //
+// LDS = true is the staging that the paper's Algorithm 2 describes, for comparison: the B rows of the
+// next tile go from global memory straight into LDS (global_load_lds, no registers in between) while
+// the current tile, read back from the other LDS buffer, is multiplied: a double buffer, one tile
+// ahead.  The register ring above measured as fast or faster on every workload and stays the default.
+//
 // This file is compiled once per (features per lane, value type): ACC_TILE_FPL in {1, 2, 4, 8}
 // and ACC_TILE_BF16 in {0, 1} come from the command line, so that the many instantiations
 // build in parallel.
@@ -129,7 +134,7 @@ struct TileData {       // what the multiply needs
 // load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
 // BF16 = true: the 16-bit values of A and B are bfloat16 instead of IEEE half; only the MFMA
 // instruction differs, the data movement is the same.
-template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16>
+template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16, bool LDS = false>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
@@ -138,6 +143,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     int32_t store_mode) {
     constexpr int R = DEPTH + 1;
     constexpr int SW = 16 * FPL;  // features per slab
+    static_assert(!LDS || (DEPTH == 1 && NS == 1 && !TAIL && FPL >= 2), "LDS staging: double buffer, whole slabs, dword lanes");
+    // LDS staging: per wave and ring slot, four planes (one per B row of the lane group) of 64 lanes x
+    // DW dwords, each dword column a plane of its own when a lane holds fewer than four (the load
+    // instruction places lane l's data at l times its size)
+    constexpr int DW = Chunk<FPL>::DW;
+    __shared__ uint32_t stage[LDS ? kWavesPerBlock * R * 4 * DW * 64 : 1];
+    uint32_t* const stage_wave = stage + (LDS ? (threadIdx.x >> 6) * (R * 4 * DW * 64) : 0);
     struct {
         const int32_t* __restrict__ rwo; const int32_t* __restrict__ tco; const int32_t* __restrict__ a2b;
         const uint64_t* __restrict__ bits; const uint16_t* __restrict__ vals; const int32_t* __restrict__ perm_pad;
@@ -259,10 +271,30 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const uint64_t hot_base = reinterpret_cast<uint64_t>(g_Bhot) + (uint64_t)f0 * 2;
     const uint64_t cold_base = reinterpret_cast<uint64_t>(p.B) + (uint64_t)f0 * 2;
     const uint32_t row_bytes = (uint32_t)N * 2u;
-    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d) __attribute__((always_inline)) {
+    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if constexpr (ADDR == kAddrNarrow) {
+            if constexpr (LDS) {
+                // the lane's address as in the register form; the data lands in LDS
+                uint64_t row;
+                if constexpr (ADDR == kAddrNarrow) {
+                    row = cold_base + (uint64_t)((__umul24((uint32_t)m.cols[q], (uint32_t)N)) << 1);
+                } else {
+                    const int32_t e = m.cols[q];
+                    const bool hot = ADDR == kAddrHot && e < 0;
+                    row = (uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes + (hot ? hot_base : cold_base);
+                }
+                uint32_t* const plane = stage_wave + (slot * 4 + q) * DW * 64;
+                if constexpr (FPL == 8) {
+                    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(row),
+                                                     (__attribute__((address_space(3))) void*)(plane), 16, 0, 0);
+                } else {
+#pragma unroll
+                    for (int k = 0; k < DW; ++k)
+                        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(row + 4u * k),
+                                                         (__attribute__((address_space(3))) void*)(plane + k * 64), 4, 0, 0);
+                }
+            } else if constexpr (ADDR == kAddrNarrow) {
                 const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
                 const uint16_t* row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
 #pragma unroll
@@ -327,6 +359,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             d.nchunk = 0;
         }
         d.nib = nib;
+    };
+
+    // LDS staging: the B rows of the tile in ring slot `slot`, which the wait above this call has
+    // seen arrive, from LDS into the registers the multiply reads
+    auto fetch_staged = [&](TileData<FPL, NS>& d, int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t* plane = stage_wave + (slot * 4 + q) * DW * 64;
+            if constexpr (FPL == 8) {
+                const uintx4 v = *reinterpret_cast<const uintx4*>(plane + lane * 4);
+                d.b[0][q].d[0] = v.x; d.b[0][q].d[1] = v.y; d.b[0][q].d[2] = v.z; d.b[0][q].d[3] = v.w;
+            } else {
+#pragma unroll
+                for (int k = 0; k < DW; ++k) d.b[0][q].d[k] = plane[k * 64 + lane];
+            }
+        }
     };
 
     // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
@@ -429,7 +477,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         TileData<FPL, NS> d;
         for (int tt = tb; tt < te; ++tt) {
             load_meta(tt, m);
-            issue(m, d);
+            issue(m, d, 0);
             multiply(d, operand_a(d));
             after_tile(tt);
         }
@@ -445,7 +493,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         for (int r = 0; r < R; ++r) load_meta(tb + r, meta[r]);
 #pragma unroll
         for (int r = 0; r < DEPTH; ++r) {
-            issue(meta[r], data[r]);
+            issue(meta[r], data[r], r);
             load_meta(tb + R + r, meta[r]);
         }
         for (int t = tb; t < te; t += R) {
@@ -455,10 +503,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 if (tt >= te) break;
                 // tile tt's sparse operand first: its cross-lane fetch (if any) shares a wait counter
                 // with the scalar index loads issued next
+                if constexpr (LDS) {
+                    // everything requested so far (this tile's rows among it) has arrived; the next
+                    // tile's requests follow only after the read-back, so they stay in flight during
+                    // the multiply.  vmcnt(0), other counters untouched.
+                    __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    fetch_staged(data[r], r);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 const uintx2 au = operand_a(data[r]);
                 if constexpr (COOP) __builtin_amdgcn_sched_barrier(0);
                 const int s = (r + DEPTH) % R;            // slot of tile tt+DEPTH
-                issue(meta[s], data[s]);
+                issue(meta[s], data[s], s);
                 load_meta(tt + 2 * DEPTH + 1, meta[s]);   // the slot's next tile
                 multiply(data[r], au);
                 after_tile(tt);
@@ -471,6 +528,14 @@ template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16>
 void launch_one(const ExecParams& p, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
     dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
+    if constexpr (DEPTH == 1 && NS == 1 && !TAIL && !BF16 && FPL >= 2) {
+        if (p.lds) {
+            hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16, true>), grid, block, 0, stream, p.rwo,
+                               p.tco, p.a2b, p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items,
+                               p.n_blocks, p.N, p.store_mode);
+            return;
+        }
+    }
     hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
                        p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items, p.n_blocks, p.N,
                        p.store_mode);

@@ -157,6 +157,40 @@ def test_every_kernel_variant(N):
                 np.testing.assert_array_equal(C, ref)      # same summation order in every variant
 
 
+@pytest.mark.parametrize("N", [32, 64, 128, 384])
+def test_lds_staging_gives_the_same_result(N):
+    """The comparison form of the tile kernel (B rows through an LDS double buffer, as the paper's
+    Algorithm 2 stages them) against the oracle and, bit for bit, against the default form; both value
+    fetches, split windows, with and without a column order (the two-matrix addressing)."""
+    w = wl.config(5, 9)
+    B = wl.dense(w.K, N, 78, "normal", 0.0, 1.0)
+    for column_order in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON):
+        ref = None
+        for lds, fetch in ((0, 1), (1, 1), (1, 2)):
+            opt = acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16, value_fetch=fetch,
+                                   lds_staging=lds, column_order=column_order)
+            plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+            try:
+                assert acc.acc_spmm_plan_stats(plan)["num_split_windows"] > 0
+                C = run_spmm(plan, B, w.M, N)
+            finally:
+                acc.acc_spmm_destroy(plan)
+            if ref is None:
+                ref = C
+                check_against_oracle(w.rowptr, w.colidx, w.vals, B, C)
+            else:
+                np.testing.assert_array_equal(C, ref)
+    # widths the comparison form does not cover are refused, not silently run another way
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(lds_staging=1))
+    try:
+        for bad_N in (16, 100, 256):
+            with pytest.raises(acc.AccSpmmError) as e:
+                run_spmm(plan, wl.dense(w.K, bad_N, 1, "normal", 0.0, 1.0), w.M, bad_N)
+            assert e.value.code == -3
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 @pytest.mark.parametrize("fetch", [0, 1, 2])
 @pytest.mark.parametrize("N", [16, 64, 128, 512])
 def test_dense_tiles_at_odd_value_offsets(fetch, N):

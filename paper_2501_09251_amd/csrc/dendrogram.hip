@@ -18,7 +18,9 @@
 // The first slot of a round always stands, so every round advances.  Everything before the first
 // slot that fails is committed (its decision equals the sequential one by induction), the rest is
 // decided again in the next round.  (c) may fail a slot whose decision would in fact have stood;
-// that costs a round, never the result.
+// that costs a round, never the result.  (Re-examining such slots exactly, every candidate's score
+// with the degree the earlier slots add to it, was tried: 6 % fewer rounds on a 2^23-vertex R-MAT
+// graph, but the re-examination cost more than the rounds it saved.)
 //
 // A community's edge list, as of its vertex's turn, is its own adjacency plus the lists of the
 // vertices merged into it (each a list of (community, weight) pairs as of that vertex's turn);

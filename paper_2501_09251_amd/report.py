@@ -26,6 +26,10 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--shrink", type=int, default=0)
     ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--plan-only", action="store_true",
+                    help="build one plan with the row reordering forced on and print its statistics and phase times "
+                         "(for profiling the preprocessing kernels); nothing is executed")
+    ap.add_argument("--dendrogram-on-host", action="store_true", help="with --plan-only: the host form of Step I")
     args = ap.parse_args()
 
     import torch
@@ -35,6 +39,17 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("report: no GPU visible", file=sys.stderr)
         return 2
+    if args.plan_only:
+        w = wl.config(args.config, args.shrink, with_B=False)
+        plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                    acc.make_options(reorder=acc.ACC_SPMM_ON, dendrogram_on_host=int(args.dendrogram_on_host)))
+        st = acc.acc_spmm_plan_stats(plan)
+        acc.acc_spmm_destroy(plan)
+        print(json.dumps({"report": "plan", "workload": w.name, **{k: st[k] for k in (
+            "t_total_s", "t_validate_s", "t_reorder_s", "t_graph_s", "t_dendrogram_s", "t_ordering_s", "t_column_order_s",
+            "t_encode_s", "t_schedule_s", "dendrogram_on_device", "dendrogram_rounds", "reorder_work_ratio", "num_tiles",
+            "num_tiles_identity")}}), flush=True)
+        return 0
     w = wl.config(args.config, args.shrink)
     dev = torch.device("cuda:0")
     B = torch.from_numpy(w.B.view(np.int16)).to(dev)

@@ -785,6 +785,30 @@ def test_paper_geometry_8x8_format_and_closed_form_size():
         acc.acc_spmm_destroy(plan)
 
 
+@pytest.mark.parametrize("WH,TW", [(16, 32), (32, 16), (64, 16), (32, 32), (8, 16)])
+def test_other_tile_geometries_build_the_oracles_format(WH, TW):
+    """Window heights and tile widths the execute kernel does not run: the five arrays still equal
+    the oracle's encoding of the same geometry byte for byte, the statistics count that format, and
+    execute refuses the plan."""
+    w = wl.config(2, 7)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals,
+                                acc.make_options(window_height=WH, tile_width=TW, reorder=acc.ACC_SPMM_ON))
+    try:
+        perm, fmt = check_format(plan, w.rowptr, w.colidx, w.vals, WH, TW)
+        st = acc.acc_spmm_plan_stats(plan)
+        T = len(fmt["tc_offset"]) - 1
+        assert st["num_tiles"] == T and st["window_height"] == WH and st["tile_width"] == TW
+        words = -(-WH * TW // 64)
+        assert st["index_bytes"] == 4 * (-(-w.M // WH) + 1) + 4 * (T + 1) + 4 * T * TW + 8 * T * words
+        tr = acc.acc_spmm_plan_traffic(plan, 128)
+        assert tr["b_bytes"] == st["sum_distinct_cols"] * 128 * 2 and tr["mfma_flops"] == 2 * T * WH * TW * 128
+        with pytest.raises(acc.AccSpmmError) as e:
+            run_spmm(plan, w.B, w.M, w.N)
+        assert e.value.code == -3
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 def test_execute_argument_errors():
     rowptr, colidx, vals = csr_from_rows([[0]])
     plan = acc.acc_spmm_plan(1, 1, 1, rowptr, colidx, vals)

@@ -44,9 +44,10 @@ constexpr int kMaxDense = 64;         // larger slots per round (each owns a wei
 // A target's chunks are listed in directory blocks inside one pool of 32-bit words.  A block is
 // {next block or -1, descriptors in use, capacity, records in its chunks} followed by `capacity`
 // descriptors of three words (chunk offset low, high, length).  A target's first block holds 4
-// descriptors, each further one twice as many up to 32, and the newest block heads the chain.
+// descriptors, each further one twice as many up to 1024 (a hub collects thousands of chunks; its
+// chain stays a dozen blocks long), and the newest block heads the chain.
 // Blocks are referred to by their word offset divided by 4 (all block sizes are multiples of 4).
-constexpr int kDirHeader = 4, kDirFirstCap = 4, kDirMaxCap = 32;
+constexpr int kDirHeader = 4, kDirFirstCap = 4, kDirMaxCap = 1024;
 constexpr long long kAdjacencyFlag = 1ll << 62;
 
 constexpr int kClassNone = 0, kClassSmall = 1, kClassLarge = 2, kClassSkipped = 3;
@@ -68,6 +69,7 @@ struct Ctl {                 // round control, lives in device memory
     int last_cut;            // slots the last commit kept
     int overflow;            // a memory pool was exhausted: nothing more is committed
     long long dir_used;      // words of the directory pool in use
+    int keep_units, pad;     // units of the round whose kept lists are still to be copied
     long long large_slots;   // larger slots prepared so far (the host sizes the prepare kernel's block by their rate)
 };
 
@@ -212,7 +214,7 @@ __device__ __forceinline__ long long block_scan(long long x, long long* sh, long
 // wavefront per larger slot, the slot's descriptors (its adjacency and its chunks, with their first
 // record's position in the slot's list) and its work units.
 template <int T>
-__global__ __launch_bounds__(T) void prepare_round_kernel(DS d) {
+__device__ __forceinline__ void prepare_round(const DS& d) {
     __shared__ long long sh[16];
     __shared__ int first_unfit, n_large;
     __shared__ int large_list[kMaxDense];
@@ -312,24 +314,29 @@ __global__ __launch_bounds__(T) void prepare_round_kernel(DS d) {
         long long guard = d.dir_cap / 4;
         for (int32_t b = d.head[x]; b >= 0 && guard > 0; --guard) {
             const int32_t* blk = d.dir + (long long)b * 4;
-            const int c = blk[1];                       // at most kDirMaxCap = 32 descriptors
-            long long off = 0;
-            int len = 0;
-            if (lane < c) {
-                const int32_t* w = blk + kDirHeader + 3 * lane;
-                off = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
-                len = w[2];
-            }
-            long long incl = len;
+            const int c = blk[1];
+            long long at = start;                       // first record of the descriptors handled so far
+            for (int e0 = 0; e0 < c; e0 += 64) {        // sixty-four descriptors per step
+                const int e = e0 + lane;
+                long long off = 0;
+                int len = 0;
+                if (e < c) {
+                    const int32_t* w = blk + kDirHeader + 3 * e;
+                    off = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
+                    len = w[2];
+                }
+                long long incl = len;
 #pragma unroll
-            for (int o = 1; o < 32; o <<= 1) {
-                const long long y = __shfl_up(incl, o);
-                if (lane >= o) incl += y;
-            }
-            if (lane < c) {
-                d.d_off[j + lane] = off;
-                d.d_len[j + lane] = len;
-                d.d_start[j + lane] = start + incl - len;
+                for (int o = 1; o < 64; o <<= 1) {
+                    const long long y = __shfl_up(incl, o);
+                    if (lane >= o) incl += y;
+                }
+                if (e < c) {
+                    d.d_off[j + e] = off;
+                    d.d_len[j + e] = len;
+                    d.d_start[j + e] = at + incl - len;
+                }
+                at += __shfl(incl, 63);
             }
             start += blk[3];
             j += c;
@@ -378,13 +385,13 @@ __global__ __launch_bounds__(256) void decide_round_kernel(DS d) {
         // then every thread takes records of the concatenated lists
         int nd = 0;
         long long guard = d.dir_cap / 4;
-        for (int32_t b = d.head[v]; b >= 0 && guard > 0 && nd + kDirMaxCap <= kSmallRecords + kDirMaxCap; --guard) {
+        for (int32_t b = d.head[v]; b >= 0 && guard > 0 && nd <= kSmallRecords; --guard) {
             const int32_t* blk = d.dir + (long long)b * 4;
             const int c = blk[1];
-            if (t < c && nd + t < kSmallRecords) {
-                const int32_t* w = blk + kDirHeader + 3 * t;
-                sd_off[nd + t] = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
-                sd_len[nd + t] = w[2];
+            for (int e = t; e < c && nd + e < kSmallRecords; e += 256) {
+                const int32_t* w = blk + kDirHeader + 3 * e;
+                sd_off[nd + e] = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
+                sd_len[nd + e] = w[2];
             }
             nd += c;
             b = blk[0];
@@ -851,6 +858,7 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     for (int i = t; i < n_prepared; i += T) d.slot_of[d.s_v[i]] = -1;
     if (t == 0) {
         ctl->last_cut = cut;
+        ctl->keep_units = ctl->n_units;
         ctl->rounds += 1;
         if (overflow_sh) {
             ctl->overflow = 1;
@@ -867,20 +875,23 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     }
 }
 
-// Round step 4: the kept edge lists go from the round's scratch memory to their chunks.
-__global__ __launch_bounds__(256) void keep_lists_kernel(DS d) {
+// Round step 4: the kept edge lists go from the round's scratch memory to their chunks.  Runs in the
+// blocks after the first of the next round's prepare launch (kKeepBlocks blocks of any size): the
+// per-slot arrays and the unit table exist twice and alternate between rounds, so the next round's
+// preparation does not overwrite what this reads.
+constexpr int kKeepBlocks = 256;
+__device__ __forceinline__ void keep_lists(const DS& d, int b, int nthreads) {
     const int cut = d.ctl->last_cut;
-    if (blockIdx.x < kSlots / 4) {                 // small slots, one wavefront each
-        const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-        if (i >= cut || !d.s_store[i] || d.s_class[i] != kClassSmall) return;
+    const int waves = nthreads / 64, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int i = b * waves + wave; i < cut; i += kKeepBlocks * waves) {      // small slots, one wavefront each
+        if (!d.s_store[i] || d.s_class[i] != kClassSmall) continue;
         const Rec* src = d.scand + (long long)i * kSmallRecords;
         Rec* dst = d.arena + d.s_chunk_off[i];
         const int nt = d.s_nt[i];
         for (int j = lane; j < nt; j += 64) dst[j] = src[j];
-        return;
     }
-    const int n_units = d.ctl->n_units;
-    for (int u = blockIdx.x - kSlots / 4; u < n_units; u += gridDim.x - kSlots / 4) {
+    const int n_units = d.ctl->keep_units;
+    for (int u = b; u < n_units; u += kKeepBlocks) {
         const int i = d.unit_slot[u];
         if (i >= cut || !d.s_store[i]) continue;
         const int k = u - d.s_unit0[i];
@@ -888,8 +899,14 @@ __global__ __launch_bounds__(256) void keep_lists_kernel(DS d) {
         const Rec* src = d.cand + d.s_cand_off[i];
         Rec* dst = d.arena + d.s_chunk_off[i];
         const int j_end = (k + 1) * kUnit < nt ? (k + 1) * kUnit : nt;
-        for (int j = k * kUnit + (int)threadIdx.x; j < j_end; j += 256) dst[j] = src[j];
+        for (int j = k * kUnit + (int)threadIdx.x; j < j_end; j += nthreads) dst[j] = src[j];
     }
+}
+
+template <int T>
+__global__ __launch_bounds__(T) void prepare_and_keep_kernel(DS cur, DS prev) {
+    if (blockIdx.x == 0) prepare_round<T>(cur);
+    else keep_lists(prev, (int)blockIdx.x - 1, T);
 }
 
 }  // namespace
@@ -926,7 +943,9 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     ACC_HIP(hipGetLastError());
 
     // memory pools
-    const int64_t dir_cap = 24 * M + 4096;   // words: a first block per vertex (16 words) and room for the larger ones
+    // words: a first block per target (16 words); every further block doubles, so a target's blocks hold
+    // at most twice its chunks (3 words each) plus headers; targets and chunks are at most M each
+    const int64_t dir_cap = 28 * M + 8192;
     const int64_t arena_cap = 3 * two_m + M + 1024;
     const int64_t cand_cap = two_m + 1024;
     const int64_t desc_cap = M + 16;
@@ -942,12 +961,12 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     scand.alloc((size_t)kSlots * kSmallRecords);
     cand.alloc(cand_cap);
     d_off.alloc(desc_cap); d_len.alloc(desc_cap); d_start.alloc(desc_cap);
-    unit_slot.alloc(unit_cap); u_best.alloc(unit_cap); u_score.alloc(unit_cap); u_second.alloc(unit_cap);
+    unit_slot.alloc(2 * unit_cap); u_best.alloc(unit_cap); u_score.alloc(unit_cap); u_second.alloc(unit_cap);
     bits.alloc((size_t)kSlots * kRowWords);
     row_dirty.alloc(kSlots);
     dense.alloc((size_t)n_dense * (size_t)M);
-    for (auto& b : sI) b.alloc(kSlots);
-    for (auto& b : sL) b.alloc(kSlots);
+    for (auto& b : sI) b.alloc(2 * kSlots);      // two sets, alternating between rounds
+    for (auto& b : sL) b.alloc(2 * kSlots);
     ctl.alloc(1);
     ACC_HIP(hipMemset(bits.p, 0, sizeof(uint32_t) * kSlots * kRowWords));
     ACC_HIP(hipMemset(row_dirty.p, 0, sizeof(int32_t) * kSlots));
@@ -971,30 +990,43 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     d.unit_slot = unit_slot.p; d.unit_cap = (int32_t)unit_cap; d.u_best = u_best.p; d.u_score = u_score.p; d.u_second = u_second.p;
     d.dense = dense.p; d.n_dense = n_dense;
 
+    // the second set of per-slot arrays and unit table
+    DS d_odd = d;
+    {
+        int32_t** ip[] = {&d_odd.s_v, &d_odd.s_nrec, &d_odd.s_class, &d_odd.s_dense, &d_odd.s_desc_off, &d_odd.s_ndesc,
+                          &d_odd.s_unit0, &d_odd.s_nunits, &d_odd.s_nt, &d_odd.s_best, &d_odd.s_store};
+        for (auto pp : ip) *pp += kSlots;
+        long long** lp[] = {&d_odd.s_cand_off, &d_odd.s_score, &d_odd.s_second, &d_odd.s_dv, &d_odd.s_chunk_off};
+        for (auto pp : lp) *pp += kSlots;
+        d_odd.unit_slot += unit_cap;
+    }
     const int64_t graph_size = two_m + M;
     const int64_t work_limit = work_budget > 0 ? (int64_t)(work_budget * (double)graph_size) : 0;
     // Rounds are enqueued in groups without waiting; the control block is read back after each group.
     int group = 4;
     int status = -1;
-    long long large_before = 0, rounds_before = 0, pos_before = 0;
+    long long large_before = 0, rounds_before = 0, pos_before = 0, launched = 0;
     constexpr double kMaxRemainingRounds = 300000.0;   // some twenty seconds of rounds
     const int64_t max_groups = 4 * M + 64;     // every round advances by at least one vertex
     for (int64_t gi = 0; gi < max_groups && status < 0; ++gi) {
         // block sizes follow what the last group of rounds looked like: large rounds sort in the commit
-        // kernel, and rounds with larger slots write their descriptors one wavefront per slot
+        // kernel, and rounds with larger slots write their descriptors one wavefront per slot (with the
+        // small block those rounds measured slower: 21.6 against 19.6 us per launch)
         const bool wide = h.P > kQuadratic;
         const bool wide_prepare = wide || h.large_slots - large_before >= h.rounds - rounds_before;
         large_before = h.large_slots;
         rounds_before = h.rounds;
         pos_before = h.pos;
-        for (int r = 0; r < group; ++r) {
-            if (wide_prepare) hipLaunchKernelGGL(prepare_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, d);
-            else hipLaunchKernelGGL(prepare_round_kernel<256>, dim3(1), dim3(256), 0, 0, d);
-            hipLaunchKernelGGL(decide_round_kernel, dim3(kSlots + kLargeBlocks), dim3(256), 0, 0, d);
-            hipLaunchKernelGGL(score_large_kernel, dim3(kLargeBlocks), dim3(256), 0, 0, d);
-            if (wide) hipLaunchKernelGGL(commit_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, d);
-            else hipLaunchKernelGGL(commit_round_kernel<256>, dim3(1), dim3(256), 0, 0, d);
-            hipLaunchKernelGGL(keep_lists_kernel, dim3(kSlots / 4 + kLargeBlocks), dim3(256), 0, 0, d);
+        for (int r = 0; r < group; ++r, ++launched) {
+            const DS& cur = (launched & 1) ? d_odd : d;
+            const DS& prev = (launched & 1) ? d : d_odd;
+            // this round's preparation, and beside it the copy of the lists the last round kept
+            if (wide_prepare) hipLaunchKernelGGL(prepare_and_keep_kernel<1024>, dim3(1 + kKeepBlocks), dim3(1024), 0, 0, cur, prev);
+            else hipLaunchKernelGGL(prepare_and_keep_kernel<256>, dim3(1 + kKeepBlocks), dim3(256), 0, 0, cur, prev);
+            hipLaunchKernelGGL(decide_round_kernel, dim3(kSlots + kLargeBlocks), dim3(256), 0, 0, cur);
+            hipLaunchKernelGGL(score_large_kernel, dim3(kLargeBlocks), dim3(256), 0, 0, cur);
+            if (wide) hipLaunchKernelGGL(commit_round_kernel<1024>, dim3(1), dim3(1024), 0, 0, cur);
+            else hipLaunchKernelGGL(commit_round_kernel<256>, dim3(1), dim3(256), 0, 0, cur);
         }
         hipLaunchKernelGGL(compress_paths_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, 0, (long long)M, d_up.p);
         ACC_HIP(hipGetLastError());

@@ -42,12 +42,15 @@ constexpr int kUnit = 512;            // edge records per thread block for large
 constexpr int kLargeBlocks = 2048;    // grid of the kernels that walk those units
 constexpr int kMaxDense = 64;         // larger slots per round (each owns a weight array over all vertices)
 // A target's chunks are listed in directory blocks inside one pool of 32-bit words.  A block is
-// {next block or -1, descriptors in use, capacity, records in its chunks} followed by `capacity`
-// descriptors of three words (chunk offset low, high, length).  A target's first block holds 4
+// {next block or -1, descriptors in use, capacity, position of its first chunk} followed by
+// `capacity` descriptors of four words (chunk offset low, high, length, position).  A chunk's
+// position is the number of records in the target's earlier chunks: the target's list is its
+// adjacency followed by its chunks in that order, and a record of it is found by walking to the
+// block and bisecting the block's positions, so nothing has to be laid out again per round.  A target's first block holds 4
 // descriptors, each further one twice as many up to 1024 (a hub collects thousands of chunks; its
 // chain stays a dozen blocks long), and the newest block heads the chain.
 // Blocks are referred to by their word offset divided by 4 (all block sizes are multiples of 4).
-constexpr int kDirHeader = 4, kDirFirstCap = 4, kDirMaxCap = 1024;
+constexpr int kDirHeader = 4, kDirDesc = 4, kDirFirstCap = 4, kDirMaxCap = 1024;
 constexpr long long kAdjacencyFlag = 1ll << 62;
 
 constexpr int kClassNone = 0, kClassSmall = 1, kClassLarge = 2, kClassSkipped = 3;
@@ -91,17 +94,13 @@ struct DS {
     long long arena_cap;
     Ctl* ctl;
     int32_t* slot_of;
-    int32_t *s_v, *s_nrec, *s_class, *s_dense, *s_desc_off, *s_ndesc, *s_unit0, *s_nunits, *s_nt, *s_best, *s_store;
+    int32_t *s_v, *s_nrec, *s_class, *s_dense, *s_unit0, *s_nunits, *s_nt, *s_best, *s_store;
     long long *s_cand_off, *s_score, *s_second, *s_dv, *s_chunk_off;
     uint32_t* bits;
     int32_t* row_dirty;
     Rec* scand;
     Rec* cand;
     long long cand_cap;
-    long long* d_off;
-    int32_t* d_len;
-    long long* d_start;
-    int32_t desc_cap;
     int32_t* unit_slot;
     int32_t unit_cap;
     int32_t* u_best;
@@ -211,8 +210,7 @@ __device__ __forceinline__ long long block_scan(long long x, long long* sh, long
 // Round step 1 (one block of T threads, two consecutive slots per thread; a round has at most 2 T
 // slots, so the small block serves the small rounds that make up most of the procedure): the round's vertices,
 // the size of their edge lists, and, in slot order, the memory the larger slots need; then, one
-// wavefront per larger slot, the slot's descriptors (its adjacency and its chunks, with their first
-// record's position in the slot's list) and its work units.
+// wavefront per larger slot, the slot's work units.
 template <int T>
 __device__ __forceinline__ void prepare_round(const DS& d) {
     __shared__ long long sh[16];
@@ -224,19 +222,17 @@ __device__ __forceinline__ void prepare_round(const DS& d) {
     const int P = ctl->P < 2 * T ? ctl->P : 2 * T;
     const int n = (int)(d.M - pos < (long long)P ? d.M - pos : (long long)P);
     if (t == 0) { first_unfit = n; n_large = 0; }
-    int v[2], nrec[2], ndesc[2], cls[2];
+    int v[2], nrec[2], cls[2];
     for (int k = 0; k < 2; ++k) {
         const int i = 2 * t + k;
-        v[k] = -1; nrec[k] = 0; ndesc[k] = 0; cls[k] = kClassNone;
+        v[k] = -1; nrec[k] = 0; cls[k] = kClassNone;
         if (i >= n) continue;
         const int32_t x = d.order[pos + i];
         v[k] = x;
         d.slot_of[x] = i;
         d.s_v[i] = x;
-        const long long deg = d.gptr[x + 1] - d.gptr[x];
-        const long long records = deg + d.tot_rec[x];
+        const long long records = d.gptr[x + 1] - d.gptr[x] + d.tot_rec[x];
         nrec[k] = (int)records;
-        ndesc[k] = (deg > 0 ? 1 : 0) + d.tot_desc[x];
         cls[k] = records <= kSmallRecords ? kClassSmall : kClassLarge;
     }
     // what the larger slots need, as exclusive prefix sums in slot order
@@ -245,28 +241,26 @@ __device__ __forceinline__ void prepare_round(const DS& d) {
         switch (what) {
             case 0: return 1;
             case 1: return nrec[k];
-            case 2: return ndesc[k];
             default: return (nrec[k] + kUnit - 1) / kUnit;
         }
     };
-    long long pre[4][2], tot[4];
-    for (int what = 0; what < 4; ++what) {
+    long long pre[3][2], tot[3];
+    for (int what = 0; what < 3; ++what) {
         const long long a = need(0, what), b = need(1, what);
         const long long ex = block_scan<T>(a + b, sh, tot[what]);
         pre[what][0] = ex;
         pre[what][1] = ex + a;
     }
-    const long long cap[4] = {(long long)d.n_dense, d.cand_cap, (long long)d.desc_cap, (long long)d.unit_cap};
+    const long long cap[3] = {(long long)d.n_dense, d.cand_cap, (long long)d.unit_cap};
     for (int k = 0; k < 2; ++k) {
         const int i = 2 * t + k;
         if (i >= n) continue;
         bool fit = true;
-        for (int what = 0; what < 4; ++what) fit = fit && pre[what][k] + need(k, what) <= cap[what];
+        for (int what = 0; what < 3; ++what) fit = fit && pre[what][k] + need(k, what) <= cap[what];
         if (!fit) atomicMin(&first_unfit, i);
     }
     __syncthreads();
     const int n_eval = first_unfit;
-    long long units_total = 0;
     for (int k = 0; k < 2; ++k) {
         const int i = 2 * t + k;
         if (i >= n) continue;
@@ -279,70 +273,29 @@ __device__ __forceinline__ void prepare_round(const DS& d) {
         const int nunits = (nrec[k] + kUnit - 1) / kUnit;
         d.s_dense[i] = (int)pre[0][k];
         d.s_cand_off[i] = pre[1][k];
-        d.s_desc_off[i] = (int)pre[2][k];
-        d.s_ndesc[i] = ndesc[k];
-        d.s_unit0[i] = (int)pre[3][k];
+        d.s_unit0[i] = (int)pre[2][k];
         d.s_nunits[i] = nunits;
-        units_total += nunits;
         large_list[atomicAdd(&n_large, 1)] = i;
     }
-    long long all_units;
-    (void)block_scan<T>(units_total, sh, all_units);
+    __syncthreads();
     if (t == 0) {
         ctl->n_prepared = n;
         ctl->n_eval = n_eval;
-        ctl->n_units = (int)all_units;
         ctl->large_slots += n_large;
     }
-    // descriptors and units of the larger slots, one wavefront per slot
+    // the work units of the larger slots, one wavefront per slot
     for (int q = wave; q < n_large; q += T / 64) {
         const int i = large_list[q];
-        const int32_t x = d.s_v[i];
         const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
         for (int u = lane; u < nu; u += 64) d.unit_slot[u0 + u] = i;
-        long long j = d.s_desc_off[i], start = 0;
-        const long long deg = d.gptr[x + 1] - d.gptr[x];
-        if (deg > 0) {
-            if (lane == 0) {
-                d.d_off[j] = d.gptr[x] | kAdjacencyFlag;
-                d.d_len[j] = (int)deg;
-                d.d_start[j] = 0;
-            }
-            start = deg;
-            ++j;
-        }
-        long long guard = d.dir_cap / 4;
-        for (int32_t b = d.head[x]; b >= 0 && guard > 0; --guard) {
-            const int32_t* blk = d.dir + (long long)b * 4;
-            const int c = blk[1];
-            long long at = start;                       // first record of the descriptors handled so far
-            for (int e0 = 0; e0 < c; e0 += 64) {        // sixty-four descriptors per step
-                const int e = e0 + lane;
-                long long off = 0;
-                int len = 0;
-                if (e < c) {
-                    const int32_t* w = blk + kDirHeader + 3 * e;
-                    off = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
-                    len = w[2];
-                }
-                long long incl = len;
-#pragma unroll
-                for (int o = 1; o < 64; o <<= 1) {
-                    const long long y = __shfl_up(incl, o);
-                    if (lane >= o) incl += y;
-                }
-                if (e < c) {
-                    d.d_off[j + e] = off;
-                    d.d_len[j + e] = len;
-                    d.d_start[j + e] = at + incl - len;
-                }
-                at += __shfl(incl, 63);
-            }
-            start += blk[3];
-            j += c;
-            b = blk[0];
-        }
     }
+    // units of the decided slots only: those of the first slot that did not fit, and of all after it, are not walked
+    long long my_units = 0;
+    for (int k = 0; k < 2; ++k)
+        if (cls[k] == kClassLarge) my_units += (nrec[k] + kUnit - 1) / kUnit;
+    long long all_units;
+    (void)block_scan<T>(my_units, sh, all_units);
+    if (t == 0) ctl->n_units = (int)all_units;
 }
 
 // Round step 2 (blocks of 256 threads).  The first kSlots blocks decide one small slot each: the
@@ -389,7 +342,7 @@ __global__ __launch_bounds__(256) void decide_round_kernel(DS d) {
             const int32_t* blk = d.dir + (long long)b * 4;
             const int c = blk[1];
             for (int e = t; e < c && nd + e < kSmallRecords; e += 256) {
-                const int32_t* w = blk + kDirHeader + 3 * e;
+                const int32_t* w = blk + kDirHeader + kDirDesc * e;
                 sd_off[nd + e] = (long long)(uint32_t)w[0] | ((long long)w[1] << 32);
                 sd_len[nd + e] = w[2];
             }
@@ -448,23 +401,29 @@ __global__ __launch_bounds__(256) void decide_round_kernel(DS d) {
         const int k = u - d.s_unit0[i];
         self = d.s_v[i];
         const int nrec = d.s_nrec[i];
-        const long long dbase = d.s_desc_off[i];
-        const int nd = d.s_ndesc[i];
+        const int32_t vtx = d.s_v[i];
+        const long long adj0 = d.gptr[vtx];
+        const int deg = (int)(d.gptr[vtx + 1] - adj0);
+        const int32_t head_blk = d.head[vtx];
         uint32_t* const weight = d.dense + (long long)d.s_dense[i] * d.M;
         Rec* const cand = d.cand + d.s_cand_off[i];
         const int p_end = (k + 1) * kUnit < nrec ? (k + 1) * kUnit : nrec;
         for (int e = t; e < kHashSize; e += 256) { hkey[e] = -1; hval[e] = 0; }
         __syncthreads();
         for (int p = k * kUnit + t; p < p_end; p += 256) {
-            int lo = 0, hi = nd - 1;          // last descriptor that starts at or before p
+            if (p < deg) { add(d.gadj[adj0 + p], 1u); continue; }
+            const int pc = p - deg;                       // position among the records of the chunks
+            const int32_t* blk = d.dir + (long long)head_blk * 4;
+            long long guard = d.dir_cap / 4;
+            while (blk[3] > pc && blk[0] >= 0 && guard-- > 0) blk = d.dir + (long long)blk[0] * 4;   // newest block first
+            int lo = 0, hi = blk[1] - 1;                  // last chunk of the block that starts at or before pc
             while (lo < hi) {
                 const int mid = (lo + hi + 1) >> 1;
-                if (d.d_start[dbase + mid] <= p) lo = mid; else hi = mid - 1;
+                if (blk[kDirHeader + kDirDesc * mid + 3] <= pc) lo = mid; else hi = mid - 1;
             }
-            const long long q = p - d.d_start[dbase + lo];
-            const long long off = d.d_off[dbase + lo];
-            if (off & kAdjacencyFlag) add(d.gadj[(off & ~kAdjacencyFlag) + q], 1u);
-            else { const Rec r = d.arena[off + q]; add(r.to, r.w); }
+            const int32_t* w = blk + kDirHeader + kDirDesc * lo;
+            const Rec r = d.arena[((long long)(uint32_t)w[0] | ((long long)w[1] << 32)) + (pc - w[3])];
+            add(r.to, r.w);
         }
         __syncthreads();
         for (int e = t; e < kHashSize; e += 256) {
@@ -591,7 +550,7 @@ __device__ __forceinline__ int dir_words_for_append(const DS& d, int32_t target)
     if (blk && blk[1] < blk[2]) return 0;
     int cap = blk ? 2 * blk[2] : kDirFirstCap;
     if (cap > kDirMaxCap) cap = kDirMaxCap;
-    return kDirHeader + 3 * cap;
+    return kDirHeader + kDirDesc * cap;
 }
 
 // Takes `total` records of the arena as a new chunk of `target` and lists it in the target's
@@ -605,22 +564,22 @@ __device__ __forceinline__ long long append_chunk(const DS& d, int32_t target, l
     if (!blk || blk[1] == blk[2]) {
         int cap = blk ? 2 * blk[2] : kDirFirstCap;
         if (cap > kDirMaxCap) cap = kDirMaxCap;
-        const long long at = (long long)atomicAdd((unsigned long long*)&ctl->dir_used, (unsigned long long)(kDirHeader + 3 * cap));
+        const long long at = (long long)atomicAdd((unsigned long long*)&ctl->dir_used, (unsigned long long)(kDirHeader + kDirDesc * cap));
         int32_t* nb = d.dir + at;
         nb[0] = b;
         nb[1] = 0;
         nb[2] = cap;
-        nb[3] = 0;
+        nb[3] = d.tot_rec[target];       // position of the block's first chunk
         d.head[target] = (int32_t)(at >> 2);
         blk = nb;
     }
     const int c = blk[1];
-    int32_t* w = blk + kDirHeader + 3 * c;
+    int32_t* w = blk + kDirHeader + kDirDesc * c;
     w[0] = (int32_t)(uint32_t)(base & 0xffffffffll);
     w[1] = (int32_t)(base >> 32);
     w[2] = (int32_t)total;
+    w[3] = d.tot_rec[target];
     blk[1] = c + 1;
-    blk[3] += (int32_t)total;
     d.tot_rec[target] += (int32_t)total;
     d.tot_desc[target] += 1;
     return base;
@@ -945,14 +904,13 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     // memory pools
     // words: a first block per target (16 words); every further block doubles, so a target's blocks hold
     // at most twice its chunks (3 words each) plus headers; targets and chunks are at most M each
-    const int64_t dir_cap = 28 * M + 8192;
+    const int64_t dir_cap = 36 * M + 8192;
     const int64_t arena_cap = 3 * two_m + M + 1024;
     const int64_t cand_cap = two_m + 1024;
-    const int64_t desc_cap = M + 16;
     const int64_t unit_cap = two_m / kUnit + kSlots + 16;
     const int n_dense = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxDense, ((int64_t)4 << 30) / (4 * M)));
-    DevBuf<int32_t> dir, d_len, unit_slot, u_best, row_dirty, sI[11];
-    DevBuf<long long> d_off, d_start, u_score, u_second, sL[5];
+    DevBuf<int32_t> dir, unit_slot, u_best, row_dirty, sI[9];
+    DevBuf<long long> u_score, u_second, sL[5];
     DevBuf<Rec> arena, scand, cand;
     DevBuf<uint32_t> bits, dense;
     DevBuf<Ctl> ctl;
@@ -960,7 +918,6 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     arena.alloc(arena_cap);
     scand.alloc((size_t)kSlots * kSmallRecords);
     cand.alloc(cand_cap);
-    d_off.alloc(desc_cap); d_len.alloc(desc_cap); d_start.alloc(desc_cap);
     unit_slot.alloc(2 * unit_cap); u_best.alloc(unit_cap); u_score.alloc(unit_cap); u_second.alloc(unit_cap);
     bits.alloc((size_t)kSlots * kRowWords);
     row_dirty.alloc(kSlots);
@@ -982,18 +939,17 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     d.tot_rec = d_tot_rec.p; d.tot_desc = d_tot_desc.p;
     d.dir = dir.p; d.dir_cap = dir_cap;
     d.arena = arena.p; d.arena_cap = arena_cap; d.ctl = ctl.p; d.slot_of = d_slot_of.p;
-    d.s_v = sI[0].p; d.s_nrec = sI[1].p; d.s_class = sI[2].p; d.s_dense = sI[3].p; d.s_desc_off = sI[4].p; d.s_ndesc = sI[5].p;
-    d.s_unit0 = sI[6].p; d.s_nunits = sI[7].p; d.s_nt = sI[8].p; d.s_best = sI[9].p; d.s_store = sI[10].p;
+    d.s_v = sI[0].p; d.s_nrec = sI[1].p; d.s_class = sI[2].p; d.s_dense = sI[3].p;
+    d.s_unit0 = sI[4].p; d.s_nunits = sI[5].p; d.s_nt = sI[6].p; d.s_best = sI[7].p; d.s_store = sI[8].p;
     d.s_cand_off = sL[0].p; d.s_score = sL[1].p; d.s_second = sL[2].p; d.s_dv = sL[3].p; d.s_chunk_off = sL[4].p;
     d.bits = bits.p; d.row_dirty = row_dirty.p; d.scand = scand.p; d.cand = cand.p; d.cand_cap = cand_cap;
-    d.d_off = d_off.p; d.d_len = d_len.p; d.d_start = d_start.p; d.desc_cap = (int32_t)desc_cap;
     d.unit_slot = unit_slot.p; d.unit_cap = (int32_t)unit_cap; d.u_best = u_best.p; d.u_score = u_score.p; d.u_second = u_second.p;
     d.dense = dense.p; d.n_dense = n_dense;
 
     // the second set of per-slot arrays and unit table
     DS d_odd = d;
     {
-        int32_t** ip[] = {&d_odd.s_v, &d_odd.s_nrec, &d_odd.s_class, &d_odd.s_dense, &d_odd.s_desc_off, &d_odd.s_ndesc,
+        int32_t** ip[] = {&d_odd.s_v, &d_odd.s_nrec, &d_odd.s_class, &d_odd.s_dense,
                           &d_odd.s_unit0, &d_odd.s_nunits, &d_odd.s_nt, &d_odd.s_best, &d_odd.s_store};
         for (auto pp : ip) *pp += kSlots;
         long long** lp[] = {&d_odd.s_cand_off, &d_odd.s_score, &d_odd.s_second, &d_odd.s_dv, &d_odd.s_chunk_off};
@@ -1010,10 +966,9 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     const int64_t max_groups = 4 * M + 64;     // every round advances by at least one vertex
     for (int64_t gi = 0; gi < max_groups && status < 0; ++gi) {
         // block sizes follow what the last group of rounds looked like: large rounds sort in the commit
-        // kernel, and rounds with larger slots write their descriptors one wavefront per slot (with the
-        // small block those rounds measured slower: 21.6 against 19.6 us per launch)
+        // kernel; the preparation handles two slots per thread
         const bool wide = h.P > kQuadratic;
-        const bool wide_prepare = wide || h.large_slots - large_before >= h.rounds - rounds_before;
+        const bool wide_prepare = h.P > 512;
         large_before = h.large_slots;
         rounds_before = h.rounds;
         pos_before = h.pos;

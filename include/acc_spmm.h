@@ -96,9 +96,12 @@ typedef struct {
      * is set. */
     int32_t pipeline_depth;
     /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its
-     * own up-to-four values; 2 = the wavefront loads the tile's values once and the lanes
-     * exchange them across registers; 0 = default: 2 when the plan has at least 24 entries
-     * per tile on average, or when N is 32 or 64 and the plan has at least 16384 tiles; else 1. */
+     * own up-to-four values one by one; 2 = the wavefront loads the tile's values once and the
+     * lanes exchange them across registers; 3 = every lane loads the twelve bytes around its
+     * (consecutive) values at once; 0 = default: 3 for N <= 32; for 32 < N <= 64, 2 when the plan
+     * has at least 24 entries per tile on average or at least 16384 tiles, else 1; for N > 64,
+     * 3 when the plan has at least 24 entries per tile on average, else 1.  (By the lane width the
+     * call uses: a width N that is not a multiple of 8 counts as the narrower class.) */
     int32_t value_fetch;
     /* The 16-bit floating-point type of csr_vals and of B: ACC_SPMM_FP16 (0, default) = IEEE
      * binary16, ACC_SPMM_BF16 (1) = bfloat16.  C is fp32 and products are accumulated in fp32

@@ -7,6 +7,7 @@ namespace accspmm {
 constexpr int kWavesPerBlock = 4;   // wavefronts (work items) per thread block of the tile kernel
 constexpr int kMaxN = 65536;
 constexpr int kAddrNarrow = 0, kAddrWide = 1, kAddrHot = 2;   // how the tile kernel addresses rows of B
+constexpr int kFetchLane = 0, kFetchCoop = 1, kFetchSpan = 2;   // how a tile's packed values reach the lanes
 constexpr int kStoreStreaming = 1, kStoreNarrow = 2;           // bits of store_mode: nontemporal C stores; 16-bit C
 
 struct ExecParams {
@@ -25,7 +26,7 @@ struct ExecParams {
     int32_t N;
     int32_t addr;      // kAddrNarrow / kAddrWide / kAddrHot
     const uint16_t* __restrict__ B_hot;  // kAddrHot: the gathered most used rows of B
-    bool coop;         // cooperative value fetch
+    int32_t fetch;     // kFetchLane / kFetchCoop / kFetchSpan
     bool tail;         // N is not a whole number of slabs
     bool bf16;         // values are bfloat16
     bool lds;          // B rows staged through an LDS double buffer instead of the register ring

@@ -284,13 +284,6 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.ws = ws;
     p.n_items = (int32_t)plan.items.size();
     p.n_blocks = (p.n_items + kWavesPerBlock - 1) / kWavesPerBlock;
-    // Cooperative value fetch (see the file header) where it measured faster: dense tiles at any
-    // N (break-even between 18 entries per tile, power-law inputs, and 35, block / stencil
-    // inputs), and N of 32 or 64 at any density once there are enough tiles to be bound by
-    // throughput rather than by the latency of one wave's chain of tiles.
-    const bool dense_tiles = plan.stats.mean_nnz_per_tile >= 24.0;
-    const bool narrow_rows = N >= 32 && N <= 64 && plan.stats.num_tiles >= 16384;
-    p.coop = plan.opt.value_fetch == 2 || (plan.opt.value_fetch == 0 && (dense_tiles || narrow_rows));
     p.N = N;
     p.B_hot = b_hot;
     p.addr = gather ? kAddrHot
@@ -308,6 +301,24 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.grid_y = (slabs + p.ns - 1) / p.ns;
     p.tail = (int64_t)p.grid_y * p.ns * slab_width != N;
     if (!p.tail && p.ns == 2 && p.fpl != 8) p.tail = true;  // shape compiled only in its general form
+    // How the packed values reach the lanes (see the tile kernel's header), by what measured fastest on
+    // uniform, power-law, stencil and block inputs at N = 16 .. 512: lanes of one or two features (N <= 32)
+    // read their span; lanes of four features (N <= 64) share one cooperative read when tiles are
+    // dense (24 entries per tile on average: the break-even lay between 18 and 35) or the launch has enough tiles to
+    // be bound by throughput rather than by the latency of one wave's chain of tiles; 16-byte lanes read
+    // their span when tiles are dense, and value by value on the sparse tiles of power-law inputs.
+    const bool dense_tiles = plan.stats.mean_nnz_per_tile >= 24.0;
+    const bool many_tiles = plan.stats.num_tiles >= 16384;
+    switch (plan.opt.value_fetch) {
+        case 1: p.fetch = kFetchLane; break;
+        case 2: p.fetch = kFetchCoop; break;
+        case 3: p.fetch = kFetchSpan; break;
+        default:
+            if (p.fpl <= 2) p.fetch = kFetchSpan;
+            else if (p.fpl == 4) p.fetch = (dense_tiles || many_tiles) ? kFetchCoop : kFetchLane;
+            else p.fetch = dense_tiles ? kFetchSpan : kFetchLane;
+    }
+    if (p.fetch == kFetchSpan && (int64_t)f.vals.n < f.nnz + 6) p.fetch = kFetchLane;   // a plan file without the slack
     const int default_depth = (p.fpl == 8 && p.ns == 1) ? 3 : (p.fpl == 8 ? 2 : 1);
     p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
     p.store_mode = (plan.opt.streaming_stores != 0 ? kStoreStreaming : 0) | (narrow_c ? kStoreNarrow : 0);

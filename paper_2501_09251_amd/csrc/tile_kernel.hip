@@ -14,13 +14,16 @@
 // position inside an MFMA is a free choice and no transpose through LDS is needed: the
 // four k-values of one feature come from four registers and are packed with v_perm_b32.
 //
-// The packed values of a tile reach the lanes in one of two ways (template COOP).  Per-lane:
-// each lane reads its up-to-four values itself (four 2-byte loads).  Cooperative: the wave
-// reads the tile's contiguous values once, one dword per lane, and every lane then picks its
-// values out of the other lanes' registers with ds_bpermute.  The second way issues a
-// quarter of the memory instructions and wins when tiles are dense; the first wins on the
-// sparse tiles of power-law inputs at N >= 128.  Execute selects the way from the plan's mean
-// entries per tile and N.
+// The packed values of a tile reach the lanes in one of three ways (template FETCH).  Per-lane
+// (kFetchLane): each lane reads its up-to-four values itself (four 2-byte loads).  Cooperative
+// (kFetchCoop): the wave reads the tile's contiguous values once, one dword per lane, and every
+// lane then picks its values out of the other lanes' registers with ds_bpermute.  Span
+// (kFetchSpan): a lane's values are consecutive in the packed array (row-major inside the tile),
+// so the lane reads the three dwords that hold its first value and the three after it with one
+// load, shifts by the odd half and routes the halves to its set bits with the byte permutes of
+// the cooperative way; the array is allocated with eight values of slack so that the load never
+// leaves it.  (The same eight bytes as one load aligned to two bytes only measured slower.)
+// Execute selects the way from the lane width, the plan's mean entries per tile and N.
 //
 // Loads are software-pipelined (the "least bubble" idea of Section 3.4): the B rows and
 // values of tiles t+1..t+DEPTH are in flight while tile t is multiplied, and the index
@@ -116,6 +119,7 @@ struct TileData {       // what the multiply needs
     // per-lane fetch: v[0..3] = up to four packed values (fp16 bits).
     // cooperative fetch: v[0..2] = the tile's packed values, chunk k's dword L in lane L;
     //                    v[3] = index of this lane's first value relative to the first loaded half
+    // span fetch: v[0..2] = the dwords around this lane's four values, v[3] = 0 or 16, the bit where they start
     uint32_t v[4];
     uint32_t nib;       // this lane's four bitmap bits
     uint32_t nchunk;    // cooperative fetch: 64-dword chunks that hold values (wave-uniform)
@@ -134,7 +138,7 @@ struct TileData {       // what the multiply needs
 // load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
 // BF16 = true: the 16-bit values of A and B are bfloat16 instead of IEEE half; only the MFMA
 // instruction differs, the data movement is the same.
-template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16, bool LDS = false>
+template <int FPL, int NS, int DEPTH, int ADDR, int FETCH, bool TAIL, bool BF16, bool LDS = false>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
@@ -188,8 +192,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     // Cooperative fetch: byte-permute selectors, entry (lane & 15) = a pattern of four bits.  Output
     // half j is half popcount(bits below j) of the lane's four consecutive values if bit j is set
     // (bytes 2k, 2k+1), else the constant zero (selector byte 0x0c).
+    constexpr bool COOP = FETCH == kFetchCoop;
+    constexpr bool SPAN = FETCH == kFetchSpan;
     uint32_t lut_lo = 0, lut_hi = 0;
-    if constexpr (COOP) {
+    if constexpr (COOP || SPAN) {
         const uint32_t pat = (uint32_t)lane & 15u;
         uint32_t sel[4];
 #pragma unroll
@@ -347,6 +353,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             if (nchunk > 2 && (uint32_t)(128 + lane) * 2u < span) d.v[2] = v32[128 + lane];
             d.v[3] = i0 - first_half;
             d.nchunk = nchunk;
+        } else if constexpr (SPAN) {
+            // the three dwords that hold values i0 .. i0+3, and the shift that brings value i0 to bit 0
+            struct __attribute__((aligned(4))) Span { uint32_t a, b, c; };
+            const Span sp = *reinterpret_cast<const Span*>(reinterpret_cast<const char*>(p.vals) + (size_t)(uint32_t)((i0 & ~1u) << 1));
+            d.v[0] = sp.a; d.v[1] = sp.b; d.v[2] = sp.c; d.v[3] = (i0 & 1u) << 4;
+            d.nchunk = 0;
         } else {
             const uint32_t i1 = i0 + (nib & 1u);
             const uint32_t i2 = i1 + ((nib >> 1) & 1u);
@@ -411,6 +423,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             const int at = (int)(nib << 2);
             const uint32_t s_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_lo);
             const uint32_t s_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_hi);
+            return uintx2{__builtin_amdgcn_perm(hi, lo, s_lo), __builtin_amdgcn_perm(hi, lo, s_hi)};
+        } else if constexpr (SPAN) {
+            // d.v[0..2] hold the lane's four consecutive values from bit d.v[3] on; half k goes to the k-th set bit of nib
+            const int at = (int)(nib << 2);
+            const uint32_t s_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_lo);
+            const uint32_t s_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_hi);
+            const uint32_t lo = __builtin_amdgcn_alignbit(d.v[1], d.v[0], d.v[3]);
+            const uint32_t hi = __builtin_amdgcn_alignbit(d.v[2], d.v[1], d.v[3]);
             return uintx2{__builtin_amdgcn_perm(hi, lo, s_lo), __builtin_amdgcn_perm(hi, lo, s_hi)};
         } else {
             const uint32_t a0 = (nib & 1u) ? d.v[0] : 0u;
@@ -513,7 +533,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 const uintx2 au = operand_a(data[r]);
-                if constexpr (COOP) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (FETCH != kFetchLane) __builtin_amdgcn_sched_barrier(0);
                 const int s = (r + DEPTH) % R;            // slot of tile tt+DEPTH
                 issue(meta[s], data[s], s);
                 load_meta(tt + 2 * DEPTH + 1, meta[s]);   // the slot's next tile
@@ -524,27 +544,30 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     }
 }
 
-template <int FPL, int NS, int DEPTH, int ADDR, bool COOP, bool TAIL, bool BF16>
+template <int FPL, int NS, int DEPTH, int ADDR, int FETCH, bool TAIL, bool BF16>
 void launch_one(const ExecParams& p, hipStream_t stream) {
     const int blocks = ((p.n_blocks + 7) / 8) * 8;
     dim3 grid(blocks, p.grid_y), block(kWavesPerBlock * 64);
     if constexpr (DEPTH == 1 && NS == 1 && !TAIL && !BF16 && FPL >= 2) {
         if (p.lds) {
-            hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16, true>), grid, block, 0, stream, p.rwo,
+            hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, FETCH, TAIL, BF16, true>), grid, block, 0, stream, p.rwo,
                                p.tco, p.a2b, p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items,
                                p.n_blocks, p.N, p.store_mode);
             return;
         }
     }
-    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, COOP, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
+    hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, FETCH, TAIL, BF16>), grid, block, 0, stream, p.rwo, p.tco, p.a2b,
                        p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items, p.n_blocks, p.N,
                        p.store_mode);
 }
 
 template <int FPL, int NS, int DEPTH, int ADDR, bool TAIL, bool BF16>
 void launch_fetch(const ExecParams& p, hipStream_t stream) {
-    if (p.coop) launch_one<FPL, NS, DEPTH, ADDR, true, TAIL, BF16>(p, stream);
-    else launch_one<FPL, NS, DEPTH, ADDR, false, TAIL, BF16>(p, stream);
+    switch (p.fetch) {
+        case kFetchCoop: launch_one<FPL, NS, DEPTH, ADDR, kFetchCoop, TAIL, BF16>(p, stream); break;
+        case kFetchSpan: launch_one<FPL, NS, DEPTH, ADDR, kFetchSpan, TAIL, BF16>(p, stream); break;
+        default: launch_one<FPL, NS, DEPTH, ADDR, kFetchLane, TAIL, BF16>(p, stream); break;
+    }
 }
 
 template <int FPL, int NS, int DEPTH, bool TAIL, bool BF16>

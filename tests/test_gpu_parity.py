@@ -142,7 +142,7 @@ def test_every_kernel_variant(N):
     B = wl.dense(w.K, N, 77, "normal", 0.0, 1.0)
     ref = None
     for depth in (0, 1, 2, 3):
-        for streaming, fetch in ((0, 1), (1, 1), (0, 2), (1, 2)):
+        for streaming, fetch in ((0, 1), (1, 1), (0, 2), (1, 2), (0, 3), (1, 3)):
             opt = acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16, streaming_stores=streaming,
                                    no_prefetch=int(depth == 0), pipeline_depth=depth, value_fetch=fetch)
             plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
@@ -166,7 +166,7 @@ def test_lds_staging_gives_the_same_result(N):
     B = wl.dense(w.K, N, 78, "normal", 0.0, 1.0)
     for column_order in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON):
         ref = None
-        for lds, fetch in ((0, 1), (1, 1), (1, 2)):
+        for lds, fetch in ((0, 1), (1, 1), (1, 2), (0, 3), (1, 3)):
             opt = acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=16, value_fetch=fetch,
                                    lds_staging=lds, column_order=column_order)
             plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
@@ -191,7 +191,7 @@ def test_lds_staging_gives_the_same_result(N):
         acc.acc_spmm_destroy(plan)
 
 
-@pytest.mark.parametrize("fetch", [0, 1, 2])
+@pytest.mark.parametrize("fetch", [0, 1, 2, 3])
 @pytest.mark.parametrize("N", [16, 64, 128, 512])
 def test_dense_tiles_at_odd_value_offsets(fetch, N):
     """Full 16x16 tiles whose packed values start at an odd index (a one-entry first tile),
@@ -215,7 +215,7 @@ def test_dense_tiles_at_odd_value_offsets(fetch, N):
 
 
 @pytest.mark.parametrize("N", [16, 64, 128, 256, 100, 7])
-@pytest.mark.parametrize("fetch", [1, 2])
+@pytest.mark.parametrize("fetch", [1, 2, 3])
 def test_bfloat16_values(N, fetch):
     """value_type = bfloat16: same bits-in, fp32-out contract, wide-exponent inputs that binary16
     could not hold, split windows, and the one-row-per-wave comparison kernel."""
@@ -739,7 +739,7 @@ def test_wide_addressing_at_every_lane_width(K, N):
     Bd = torch.from_numpy(B.view(np.int16)).to(dev)
     C_ref, bound = oracle.spmm(rowptr, colidx, vals, B)
     first = None
-    for fetch in (1, 2):
+    for fetch in (1, 2, 3):
         for depth in (0, 1, 2, 3):
             plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
                                         acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=4,
@@ -992,7 +992,7 @@ def test_randomised_shapes_and_options(block):
         operand_order = int(rng.integers(0, 2))
         opt = dict(reorder=int(rng.integers(0, 3)), load_balance=int(rng.integers(0, 3)),
                    max_tiles_per_item=int(rng.choice([0, 1, 3, 8, 64])), column_order=int(rng.integers(0, 3)),
-                   operand_order=operand_order, value_fetch=int(rng.integers(0, 3)),
+                   operand_order=operand_order, value_fetch=int(rng.integers(0, 4)),
                    pipeline_depth=int(rng.integers(0, 4)), streaming_stores=int(rng.integers(0, 2)),
                    segment_length=int(rng.choice([0, 2, 37, 4096])), keep_csr=1, keep_entry_map=1,
                    value_type=acc.ACC_SPMM_BF16 if use_bf16 else acc.ACC_SPMM_FP16)

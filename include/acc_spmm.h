@@ -71,10 +71,14 @@ typedef struct {
      * (acc_spmm_stats.max_tiles_per_item reports it). */
     int32_t max_tiles_per_item;
     /* Tile geometry: rows per row window (8, 16, 32 or 64) and condensed columns per tile (8, 16
-     * or 32).  0 = default (16,16), the geometry the execute kernel runs.  The others, among them
-     * the paper's (8,8) (Section 3.3), are accepted for building, exporting and measuring the
-     * format only (acc_spmm_plan_stats, acc_spmm_plan_traffic): acc_spmm_execute returns
-     * ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
+     * or 32).  0 = default (16,16).  The execute kernel runs (16,16) and (16,32); the latter, on
+     * the 32-deep matrix instruction, halves the tiles and measured between 12 % slower and 7 %
+     * faster than (16,16) depending on input and N, so no AUTO decision picks it.  A (16,32) plan
+     * fetches values as value_fetch = 3, runs pipeline depths 1 and 2 only (deeper requests run
+     * as 2), and refuses no_prefetch, lds_staging and acc_spmm_sddmm.  The other geometries,
+     * among them the paper's (8,8) (Section 3.3), are accepted for building, exporting and
+     * measuring the format only (acc_spmm_plan_stats, acc_spmm_plan_traffic): acc_spmm_execute
+     * returns ACC_SPMM_ERR_UNSUPPORTED on such a plan. */
     int32_t window_height;
     int32_t tile_width;
     /* Leaves per segment in the ordering step's candidate search.  0 = default 1024; at

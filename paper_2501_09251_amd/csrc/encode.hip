@@ -169,8 +169,8 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
             ACC_HIP(hipMemset(out.tc_offset.p, 0, sizeof(int32_t)));
             out.sparse_a_to_b.alloc(0);
             out.tc_local_bit.alloc(0);
-            out.vals.alloc(8);
-            ACC_HIP(hipMemset(out.vals.p, 0, 16));
+            out.vals.alloc(16);
+            ACC_HIP(hipMemset(out.vals.p, 0, 32));
         }
         return;
     }
@@ -261,8 +261,8 @@ void encode_on_device(int64_t M, int64_t K, int64_t nnz, const int32_t* d_rowptr
     cnt.release();
 
     // 8. values (8 halves of zero padding: the runtime kernel reads up to 4 past a tile's end)
-    out.vals.alloc(nnz + 8);
-    ACC_HIP(hipMemset(out.vals.p + nnz, 0, 16));
+    out.vals.alloc(nnz + 16);   // slack: the tile kernel's span loads read up to ten values past a lane's first
+    ACC_HIP(hipMemset(out.vals.p + nnz, 0, 32));
     if (entry_of) entry_of->alloc(nnz);
     hipLaunchKernelGGL(scatter_values_kernel, dim3(blocks_for(M, 4)), dim3(256), 0, 0, M, d_rowptr, d_vals, d_perm,
                        new_rowptr.p, tile_of.p, bit_of.p, out.tc_local_bit.p, NW, out.tc_offset.p, out.vals.p,

@@ -29,6 +29,7 @@ struct ExecParams {
     int32_t fetch;     // kFetchLane / kFetchCoop / kFetchSpan
     bool tail;         // N is not a whole number of slabs
     bool bf16;         // values are bfloat16
+    bool tw32;         // the plan's tiles are 16 x 32 (span fetch, depth 1 or 2)
     bool lds;          // B rows staged through an LDS double buffer instead of the register ring
     int32_t fpl, ns, grid_y, depth, store_mode;
 };

@@ -224,8 +224,11 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
         ~EventGuard() { for (int i = 0; i < 4; ++i) if (ev[i]) (void)hipEventDestroy(ev[i]); }
     } guard{ev};
     const DeviceFormat& f = plan.fmt;
-    if (f.WH != 16 || f.TW != 16)
-        fail(ACC_SPMM_ERR_UNSUPPORTED, "execute needs a plan with 16x16 tiles");
+    if (f.WH != 16 || (f.TW != 16 && f.TW != 32))
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "execute needs a plan with 16x16 or 16x32 tiles");
+    const bool tw32 = f.TW == 32;
+    if (tw32 && (int64_t)f.vals.n < f.nnz + 10)
+        fail(ACC_SPMM_ERR_UNSUPPORTED, "this plan's value array lacks the slack that the 16x32 kernel's loads need");
     if (N <= 0 || N > kMaxN) fail(ACC_SPMM_ERR_UNSUPPORTED, "N must be between 1 and 65536");
     if ((reinterpret_cast<uintptr_t>(B) | reinterpret_cast<uintptr_t>(C)) & 15)
         fail(ACC_SPMM_ERR_INVALID_ARG, "B and C must be 16-byte aligned");
@@ -319,14 +322,21 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
             else p.fetch = dense_tiles ? kFetchSpan : kFetchLane;
     }
     if (p.fetch == kFetchSpan && (int64_t)f.vals.n < f.nnz + 6) p.fetch = kFetchLane;   // a plan file without the slack
+    p.tw32 = tw32;
+    if (tw32) p.fetch = kFetchSpan;   // the only way the 16 x 32 kernel fetches values
     const int default_depth = (p.fpl == 8 && p.ns == 1) ? 3 : (p.fpl == 8 ? 2 : 1);
     p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
+    if (tw32) {
+        // a tile holds twice the rows of B: half the depth keeps the same bytes in flight; depths 1 and 2 exist
+        if (plan.opt.no_prefetch) fail(ACC_SPMM_ERR_UNSUPPORTED, "plans with 16x32 tiles run with prefetch only");
+        p.depth = plan.opt.pipeline_depth > 0 ? std::min(plan.opt.pipeline_depth, 2) : (default_depth >= 3 ? 2 : 1);
+    }
     p.store_mode = (plan.opt.streaming_stores != 0 ? kStoreStreaming : 0) | (narrow_c ? kStoreNarrow : 0);
     p.bf16 = plan.opt.value_type == ACC_SPMM_BF16;
     p.lds = plan.opt.lds_staging != 0;
     if (p.lds) {
         // the comparison form exists for whole slabs of at least two features per lane, one slab per wave
-        if (p.fpl < 2 || p.ns != 1 || p.tail || p.bf16 || plan.opt.no_prefetch)
+        if (p.fpl < 2 || p.ns != 1 || p.tail || p.bf16 || plan.opt.no_prefetch || tw32)
             fail(ACC_SPMM_ERR_UNSUPPORTED, "lds_staging runs fp16 plans at N = 32, 64 or an odd multiple of 128 up to 384, with prefetch");
         p.depth = 1;   // a double buffer: one tile ahead
     }

@@ -34,9 +34,19 @@
 // the current tile, read back from the other LDS buffer, is multiplied: a double buffer, one tile
 // ahead.  The register ring above measured as fast or faster on every workload and stays the default.
 //
+// TW32 = true runs plans whose tiles are 16 x 32 (tile_width = 32) on v_mfma_f32_16x16x32_f16: a lane
+// group gathers eight rows of B per tile, a lane's sparse operand is the eight positions (row c,
+// k = 8g .. 8g+7), i.e. one byte of the row's 32-bit bitmap word, which the lane loads itself (a
+// row is exactly one dword; the offset of the row's first value is a prefix sum of popcounts over
+// the sixteen lanes of a group, by DPP row shifts), and the values come by two span loads, one per
+// nibble.  Half as many tiles, index-word requests and window tests for the same columns; the
+// padding of a window's last tile grows.
+//
 // This file is compiled once per (features per lane, value type): ACC_TILE_FPL in {1, 2, 4, 8}
 // and ACC_TILE_BF16 in {0, 1} come from the command line, so that the many instantiations
 // build in parallel.
+#include <type_traits>
+
 #include "execute.h"
 
 #if !defined(ACC_TILE_FPL) || !defined(ACC_TILE_BF16)
@@ -52,6 +62,8 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
 typedef int32_t intx4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bfloat8 __attribute__((ext_vector_type(8)));
 
 template <int FPL>
 struct Chunk {  // FPL consecutive fp16 features of one B row, as dwords
@@ -107,21 +119,29 @@ __device__ __forceinline__ uint32_t narrow16(float x) {
     }
 }
 
-struct TileMeta {       // index words of one tile
+template <bool TW32>
+struct TileMeta {       // index words of one 16 x 16 tile
     intx4 cols;         // this lane group's four SparseAToB entries
     uint64_t bm[4];     // TCLocalBit (wave-uniform)
     int32_t tco;        // TCOffset (wave-uniform)
 };
+template <>
+struct TileMeta<true> { // index words of one 16 x 32 tile
+    intx4 cols, cols2;  // this lane group's eight SparseAToB entries
+    uint32_t rowbits;   // TCLocalBit: the 32 bits of this lane's row c
+    int32_t tco;        // TCOffset (wave-uniform)
+};
 
-template <int FPL, int NS>
-struct TileData {       // what the multiply needs
-    Chunk<FPL> b[NS][4];
+template <int FPL, int NS, int QR>
+struct TileData {       // what the multiply needs; QR = rows of B per lane group and tile
+    Chunk<FPL> b[NS][QR];
     // per-lane fetch: v[0..3] = up to four packed values (fp16 bits).
     // cooperative fetch: v[0..2] = the tile's packed values, chunk k's dword L in lane L;
     //                    v[3] = index of this lane's first value relative to the first loaded half
     // span fetch: v[0..2] = the dwords around this lane's four values, v[3] = 0 or 16, the bit where they start
-    uint32_t v[4];
-    uint32_t nib;       // this lane's four bitmap bits
+    //             (16 x 32 tiles: v[4..7] = the same for the values of the upper nibble)
+    uint32_t v[QR];
+    uint32_t nib;       // this lane's four (eight) bitmap bits
     uint32_t nchunk;    // cooperative fetch: 64-dword chunks that hold values (wave-uniform)
 };
 
@@ -138,7 +158,7 @@ struct TileData {       // what the multiply needs
 // load nor store.  N is always a multiple of FPL, so a lane is wholly inside or wholly outside.
 // BF16 = true: the 16-bit values of A and B are bfloat16 instead of IEEE half; only the MFMA
 // instruction differs, the data movement is the same.
-template <int FPL, int NS, int DEPTH, int ADDR, int FETCH, bool TAIL, bool BF16, bool LDS = false>
+template <int FPL, int NS, int DEPTH, int ADDR, int FETCH, bool TAIL, bool BF16, bool LDS = false, bool TW32 = false>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const int32_t* __restrict__ g_rwo, const int32_t* __restrict__ g_tco, const int32_t* __restrict__ g_a2b,
     const uint64_t* __restrict__ g_bits, const uint16_t* __restrict__ g_vals, const int32_t* __restrict__ g_perm_pad,
@@ -147,7 +167,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     int32_t store_mode) {
     constexpr int R = DEPTH + 1;
     constexpr int SW = 16 * FPL;  // features per slab
-    static_assert(!LDS || (DEPTH == 1 && NS == 1 && !TAIL && FPL >= 2), "LDS staging: double buffer, whole slabs, dword lanes");
+    static_assert(!LDS || (DEPTH == 1 && NS == 1 && !TAIL && FPL >= 2 && !TW32), "LDS staging: double buffer, whole slabs, dword lanes");
+    static_assert(!TW32 || FETCH == kFetchSpan, "16 x 32 tiles fetch their values by span");
+    constexpr int QR = TW32 ? 8 : 4;     // rows of B per lane group and tile
     // LDS staging: per wave and ring slot, four planes (one per B row of the lane group) of 64 lanes x
     // DW dwords, each dword column a plane of its own when a lane holds fewer than four (the load
     // instruction places lane l's data at l times its size)
@@ -265,11 +287,17 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             for (int m = 0; m < FPL; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
     };
 
-    auto load_meta = [&](int t, TileMeta& m) __attribute__((always_inline)) {
+    auto load_meta = [&](int t, TileMeta<TW32>& m) __attribute__((always_inline)) {
         t = t < te ? t : te - 1;  // past the end: re-read the last tile (always in bounds)
-        m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 16 + 4 * g);
-        const uint64_t* bm = p.bits + (size_t)t * 4;
-        m.bm[0] = bm[0]; m.bm[1] = bm[1]; m.bm[2] = bm[2]; m.bm[3] = bm[3];
+        if constexpr (TW32) {
+            m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 32 + 8 * g);
+            m.cols2 = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 32 + 8 * g + 4);
+            m.rowbits = reinterpret_cast<const uint32_t*>(p.bits)[(size_t)t * 16 + c];
+        } else {
+            m.cols = *reinterpret_cast<const intx4*>(p.a2b + (size_t)t * 16 + 4 * g);
+            const uint64_t* bm = p.bits + (size_t)t * 4;
+            m.bm[0] = bm[0]; m.bm[1] = bm[1]; m.bm[2] = bm[2]; m.bm[3] = bm[3];
+        }
         m.tco = p.tco[t];
     };
 
@@ -277,16 +305,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     const uint64_t hot_base = reinterpret_cast<uint64_t>(g_Bhot) + (uint64_t)f0 * 2;
     const uint64_t cold_base = reinterpret_cast<uint64_t>(p.B) + (uint64_t)f0 * 2;
     const uint32_t row_bytes = (uint32_t)N * 2u;
-    auto issue = [&](const TileMeta& m, TileData<FPL, NS>& d, int slot) __attribute__((always_inline)) {
+    auto issue = [&](const TileMeta<TW32>& m, TileData<FPL, NS, QR>& d, int slot) __attribute__((always_inline)) {
+        int32_t entry[QR];
+        entry[0] = m.cols[0]; entry[1] = m.cols[1]; entry[2] = m.cols[2]; entry[3] = m.cols[3];
+        if constexpr (TW32) { entry[4] = m.cols2[0]; entry[5] = m.cols2[1]; entry[6] = m.cols2[2]; entry[7] = m.cols2[3]; }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < QR; ++q) {
             if constexpr (LDS) {
                 // the lane's address as in the register form; the data lands in LDS
                 uint64_t row;
                 if constexpr (ADDR == kAddrNarrow) {
-                    row = cold_base + (uint64_t)((__umul24((uint32_t)m.cols[q], (uint32_t)N)) << 1);
+                    row = cold_base + (uint64_t)((__umul24((uint32_t)entry[q], (uint32_t)N)) << 1);
                 } else {
-                    const int32_t e = m.cols[q];
+                    const int32_t e = entry[q];
                     const bool hot = ADDR == kAddrHot && e < 0;
                     row = (uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes + (hot ? hot_base : cold_base);
                 }
@@ -301,7 +332,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                                                          (__attribute__((address_space(3))) void*)(plane + k * 64), 4, 0, 0);
                 }
             } else if constexpr (ADDR == kAddrNarrow) {
-                const uint32_t off = (__umul24((uint32_t)m.cols[q], (uint32_t)N) + (uint32_t)f0) << 1;
+                const uint32_t off = (__umul24((uint32_t)entry[q], (uint32_t)N) + (uint32_t)f0) << 1;
                 const uint16_t* row = reinterpret_cast<const uint16_t*>(reinterpret_cast<const char*>(p.B) + (size_t)off);
 #pragma unroll
                 for (int s = 0; s < NS; ++s) {
@@ -315,7 +346,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 }
             } else {
                 // one 32x32+64-bit multiply-add on top of the lane's precomputed base(s)
-                const int32_t e = m.cols[q];
+                const int32_t e = entry[q];
                 const bool hot = ADDR == kAddrHot && e < 0;
                 const uint64_t row = (uint64_t)(uint32_t)(hot ? ~e : e) * (uint64_t)row_bytes + (hot ? hot_base : cold_base);
 #pragma unroll
@@ -330,18 +361,35 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                 }
             }
         }
-        // this lane's bitmap word and the popcount of the words below it, by plain selects
-        const int c0 = __builtin_popcountll(m.bm[0]), c1 = __builtin_popcountll(m.bm[1]),
-                  c2 = __builtin_popcountll(m.bm[2]);
-        uint64_t word = m.bm[0];
-        word = w1 ? m.bm[1] : word;
-        word = w2 ? m.bm[2] : word;
-        word = w3 ? m.bm[3] : word;
-        const int pre = (w1 ? c0 : 0) + (w2 ? c1 : 0) + (w3 ? c2 : 0);
-        const uint32_t nib = (uint32_t)(word >> sh) & 15u;
-        const uint32_t i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
+        uint32_t nib, i0, tile_cnt = 0;   // tile_cnt: entries of the tile (cooperative fetch only)
+        if constexpr (TW32) {
+            // the row's entries before this lane's byte, and the entries of the rows above by an inclusive
+            // prefix sum of the rows' counts over the sixteen lanes of the group (DPP row shifts; a lane that
+            // would read from outside its row adds zero)
+            const uint32_t rb = m.rowbits;
+            const uint32_t cnt = (uint32_t)__builtin_popcount(rb);
+            uint32_t incl = cnt;
+            incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x111, 0xf, 0xf, true);   // row_shr:1
+            incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x112, 0xf, 0xf, true);   // row_shr:2
+            incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x114, 0xf, 0xf, true);   // row_shr:4
+            incl += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)incl, 0x118, 0xf, 0xf, true);   // row_shr:8
+            nib = (rb >> (8 * g)) & 255u;
+            i0 = (uint32_t)m.tco + (incl - cnt) + (uint32_t)__builtin_popcount(rb & ((1u << (8 * g)) - 1u));
+        } else {
+            // this lane's bitmap word and the popcount of the words below it, by plain selects
+            const int c0 = __builtin_popcountll(m.bm[0]), c1 = __builtin_popcountll(m.bm[1]),
+                      c2 = __builtin_popcountll(m.bm[2]);
+            uint64_t word = m.bm[0];
+            word = w1 ? m.bm[1] : word;
+            word = w2 ? m.bm[2] : word;
+            word = w3 ? m.bm[3] : word;
+            const int pre = (w1 ? c0 : 0) + (w2 ? c1 : 0) + (w3 ? c2 : 0);
+            nib = (uint32_t)(word >> sh) & 15u;
+            i0 = (uint32_t)(m.tco + pre + __builtin_popcountll(word & below_mask));
+            if constexpr (COOP) tile_cnt = (uint32_t)(c0 + c1 + c2 + __builtin_popcountll(m.bm[3]));
+        }
         if constexpr (COOP) {
-            const uint32_t cnt = (uint32_t)(c0 + c1 + c2 + __builtin_popcountll(m.bm[3]));
+            const uint32_t cnt = tile_cnt;
             const uint32_t first_half = (uint32_t)m.tco & ~1u;        // first loaded value (dword aligned)
             const uint32_t span = ((uint32_t)m.tco & 1u) + cnt;       // halves from there to the tile's end
             const uint32_t nchunk = (span + 127u) >> 7;               // 0..3
@@ -358,6 +406,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             struct __attribute__((aligned(4))) Span { uint32_t a, b, c; };
             const Span sp = *reinterpret_cast<const Span*>(reinterpret_cast<const char*>(p.vals) + (size_t)(uint32_t)((i0 & ~1u) << 1));
             d.v[0] = sp.a; d.v[1] = sp.b; d.v[2] = sp.c; d.v[3] = (i0 & 1u) << 4;
+            if constexpr (TW32) {   // the values of the upper nibble follow those of the lower one
+                const uint32_t i1 = i0 + (uint32_t)__builtin_popcount(nib & 15u);
+                const Span sq = *reinterpret_cast<const Span*>(reinterpret_cast<const char*>(p.vals) + (size_t)(uint32_t)((i1 & ~1u) << 1));
+                d.v[4] = sq.a; d.v[5] = sq.b; d.v[6] = sq.c; d.v[7] = (i1 & 1u) << 4;
+            }
             d.nchunk = 0;
         } else {
             const uint32_t i1 = i0 + (nib & 1u);
@@ -375,7 +428,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
 
     // LDS staging: the B rows of the tile in ring slot `slot`, which the wait above this call has
     // seen arrive, from LDS into the registers the multiply reads
-    auto fetch_staged = [&](TileData<FPL, NS>& d, int slot) __attribute__((always_inline)) {
+    auto fetch_staged = [&](TileData<FPL, NS, QR>& d, int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const uint32_t* plane = stage_wave + (slot * 4 + q) * DW * 64;
@@ -390,8 +443,23 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
     };
 
     // The sparse tile as this lane's MFMA operand: four fp16 values (zero where the bit is clear).
-    auto operand_a = [&](const TileData<FPL, NS>& d) __attribute__((always_inline)) -> uintx2 {
+    auto operand_a = [&](const TileData<FPL, NS, QR>& d) __attribute__((always_inline)) {
         const uint32_t nib = d.nib;
+        if constexpr (TW32) {
+            // eight positions: the lower nibble takes its halves from v[0..3], the upper one from v[4..7]
+            uintx4 a;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t lo = __builtin_amdgcn_alignbit(d.v[4 * h + 1], d.v[4 * h], d.v[4 * h + 3]);
+                const uint32_t hi = __builtin_amdgcn_alignbit(d.v[4 * h + 2], d.v[4 * h + 1], d.v[4 * h + 3]);
+                const int at = (int)(((nib >> (4 * h)) & 15u) << 2);
+                const uint32_t s_lo = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_lo);
+                const uint32_t s_hi = (uint32_t)__builtin_amdgcn_ds_bpermute(at, (int)lut_hi);
+                a[2 * h] = __builtin_amdgcn_perm(hi, lo, s_lo);
+                a[2 * h + 1] = __builtin_amdgcn_perm(hi, lo, s_hi);
+            }
+            return a;
+        } else
         if constexpr (COOP) {
             // This lane's values are halves r0..r0+3 of what the wave loaded (r0 = d.v[3]): they lie in
             // the dwords j, j+1, j+2 with j = r0 >> 1, each held by lane (dword & 63) of chunk
@@ -440,21 +508,35 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
             return uintx2{a0 | (a1 << 16), a2 | (a3 << 16)};
         }
     };
+    using OperandA = std::conditional_t<TW32, uintx4, uintx2>;
 
-    auto multiply = [&](const TileData<FPL, NS>& d, const uintx2 au) __attribute__((always_inline)) {
+    auto multiply = [&](const TileData<FPL, NS, QR>& d, const OperandA au) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
 #pragma unroll
             for (int m = 0; m < FPL; ++m) {
                 const uint32_t sel = (m & 1) ? 0x07060302u : 0x05040100u;
-                const uintx2 bu{__builtin_amdgcn_perm(d.b[s][1].d[m >> 1], d.b[s][0].d[m >> 1], sel),
-                                __builtin_amdgcn_perm(d.b[s][3].d[m >> 1], d.b[s][2].d[m >> 1], sel)};
-                if constexpr (BF16)
-                    acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, au),
-                                                                          __builtin_bit_cast(shortx4, bu), acc[s][m], 0, 0, 0);
-                else
-                    acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, au),
-                                                                      __builtin_bit_cast(half4, bu), acc[s][m], 0, 0, 0);
+                if constexpr (TW32) {
+                    const uintx4 bu{__builtin_amdgcn_perm(d.b[s][1].d[m >> 1], d.b[s][0].d[m >> 1], sel),
+                                    __builtin_amdgcn_perm(d.b[s][3].d[m >> 1], d.b[s][2].d[m >> 1], sel),
+                                    __builtin_amdgcn_perm(d.b[s][5].d[m >> 1], d.b[s][4].d[m >> 1], sel),
+                                    __builtin_amdgcn_perm(d.b[s][7].d[m >> 1], d.b[s][6].d[m >> 1], sel)};
+                    if constexpr (BF16)
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bfloat8, au),
+                                                                            __builtin_bit_cast(bfloat8, bu), acc[s][m], 0, 0, 0);
+                    else
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, au),
+                                                                           __builtin_bit_cast(half8, bu), acc[s][m], 0, 0, 0);
+                } else {
+                    const uintx2 bu{__builtin_amdgcn_perm(d.b[s][1].d[m >> 1], d.b[s][0].d[m >> 1], sel),
+                                    __builtin_amdgcn_perm(d.b[s][3].d[m >> 1], d.b[s][2].d[m >> 1], sel)};
+                    if constexpr (BF16)
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(shortx4, au),
+                                                                              __builtin_bit_cast(shortx4, bu), acc[s][m], 0, 0, 0);
+                    else
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, au),
+                                                                          __builtin_bit_cast(half4, bu), acc[s][m], 0, 0, 0);
+                }
             }
     };
 
@@ -493,8 +575,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
 
     if constexpr (DEPTH == 0) {
         // ablation: every tile's loads are issued only when the tile is computed
-        TileMeta m;
-        TileData<FPL, NS> d;
+        TileMeta<TW32> m;
+        TileData<FPL, NS, QR> d;
         for (int tt = tb; tt < te; ++tt) {
             load_meta(tt, m);
             issue(m, d, 0);
@@ -507,8 +589,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
         // tile waits for every load issued before them.  They are therefore requested DEPTH+1 tiles
         // before the rows they address (tile tt+2*DEPTH+1 while tile tt is multiplied), so that the
         // wait leaves the rows of the DEPTH tiles issued since then in flight.
-        TileMeta meta[R];
-        TileData<FPL, NS> data[R];
+        TileMeta<TW32> meta[R];
+        TileData<FPL, NS, QR> data[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) load_meta(tb + r, meta[r]);
 #pragma unroll
@@ -532,7 +614,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void spmm_tiles_kernel(
                     fetch_staged(data[r], r);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                const uintx2 au = operand_a(data[r]);
+                const OperandA au = operand_a(data[r]);
                 if constexpr (FETCH != kFetchLane) __builtin_amdgcn_sched_barrier(0);
                 const int s = (r + DEPTH) % R;            // slot of tile tt+DEPTH
                 issue(meta[s], data[s], s);
@@ -552,6 +634,14 @@ void launch_one(const ExecParams& p, hipStream_t stream) {
         if (p.lds) {
             hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, FETCH, TAIL, BF16, true>), grid, block, 0, stream, p.rwo,
                                p.tco, p.a2b, p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items,
+                               p.n_blocks, p.N, p.store_mode);
+            return;
+        }
+    }
+    if constexpr (FETCH == kFetchSpan && (DEPTH == 1 || DEPTH == 2)) {
+        if (p.tw32) {
+            hipLaunchKernelGGL((spmm_tiles_kernel<FPL, NS, DEPTH, ADDR, FETCH, TAIL, BF16, false, true>), grid, block, 0, stream,
+                               p.rwo, p.tco, p.a2b, p.bits, p.vals, p.perm_pad, p.items, p.B, p.B_hot, p.C, p.ws, p.n_items,
                                p.n_blocks, p.N, p.store_mode);
             return;
         }

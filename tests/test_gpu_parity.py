@@ -785,7 +785,65 @@ def test_paper_geometry_8x8_format_and_closed_form_size():
         acc.acc_spmm_destroy(plan)
 
 
-@pytest.mark.parametrize("WH,TW", [(16, 32), (32, 16), (64, 16), (32, 32), (8, 16)])
+@pytest.mark.parametrize("N", [16, 32, 64, 128, 256, 512, 1, 7, 30, 36, 100, 200, 136, 640])
+@pytest.mark.parametrize("lb", [acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON])
+def test_tiles_of_width_32_at_all_widths(N, lb):
+    """Plans with 16 x 32 tiles (the 32-deep matrix instruction): the five arrays equal the oracle's
+    encoding of that geometry and every element of C is within tolerance, for every lane width, masked
+    tails, one and two slabs per wave, split windows, and dense rows whose bytes are all ones."""
+    rng = np.random.default_rng(1000 + N + lb)
+    M, K = 333, 700
+    rowptr, colidx, vals = random_csr(rng, M, K, 0.05)
+    rows = [colidx[rowptr[i]:rowptr[i + 1]].tolist() for i in range(M)]
+    rows[40] = np.sort(rng.choice(K, 650, replace=False)).tolist()      # heavy: its window is split
+    for i in range(96, 112):                                             # one window of full 16 x 32 tiles
+        rows[i] = list(range(100, 100 + 96))
+    rows[200] = []
+    rowptr, colidx, _ = csr_from_rows(rows)
+    vals = f16(rng.uniform(-1, 1, len(colidx)))
+    B = f16(rng.standard_normal((K, N)))
+    plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
+                                acc.make_options(tile_width=32, load_balance=lb, max_tiles_per_item=4))
+    try:
+        st = acc.acc_spmm_plan_stats(plan)
+        assert st["tile_width"] == 32 and (st["num_split_windows"] >= 1) == (lb == acc.ACC_SPMM_ON)
+        check_format(plan, rowptr, colidx, vals, 16, 32)
+        C = run_spmm(plan, B, M, N)
+        check_against_oracle(rowptr, colidx, vals, B, C)
+        np.testing.assert_array_equal(C, run_spmm(plan, B, M, N))        # fixed summation order
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg,shrink", [(2, 6), (3, 6), (4, 4), (5, 7)])
+@pytest.mark.parametrize("value_type", ["f16", "bf16"])
+def test_tiles_of_width_32_on_the_workloads(cfg, shrink, value_type):
+    """16 x 32 tiles on shrunk workloads with the library's default decisions (reordering, column
+    order, load balancing), both value types, both pipeline depths, both orders of B."""
+    w = wl.config(cfg, shrink)
+    vals, B = w.vals, w.B
+    if value_type == "bf16":
+        rng = np.random.default_rng(cfg)
+        vals = bf16(rng.uniform(-1, 1, w.nnz) * 2.0 ** rng.integers(-20, 20, w.nnz))
+        B = bf16(rng.standard_normal((w.K, w.N)))
+    vt = acc.ACC_SPMM_BF16 if value_type == "bf16" else acc.ACC_SPMM_FP16
+    for depth, column_order, operand_order in ((0, acc.ACC_SPMM_AUTO, 0), (1, acc.ACC_SPMM_ON, 0), (2, acc.ACC_SPMM_ON, 1),
+                                               (2, acc.ACC_SPMM_OFF, 0)):
+        if operand_order == 1 and w.M != w.K:
+            continue
+        plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, vals,
+                                    acc.make_options(tile_width=32, value_type=vt, pipeline_depth=depth,
+                                                     column_order=column_order, operand_order=operand_order))
+        try:
+            check_format(plan, w.rowptr, w.colidx, vals, 16, 32, operand_order)
+            in_plan_order = operand_order == 1 and acc.acc_spmm_plan_stats(plan)["column_order_applied"] == 1
+            C = run_spmm(plan, _permuted(plan, B) if in_plan_order else B, w.M, w.N)
+            check_against_oracle(w.rowptr, w.colidx, vals, B, C, value_type=value_type)
+        finally:
+            acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("WH,TW", [(32, 16), (64, 16), (32, 32), (8, 16)])
 def test_other_tile_geometries_build_the_oracles_format(WH, TW):
     """Window heights and tile widths the execute kernel does not run: the five arrays still equal
     the oracle's encoding of the same geometry byte for byte, the statistics count that format, and

@@ -174,7 +174,8 @@ typedef struct {
     double t_column_order_s;
     int32_t dendrogram_on_device; /* 1: Step I of the reordering ran in its device form          */
     int32_t pad_;
-    int64_t dendrogram_rounds;    /* rounds of that form (0 for the host form)                  */
+    int64_t dendrogram_rounds;    /* rounds of the device form, those before a handover to the  */
+                                  /* host form included (0 if the host form was asked for)      */
 } acc_spmm_stats;
 
 /* Arrays acc_spmm_plan_export can copy out (element type, element count). */

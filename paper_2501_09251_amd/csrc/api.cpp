@@ -166,7 +166,6 @@ void choose_row_order(Plan& P, int64_t M, int64_t K, int64_t nnz, const int32_t*
                 graph.adj.release();
                 graph.ptr.release();
                 info.on_device = false;
-                info.rounds = 0;
                 complete = build_dendrogram_host(M, host_graph.ptr, host_graph.adj, opt.segment_length, budget, P.parent, seq,
                                                  seg_start, &info.work_ratio);
             } else {

@@ -27,6 +27,9 @@
 // endpoints are mapped to their present roots when the list is read.  The lists of the vertices
 // that one round merges into one target are stored as one chunk; a target's chunks are found
 // through a chain of small directory blocks.
+#include <algorithm>
+#include <chrono>
+
 #include "device_util.h"
 
 namespace accspmm {
@@ -961,17 +964,19 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     // Rounds are enqueued in groups without waiting; the control block is read back after each group.
     int group = 4;
     int status = -1;
-    long long large_before = 0, rounds_before = 0, pos_before = 0, launched = 0;
-    constexpr double kMaxRemainingRounds = 300000.0;   // some twenty seconds of rounds
+    long long rounds_before = 0, pos_before = 0, launched = 0;
+    // what the sequential host form needs for the whole graph, roughly (it measured 19 ns per graph entry on
+    // 500 M entries and less on graphs that fit the caches), and the least time worth a change of form
+    const double host_estimate_s = std::max(25e-9 * (double)graph_size, 0.25);
     const int64_t max_groups = 4 * M + 64;     // every round advances by at least one vertex
     for (int64_t gi = 0; gi < max_groups && status < 0; ++gi) {
         // block sizes follow what the last group of rounds looked like: large rounds sort in the commit
         // kernel; the preparation handles two slots per thread
         const bool wide = h.P > kQuadratic;
         const bool wide_prepare = h.P > 512;
-        large_before = h.large_slots;
         rounds_before = h.rounds;
         pos_before = h.pos;
+        const auto group_start = std::chrono::steady_clock::now();
         for (int r = 0; r < group; ++r, ++launched) {
             const DS& cur = (launched & 1) ? d_odd : d;
             const DS& prev = (launched & 1) ? d : d_odd;
@@ -990,11 +995,15 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
         else if (h.pos >= M) {
             status = (work_limit > 0 && h.work_at_last > work_limit) ? kDendrogramOverBudget : kDendrogramDone;
         } else if (work_limit > 0 && h.work > work_limit) status = kDendrogramOverBudget;
-        else if (h.rounds >= 1024) {
-            // crawling: at the rate of the last group the rest would take more rounds than the host form
-            // needs time for (chains of vertices that each depend on the one before, as in banded matrices)
-            const double rate = (double)(h.pos - pos_before) / (double)std::max<long long>(1, h.rounds - rounds_before);
-            if ((double)(M - h.pos) / std::max(rate, 1e-3) > kMaxRemainingRounds) status = kDendrogramUseHost;
+        else if (h.rounds >= 256) {
+            // crawling: at the pace of the last group of rounds the rest would take longer than the host form
+            // needs for everything (chains of vertices that each depend on the one before, as in banded
+            // matrices, where a round commits one or two vertices)
+            const double group_s = std::chrono::duration<double>(std::chrono::steady_clock::now() - group_start).count();
+            const double group_rounds = (double)std::max<long long>(1, h.rounds - rounds_before);
+            const double per_round = (double)(h.pos - pos_before) / group_rounds;
+            const double rest_s = (double)(M - h.pos) / std::max(per_round, 1e-3) * (group_s / group_rounds);
+            if (rest_s > host_estimate_s) status = kDendrogramUseHost;
         }
         if (group < 64) group *= 2;
     }

@@ -638,6 +638,22 @@ def test_dendrogram_rounds_on_special_graphs():
         np.testing.assert_array_equal(host_parent, parent, err_msg=name)
 
 
+def test_dendrogram_of_a_banded_matrix_falls_back_to_the_host_form():
+    """A chain: every vertex's decision depends on its predecessor's, so a round commits one or two
+    vertices.  The device form notices that the rest would take longer than the sequential form
+    needs for the whole graph and hands over; the result is the oracle's either way."""
+    M = 1 << 17
+    offs = np.array([-4, -3, -2, -1, 1, 2, 3, 4])
+    cols = np.arange(M, dtype=np.int64)[:, None] + offs[None, :]
+    ok = (cols >= 0) & (cols < M)
+    rowptr = np.zeros(M + 1, np.int32)
+    np.cumsum(ok.sum(1), out=rowptr[1:])
+    colidx = cols[ok].astype(np.int32)
+    parent, st = _dendrogram_of(rowptr, colidx)
+    assert st["dendrogram_on_device"] == 0 and st["dendrogram_rounds"] >= 256
+    np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0])
+
+
 def test_linearity_in_B_exact_on_small_integers():
     rng = np.random.default_rng(5)
     M = K = 200

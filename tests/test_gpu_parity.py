@@ -135,10 +135,12 @@ def test_all_widths_with_and_without_load_balancing(N, lb):
 
 
 @pytest.mark.parametrize("N", [32, 128, 256, 36, 200])
-def test_every_kernel_variant(N):
-    """All pipeline depths (0 = no prefetch), both store policies and both ways of fetching
-    the packed values give the same, correct C."""
-    w = wl.config(5, 9)
+@pytest.mark.parametrize("cfg,shrink", [(5, 9), (3, 7)])
+def test_every_kernel_variant(N, cfg, shrink):
+    """All pipeline depths (0 = no prefetch), both store policies and the three ways of fetching
+    the packed values give the same, correct C; on sparse tiles (one feature slab per wave) and on
+    dense ones (two)."""
+    w = wl.config(cfg, shrink)
     B = wl.dense(w.K, N, 77, "normal", 0.0, 1.0)
     ref = None
     for depth in (0, 1, 2, 3):
@@ -192,11 +194,13 @@ def test_lds_staging_gives_the_same_result(N):
 
 
 @pytest.mark.parametrize("fetch", [0, 1, 2, 3])
-@pytest.mark.parametrize("N", [16, 64, 128, 512])
+@pytest.mark.parametrize("N", [16, 64, 128, 512, 17, 50, 100, 200, 640])
 def test_dense_tiles_at_odd_value_offsets(fetch, N):
     """Full 16x16 tiles whose packed values start at an odd index (a one-entry first tile),
     tiles with more than 128 and more than 254 values, and a ragged last tile: the cases that
-    decide how many 64-dword chunks the cooperative value fetch reads."""
+    decide how many 64-dword chunks the cooperative value fetch reads.  Plans with dense tiles
+    are also the ones whose waves take two feature slabs each: the widths cover that shape with
+    and without a masked tail at every lane width."""
     rng = np.random.default_rng(N)
     rows = [[0]] + [list(range(40)) for _ in range(15)]           # window 0: 1 + 15*16, 240, 120 entries
     rows += [list(range(40)) for _ in range(16)]                  # window 1: 256, 256, 128
@@ -733,18 +737,23 @@ def test_wide_matrix_uses_64bit_row_offsets():
 # (K, N): B of 4 GiB or more, or K >= 2^24, makes execute address rows of B with 64-bit offsets.
 # The widths cover every lane width of that addressing mode: 2, 4 and 8 features per lane, one and
 # two feature slabs per wavefront, whole slabs and masked tails.
+@pytest.mark.parametrize("dense", [False, True])
 @pytest.mark.parametrize("K,N", [((1 << 24) + 64, 30), ((1 << 24) + 64, 36), ((1 << 24) + 64, 100),
                                  ((1 << 24) + 64, 128), (1 << 23, 256), (1 << 23, 512)])
-def test_wide_addressing_at_every_lane_width(K, N):
+def test_wide_addressing_at_every_lane_width(K, N, dense):
     """The 64-bit row-offset variants of the tile kernel at the widths real calls use (16-byte
     lanes, two slabs per wave), with both ways of fetching the packed values, all pipeline depths,
-    split windows, and columns at both ends of K; every element of C against the oracle."""
+    split windows, and columns at both ends of K; every element of C against the oracle.  dense: all
+    rows of a window share their columns, so that tiles are full and waves take two slabs each."""
     rng = np.random.default_rng(N)
     M = 301
     rows = []
+    shared = []
     for i in range(M):
         n = 330 if i == 37 else 24                       # one heavy row: its window is split
-        cols = set(rng.integers(0, K, n).tolist()) | {K - 1 - i, i, (K // 2) + i}
+        if dense and i % 16 == 0:
+            shared = rng.integers(0, K, 72).tolist() + [K - 1 - i, i, (K // 2) + i]
+        cols = set(shared) if dense and i != 37 else set(rng.integers(0, K, n).tolist()) | {K - 1 - i, i, (K // 2) + i}
         rows.append(sorted(cols))
     rowptr, colidx, _ = csr_from_rows(rows)
     vals = f16(rng.uniform(-1, 1, len(colidx)))
@@ -759,11 +768,13 @@ def test_wide_addressing_at_every_lane_width(K, N):
         for depth in (0, 1, 2, 3):
             plan = acc.acc_spmm_plan_ex(M, K, len(colidx), rowptr, colidx, vals,
                                         acc.make_options(load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=4,
+                                                         reorder=acc.ACC_SPMM_OFF,
                                                          value_fetch=fetch, pipeline_depth=depth,
                                                          no_prefetch=int(depth == 0),
                                                          column_order=acc.ACC_SPMM_OFF))   # B read in place
             try:
-                assert acc.acc_spmm_plan_stats(plan)["num_split_windows"] >= 1
+                st = acc.acc_spmm_plan_stats(plan)
+                assert st["num_split_windows"] >= 1 and (st["mean_nnz_per_tile"] >= 24.0) == dense
                 if first is None:
                     check_format(plan, rowptr, colidx, vals)
                 buf = torch.full((M * N + 4096,), float("nan"), dtype=torch.float32, device=dev)

@@ -955,6 +955,46 @@ def test_plan_survives_a_round_trip_through_a_file(tmp_path):
         assert e.value.code in (-1, -3)
 
 
+def test_plan_with_tiles_of_width_32_through_a_file_and_the_other_execute_calls(tmp_path):
+    """A 16 x 32 plan saved and loaded gives the same C bit for bit; the entry point that allocates
+    nothing and the 16-bit-C call run it too; the sampled dense-dense product refuses it."""
+    w = wl.config(2, 6)
+    opt = acc.make_options(tile_width=32, load_balance=acc.ACC_SPMM_ON, max_tiles_per_item=8, column_order=acc.ACC_SPMM_ON,
+                           keep_entry_map=1)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, opt)
+    path = str(tmp_path / "plan32.bin")
+    try:
+        assert acc.acc_spmm_plan_stats(plan)["num_split_windows"] >= 1
+        acc.acc_spmm_plan_save(plan, path)
+        twin = acc.acc_spmm_plan_load(path)
+        try:
+            assert acc.acc_spmm_plan_stats(twin) == acc.acc_spmm_plan_stats(plan)
+            for N in (128, 40):
+                B = wl.dense(w.K, N, 6, "normal", 0.0, 1.0)
+                C = run_spmm(plan, B, w.M, N)
+                check_against_oracle(w.rowptr, w.colidx, w.vals, B, C)
+                np.testing.assert_array_equal(run_spmm(twin, B, w.M, N), C)
+                dev = torch.device("cuda:0")
+                Bd = torch.from_numpy(B.view(np.int16)).to(dev)
+                Cs = torch.full((w.M, N), float("nan"), dtype=torch.float32, device=dev)
+                acc.acc_spmm_execute_static(twin, Bd, N, Cs, torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(Cs.cpu().numpy(), C)
+                C16 = torch.zeros((w.M, N), dtype=torch.float16, device=dev)
+                acc.acc_spmm_execute_c16(plan, Bd, N, C16, torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(C16.cpu().numpy(), C.astype(np.float16))
+            X = torch.zeros((w.M, 64), dtype=torch.float16, device="cuda")
+            out = torch.zeros(w.nnz, dtype=torch.float32, device="cuda")
+            with pytest.raises(acc.AccSpmmError) as e:
+                acc.acc_spmm_sddmm(plan, X, X, 64, out, 0, None)
+            assert e.value.code == -3
+        finally:
+            acc.acc_spmm_destroy(twin)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 def test_execute_can_be_captured_in_a_hip_graph():
     """After one eager call (which allocates the plan's buffers), execute only enqueues kernels:
     captured into a graph and replayed with new contents of B, with eager work between the

@@ -4,6 +4,7 @@
 #include <chrono>
 #include <cstring>
 #include <new>
+#include <thread>
 
 #include "internal.h"
 
@@ -85,39 +86,65 @@ namespace {
 
 // Checks the CSR (monotone row pointers, columns in range, no duplicate column in a row).
 // Rows whose columns are not ascending are sorted into `fixed_*`; returns true if that
-// copy must be used.
+// copy must be used.  One pass over the entries, rows split over a few threads; the error
+// reported is the one at the lowest row.
 bool validate_csr(int64_t M, int64_t K, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
                   const uint16_t* vals, std::vector<int32_t>& fixed_col, std::vector<uint16_t>& fixed_val) {
     if (rowptr[0] != 0) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr[0] must be 0");
     for (int64_t i = 0; i < M; ++i)
         if (rowptr[i + 1] < rowptr[i]) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr decreases at row " + std::to_string(i));
     if (rowptr[M] != nnz) fail(ACC_SPMM_ERR_INVALID_CSR, "csr_rowptr[M] != nnz");
-    bool unsorted = false;
-    for (int64_t p = 0; p < nnz; ++p)
-        if (colidx[p] < 0 || colidx[p] >= K)
-            fail(ACC_SPMM_ERR_INVALID_CSR, "column index out of range at entry " + std::to_string(p));
-    for (int64_t i = 0; i < M && !unsorted; ++i)
-        for (int64_t p = rowptr[i] + 1; p < rowptr[i + 1]; ++p)
-            if (colidx[p] <= colidx[p - 1]) { unsorted = true; break; }
-    if (unsorted) {
-        fixed_col.assign(colidx, colidx + nnz);
-        fixed_val.assign(vals, vals + nnz);
-        std::vector<std::pair<int32_t, uint16_t>> row;
-        for (int64_t i = 0; i < M; ++i) {
+    struct Finding {
+        int64_t bad_entry = -1;   // first entry whose column is out of range
+        bool unsorted = false;    // some row's columns are not strictly ascending
+    };
+    const int n_threads = nnz < (1 << 22) ? 1 : (int)std::min<unsigned>(16u, std::max(1u, std::thread::hardware_concurrency()));
+    std::vector<Finding> found(n_threads);
+    auto scan = [&](int k) {
+        // rows [r0, r1): equal shares of the entries
+        const int64_t e0 = nnz * k / n_threads, e1 = nnz * (k + 1) / n_threads;
+        const int64_t r0 = k == 0 ? 0 : std::upper_bound(rowptr, rowptr + M + 1, (int32_t)e0) - rowptr - 1;
+        const int64_t r1 = k == n_threads - 1 ? M : std::upper_bound(rowptr, rowptr + M + 1, (int32_t)e1) - rowptr - 1;
+        Finding f;
+        for (int64_t i = r0; i < r1 && f.bad_entry < 0; ++i) {
             const int64_t b = rowptr[i], e = rowptr[i + 1];
-            if (std::is_sorted(colidx + b, colidx + e)) continue;
+            for (int64_t p = b; p < e; ++p) {
+                const int32_t c = colidx[p];
+                if (c < 0 || c >= K) { f.bad_entry = p; break; }
+                if (p > b && c <= colidx[p - 1]) f.unsorted = true;
+            }
+        }
+        found[k] = f;
+    };
+    if (n_threads == 1) {
+        scan(0);
+    } else {
+        std::vector<std::thread> pool;
+        for (int k = 0; k < n_threads; ++k) pool.emplace_back(scan, k);
+        for (auto& th : pool) th.join();
+    }
+    bool unsorted = false;
+    for (const Finding& f : found) {
+        if (f.bad_entry >= 0) fail(ACC_SPMM_ERR_INVALID_CSR, "column index out of range at entry " + std::to_string(f.bad_entry));
+        unsorted = unsorted || f.unsorted;
+    }
+    if (!unsorted) return false;   // strictly ascending everywhere: no duplicates either
+    fixed_col.assign(colidx, colidx + nnz);
+    fixed_val.assign(vals, vals + nnz);
+    std::vector<std::pair<int32_t, uint16_t>> row;
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t b = rowptr[i], e = rowptr[i + 1];
+        if (!std::is_sorted(colidx + b, colidx + e)) {
             row.clear();
             for (int64_t p = b; p < e; ++p) row.push_back({colidx[p], vals[p]});
             std::stable_sort(row.begin(), row.end(), [](auto& x, auto& y) { return x.first < y.first; });
             for (int64_t p = b; p < e; ++p) { fixed_col[p] = row[p - b].first; fixed_val[p] = row[p - b].second; }
         }
-        colidx = fixed_col.data();
+        for (int64_t p = b + 1; p < e; ++p)
+            if (fixed_col[p] == fixed_col[p - 1])
+                fail(ACC_SPMM_ERR_INVALID_CSR, "duplicate column " + std::to_string(fixed_col[p]) + " in row " + std::to_string(i));
     }
-    for (int64_t i = 0; i < M; ++i)
-        for (int64_t p = rowptr[i] + 1; p < rowptr[i + 1]; ++p)
-            if (colidx[p] == colidx[p - 1])
-                fail(ACC_SPMM_ERR_INVALID_CSR, "duplicate column " + std::to_string(colidx[p]) + " in row " + std::to_string(i));
-    return unsorted;
+    return true;
 }
 
 // The graph build of the reordering numbers the 2*nnz directed edge keys, and their run heads,

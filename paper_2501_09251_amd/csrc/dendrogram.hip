@@ -49,12 +49,12 @@ constexpr int kMaxDense = 64;         // larger slots per round (each owns a wei
 // `capacity` descriptors of four words (chunk offset low, high, length, position).  A chunk's
 // position is the number of records in the target's earlier chunks: the target's list is its
 // adjacency followed by its chunks in that order, and a record of it is found by walking to the
-// block and bisecting the block's positions, so nothing has to be laid out again per round.  A target's first block holds 4
-// descriptors, each further one twice as many up to 1024 (a hub collects thousands of chunks; its
-// chain stays a dozen blocks long), and the newest block heads the chain.
+// block and bisecting the block's positions, so nothing has to be laid out again per round.  A
+// target's first block holds 4 descriptors, each further one twice as many up to 1024 (a hub
+// collects thousands of chunks; its chain stays a few dozen blocks long), and the newest block
+// heads the chain.
 // Blocks are referred to by their word offset divided by 4 (all block sizes are multiples of 4).
 constexpr int kDirHeader = 4, kDirDesc = 4, kDirFirstCap = 4, kDirMaxCap = 1024;
-constexpr long long kAdjacencyFlag = 1ll << 62;
 
 constexpr int kClassNone = 0, kClassSmall = 1, kClassLarge = 2, kClassSkipped = 3;
 
@@ -76,7 +76,7 @@ struct Ctl {                 // round control, lives in device memory
     int overflow;            // a memory pool was exhausted: nothing more is committed
     long long dir_used;      // words of the directory pool in use
     int keep_units, pad;     // units of the round whose kept lists are still to be copied
-    long long large_slots;   // larger slots prepared so far (the host sizes the prepare kernel's block by their rate)
+    long long large_slots;   // larger slots prepared so far (a statistic)
 };
 
 struct DS {
@@ -90,7 +90,6 @@ struct DS {
     long long* dsum;
     int32_t* head;        // per vertex: its newest directory block, -1 if none
     int32_t* tot_rec;     // per vertex: records in all its chunks
-    int32_t* tot_desc;    // per vertex: number of its chunks
     int32_t* dir;         // the directory pool
     long long dir_cap;    // its size in words
     Rec* arena;
@@ -160,7 +159,7 @@ __device__ __forceinline__ Best best_wave_reduce(Best b) {
 
 __global__ void init_state_kernel(long long M, const long long* __restrict__ gptr, const int32_t* __restrict__ order,
                                   int32_t* idx, int32_t* parent, int32_t* up, long long* dsum, int32_t* head,
-                                  int32_t* slot_of, int32_t* tot_rec, int32_t* tot_desc) {
+                                  int32_t* slot_of, int32_t* tot_rec) {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
     idx[order[i]] = (int32_t)i;
@@ -170,7 +169,6 @@ __global__ void init_state_kernel(long long M, const long long* __restrict__ gpt
     head[i] = -1;
     slot_of[i] = -1;
     tot_rec[i] = 0;
-    tot_desc[i] = 0;
 }
 
 __global__ void degree_keys_kernel(long long M, const long long* __restrict__ gptr, uint32_t* key, int32_t* id) {
@@ -584,7 +582,6 @@ __device__ __forceinline__ long long append_chunk(const DS& d, int32_t target, l
     w[3] = d.tot_rec[target];
     blk[1] = c + 1;
     d.tot_rec[target] += (int32_t)total;
-    d.tot_desc[target] += 1;
     return base;
 }
 
@@ -884,10 +881,10 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     if (two_m >= ((int64_t)1 << 31)) return kDendrogramUseHost;
 
     Scratch tmp;
-    DevBuf<int32_t> d_order, d_idx, d_parent, d_up, d_head, d_slot_of, d_tot_rec, d_tot_desc;
+    DevBuf<int32_t> d_order, d_idx, d_parent, d_up, d_head, d_slot_of, d_tot_rec;
     DevBuf<long long> d_dsum;
     d_order.alloc(M); d_idx.alloc(M); d_parent.alloc(M); d_up.alloc(M); d_head.alloc(M); d_slot_of.alloc(M);
-    d_tot_rec.alloc(M); d_tot_desc.alloc(M);
+    d_tot_rec.alloc(M);
     d_dsum.alloc(M);
     {   // visiting order: stable sort of the ids by degree
         DevBuf<uint32_t> key, key_sorted;
@@ -901,14 +898,17 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     }
     hipLaunchKernelGGL(init_state_kernel, dim3(blocks_for(M, 256)), dim3(256), 0, 0, (long long)M,
                        reinterpret_cast<const long long*>(g.ptr.p), d_order.p, d_idx.p, d_parent.p, d_up.p, d_dsum.p,
-                       d_head.p, d_slot_of.p, d_tot_rec.p, d_tot_desc.p);
+                       d_head.p, d_slot_of.p, d_tot_rec.p);
     ACC_HIP(hipGetLastError());
 
     // memory pools
     // words: a first block per target (16 words); every further block doubles, so a target's blocks hold
     // at most twice its chunks (3 words each) plus headers; targets and chunks are at most M each
     const int64_t dir_cap = 36 * M + 8192;
-    const int64_t arena_cap = 3 * two_m + M + 1024;
+    // list lengths are 32-bit: a vertex's records are its adjacency (fewer than M) plus what lies in the
+    // arena, so an arena of fewer than 2^31 - M records keeps every length in range (a graph that needs
+    // more exhausts the pool and goes to the host form)
+    const int64_t arena_cap = std::min<int64_t>(3 * two_m + M + 1024, ((int64_t)1 << 31) - M - 1024);
     const int64_t cand_cap = two_m + 1024;
     const int64_t unit_cap = two_m / kUnit + kSlots + 16;
     const int n_dense = (int)std::max<int64_t>(1, std::min<int64_t>(kMaxDense, ((int64_t)4 << 30) / (4 * M)));
@@ -939,7 +939,7 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     d.M = M; d.two_m = two_m;
     d.gptr = reinterpret_cast<const long long*>(g.ptr.p); d.gadj = g.adj.p; d.order = d_order.p; d.idx = d_idx.p;
     d.parent = d_parent.p; d.up = d_up.p; d.dsum = d_dsum.p; d.head = d_head.p;
-    d.tot_rec = d_tot_rec.p; d.tot_desc = d_tot_desc.p;
+    d.tot_rec = d_tot_rec.p;
     d.dir = dir.p; d.dir_cap = dir_cap;
     d.arena = arena.p; d.arena_cap = arena_cap; d.ctl = ctl.p; d.slot_of = d_slot_of.p;
     d.s_v = sI[0].p; d.s_nrec = sI[1].p; d.s_class = sI[2].p; d.s_dense = sI[3].p;

@@ -92,6 +92,29 @@ def test_invalid_input_is_reported_not_crashed():
         assert code == expect and "2^30" in msg
 
 
+def test_invalid_input_in_a_large_matrix_names_the_first_offence():
+    """Matrices of 2^22 entries or more are checked by several threads, each over a share of the rows:
+    the error still names the lowest offending entry, and a duplicate is found wherever it sits."""
+    M, K, per_row = 1 << 19, 1 << 20, 10
+    rng = np.random.default_rng(4)
+    cols = np.sort(rng.choice(K, per_row, replace=False)).astype(np.int32)
+    colidx = np.tile(cols, M)
+    rowptr = (np.arange(M + 1, dtype=np.int64) * per_row).astype(np.int32)
+    vals = np.zeros(len(colidx), np.uint16)
+    assert len(colidx) >= 1 << 22
+    for where in (17, len(colidx) // 2 + 3, len(colidx) - 5):
+        bad = colidx.copy()
+        bad[where] = K
+        bad[len(colidx) - 1] = -7                                   # a later offence must not be the one reported
+        assert _plan_error(M, K, rowptr, bad, vals) == -2
+        assert f"entry {where}" in acc.acc_spmm_last_error()[1]
+    for row in (0, M // 3, M - 1):
+        dup = colidx.copy()
+        dup[row * per_row + 4] = dup[row * per_row + 3]
+        assert _plan_error(M, K, rowptr, dup, vals) == -2
+        assert f"in row {row}" in acc.acc_spmm_last_error()[1]
+
+
 @pytest.mark.skipif(_has_gpu(), reason="only meaningful on a machine without a GPU")
 def test_no_gpu_means_a_loud_error_not_a_fallback():
     code = _plan_error(2, 2, [0, 1, 2], [0, 1], np.zeros(2, np.uint16))

@@ -658,6 +658,30 @@ def test_dendrogram_of_a_banded_matrix_falls_back_to_the_host_form():
     np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0])
 
 
+def test_unsorted_rows_in_a_large_matrix():
+    """Input rows need not be sorted; in a matrix large enough for the threaded input check, rows
+    with descending columns in every thread's share give the result of the sorted matrix."""
+    M, K, per_row, N = 1 << 19, 1 << 16, 9, 32
+    rng = np.random.default_rng(12)
+    colidx = np.sort(rng.integers(0, K // per_row, (M, per_row)) + np.arange(per_row) * (K // per_row), axis=1).astype(np.int32)
+    vals = f16(rng.uniform(-1, 1, (M, per_row)))
+    flipped = rng.random(M) < 0.3
+    given_c, given_v = colidx.copy(), vals.copy()
+    given_c[flipped] = given_c[flipped, ::-1]
+    given_v[flipped] = given_v[flipped, ::-1]
+    rowptr = (np.arange(M + 1, dtype=np.int64) * per_row).astype(np.int32)
+    assert M * per_row >= 1 << 22 and flipped[: M // 16].any() and flipped[-M // 16:].any()
+    B = f16(rng.standard_normal((K, N)))
+    plan = acc.acc_spmm_plan_ex(M, K, M * per_row, rowptr, given_c.ravel(), given_v.ravel(),
+                                acc.make_options(reorder=acc.ACC_SPMM_OFF))
+    try:
+        C = run_spmm(plan, B, M, N)
+        rows = np.unique(np.concatenate([np.arange(40), np.flatnonzero(flipped)[:200], rng.integers(0, M, 300), np.arange(M - 40, M)]))
+        check_against_oracle(rowptr, colidx.ravel(), vals.ravel(), B, C, rows=rows)
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
 def test_linearity_in_B_exact_on_small_integers():
     rng = np.random.default_rng(5)
     M = K = 200

@@ -613,7 +613,8 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     __shared__ uint8_t inv[kSlots], head[kSlots], flag[kSlots];
     __shared__ int16_t pos_of_slot[kSlots], hpos[kSlots];
     __shared__ int32_t tg[kQuadratic], want[kQuadratic];
-    __shared__ int cut_sh, overflow_sh;
+    __shared__ int cut_sh, overflow_sh, n_large_sh;
+    __shared__ int16_t large_list[kMaxDense];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     Ctl* const ctl = d.ctl;
     const int n_prepared = ctl->n_prepared, n_eval = ctl->n_eval;
@@ -623,24 +624,11 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     int n2 = 64;
     while (n2 < n_eval) n2 <<= 1;
     if (t < kRowWords) mmask[t] = 0;
-    if (t == 0) { cut_sh = n_eval; overflow_sh = 0; }
+    if (t == 0) { cut_sh = n_eval; overflow_sh = 0; n_large_sh = 0; }
     for (int i = t; i < n2; i += T) { inv[i] = 0; flag[i] = i < n_eval ? (uint8_t)d.row_dirty[i] : (uint8_t)0; }
     __syncthreads();
-    // results of the larger slots from their blocks' partial results; who merges
-    for (int i = t; i < n2; i += T) {
-        key[i] = ~0ull;
-        val[i] = 0;
-        if (i < kQuadratic) { tg[i] = -1; want[i] = 0; }
-        if (i >= n_eval) continue;
-        if (d.s_class[i] == kClassLarge) {
-            Best all{kNoScore, kNoScore, -1};
-            const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
-            for (int u = u0; u < u0 + nu; ++u) best_join(all, Best{d.u_score[u], d.u_second[u], d.u_best[u]});
-            d.s_best[i] = all.r;
-            d.s_score[i] = all.s;
-            d.s_second[i] = all.second;
-            d.s_dv[i] = d.dsum[d.s_v[i]];
-        }
+    // a slot that merges: its key, its degree, and in a small round its target and what it keeps
+    auto merging_slot = [&](int i) {
         const int32_t best = d.s_best[i];
         if (best >= 0 && d.s_score[i] > 0) {
             atomicOr(&mmask[i >> 5], 1u << (i & 31));
@@ -653,8 +641,48 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
                 if (s > i && s < n_eval) inv[s] = 1;                          // (b), see below
             }
         }
+    };
+    // results of the larger slots from their blocks' partial results; who merges
+    constexpr int kUnitsInline = 128;
+    for (int i = t; i < n2; i += T) {
+        key[i] = ~0ull;
+        val[i] = 0;
+        if (i < kQuadratic) { tg[i] = -1; want[i] = 0; }
+        if (i >= n_eval) continue;
+        if (d.s_class[i] == kClassLarge) {
+            const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
+            if (nu > kUnitsInline) {      // a hub: left to a whole wavefront below
+                large_list[atomicAdd(&n_large_sh, 1)] = (int16_t)i;    // at most kMaxDense larger slots per round
+                continue;
+            }
+            Best all{kNoScore, kNoScore, -1};
+            for (int u = u0; u < u0 + nu; ++u) best_join(all, Best{d.u_score[u], d.u_second[u], d.u_best[u]});
+            d.s_best[i] = all.r;
+            d.s_score[i] = all.s;
+            d.s_second[i] = all.second;
+            d.s_dv[i] = d.dsum[d.s_v[i]];
+        }
+        merging_slot(i);
     }
     __syncthreads();
+    if (n_large_sh > 0) {     // hubs whose lists thousands of blocks walked: one wavefront reduces a slot's partial results
+        for (int q = wave; q < n_large_sh; q += T / 64) {
+            const int i = large_list[q];
+            Best all{kNoScore, kNoScore, -1};
+            const int u0 = d.s_unit0[i], nu = d.s_nunits[i];
+            for (int u = u0 + lane; u < u0 + nu; u += 64) best_join(all, Best{d.u_score[u], d.u_second[u], d.u_best[u]});
+            all = best_wave_reduce(all);
+            if (lane == 0) {
+                d.s_best[i] = all.r;
+                d.s_score[i] = all.s;
+                d.s_second[i] = all.second;
+                d.s_dv[i] = d.dsum[d.s_v[i]];
+                __threadfence_block();
+                merging_slot(i);
+            }
+        }
+        __syncthreads();
+    }
     // (b) an earlier slot merges into this slot's vertex
     if (!direct)
         for (int j = t; j < n_eval; j += T) {

@@ -618,7 +618,12 @@ __global__ __launch_bounds__(T) void commit_round_kernel(DS d) {
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     Ctl* const ctl = d.ctl;
     const int n_prepared = ctl->n_prepared, n_eval = ctl->n_eval;
-    if (n_prepared == 0) return;
+    if (n_prepared == 0) {
+        // a round enqueued after the last vertex had its turn: nothing was kept, and the next launch must
+        // not copy the last real round's lists again from the other set of per-slot arrays
+        if (t == 0) { ctl->last_cut = 0; ctl->keep_units = 0; }
+        return;
+    }
     const long long pos = ctl->pos;
     const bool direct = n_eval <= kQuadratic;
     int n2 = 64;
@@ -889,7 +894,7 @@ __device__ __forceinline__ void keep_lists(const DS& d, int b, int nthreads) {
     const int n_units = d.ctl->keep_units;
     for (int u = b; u < n_units; u += kKeepBlocks) {
         const int i = d.unit_slot[u];
-        if (i >= cut || !d.s_store[i]) continue;
+        if (i < 0 || i >= cut || !d.s_store[i]) continue;
         const int k = u - d.s_unit0[i];
         const int nt = d.s_nt[i];
         const Rec* src = d.cand + d.s_cand_off[i];
@@ -967,6 +972,9 @@ int build_dendrogram_on_device(const DeviceGraph& g, double work_budget, std::ve
     ctl.alloc(1);
     ACC_HIP(hipMemset(bits.p, 0, sizeof(uint32_t) * kSlots * kRowWords));
     ACC_HIP(hipMemset(row_dirty.p, 0, sizeof(int32_t) * kSlots));
+    ACC_HIP(hipMemset(unit_slot.p, 0, sizeof(int32_t) * 2 * (size_t)unit_cap));
+    for (auto& b : sI) ACC_HIP(hipMemset(b.p, 0, sizeof(int32_t) * 2 * kSlots));
+    for (auto& b : sL) ACC_HIP(hipMemset(b.p, 0, sizeof(long long) * 2 * kSlots));
     ACC_HIP(hipMemset(dense.p, 0, sizeof(uint32_t) * (size_t)n_dense * (size_t)M));
     Ctl h{};
     h.P = kSlots;

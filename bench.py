@@ -301,7 +301,8 @@ def run_workload(torch, acc, oracle, w, args, opt_kw, headline):
     torch.cuda.empty_cache()
 
     defaults = (args.reorder, args.load_balance, args.column_order) == ("auto", "auto", "auto") and not args.mtx \
-        and not args.shrink and not args.b_in_plan_order and not args.cap and not args.value_fetch
+        and not args.shrink and not args.b_in_plan_order and not args.cap and not args.value_fetch and not args.tile_width \
+        and not args.no_prefetch and not args.streaming_stores
     tm = measured_traffic(w.name) if defaults else None
     traffic = tm["fetch_bytes"] + tm["write_bytes"] if tm else None
     roofline = {
@@ -368,8 +369,10 @@ def main() -> int:
                     help="hand B over in the plan's column order (permuted once, outside the timed region) "
                          "instead of letting every step gather it")
     ap.add_argument("--c16", action="store_true", help="also time acc_spmm_execute_c16 (C rounded to 16 bits)")
-    ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2),
-                    help="0 library default, 1 per-lane value loads, 2 cooperative value fetch")
+    ap.add_argument("--value-fetch", type=int, default=0, choices=(0, 1, 2, 3),
+                    help="0 library default, 1 per-lane value loads, 2 cooperative value fetch, 3 one span load per lane")
+    ap.add_argument("--tile-width", type=int, default=0, choices=(0, 16, 32),
+                    help="condensed columns per tile (0 = library default 16; 32 runs the 32-deep matrix instruction)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-naive", action="store_true")
     ap.add_argument("--vendor", action="store_true",
@@ -398,7 +401,7 @@ def main() -> int:
     opt_kw = dict(reorder=mode[args.reorder], load_balance=mode[args.load_balance],
                   max_tiles_per_item=args.cap, keep_csr=0 if args.no_naive else 1,
                   no_prefetch=int(args.no_prefetch), streaming_stores=int(args.streaming_stores),
-                  value_fetch=args.value_fetch, column_order=mode[args.column_order],
+                  value_fetch=args.value_fetch, tile_width=args.tile_width, column_order=mode[args.column_order],
                   operand_order=int(args.b_in_plan_order))
 
     t0 = time.time()

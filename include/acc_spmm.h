@@ -104,7 +104,8 @@ typedef struct {
      * lanes exchange them across registers; 3 = every lane loads the twelve bytes around its
      * (consecutive) values at once; 0 = default: 3 for N <= 32; for 32 < N <= 64, 2 when the plan
      * has at least 24 entries per tile on average or at least 16384 tiles, else 1; for N > 64,
-     * 3 when the plan has at least 24 entries per tile on average, else 1.  (By the lane width the
+     * 3 when the plan has at least 24 entries per tile on average or fewer than 64 tiles per
+     * work item, else 1.  (By the lane width the
      * call uses: a width N that is not a multiple of 8 counts as the narrower class.) */
     int32_t value_fetch;
     /* The 16-bit floating-point type of csr_vals and of B: ACC_SPMM_FP16 (0, default) = IEEE

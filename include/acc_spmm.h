@@ -145,6 +145,13 @@ typedef struct {
      * result bit for bit.  fp16 plans, N = 32, 64, 128 or 384; other calls return
      * ACC_SPMM_ERR_UNSUPPORTED. */
     int32_t lds_staging;
+    /* Feature slabs (16 times the features per lane, 128 features at N >= 128) that one wavefront
+     * accumulates: 2 halves the reads of A and of the index words, 1 puts twice the wavefronts on
+     * the rows of B.  0 = default: 1 when the plan has fewer than 24 entries per tile on average and
+     * the call gathers the most used rows of B (a column order with B in the caller's order), else
+     * 2 where N spans an even number of slabs or more than three.  1 and 2 force it where the
+     * width allows (2 needs at least two slabs). */
+    int32_t slabs_per_wave;
 } acc_spmm_options;
 
 /* What a plan holds; filled by acc_spmm_plan_stats. */

@@ -53,6 +53,7 @@ class acc_spmm_options(ctypes.Structure):
         ("keep_entry_map", ctypes.c_int32),
         ("dendrogram_on_host", ctypes.c_int32),
         ("lds_staging", ctypes.c_int32),
+        ("slabs_per_wave", ctypes.c_int32),
     ]
 
 

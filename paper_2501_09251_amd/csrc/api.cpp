@@ -294,6 +294,7 @@ acc_spmm_plan_t* build_plan(int64_t M, int64_t K, int64_t nnz, const int32_t* ro
     if (opt.value_fetch < 0 || opt.value_fetch > 3) fail(ACC_SPMM_ERR_INVALID_ARG, "value_fetch must be 0, 1, 2 or 3");
     if (opt.dendrogram_on_host < 0 || opt.dendrogram_on_host > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "dendrogram_on_host must be 0 or 1");
     if (opt.lds_staging < 0 || opt.lds_staging > 1) fail(ACC_SPMM_ERR_INVALID_ARG, "lds_staging must be 0 or 1");
+    if (opt.slabs_per_wave < 0 || opt.slabs_per_wave > 2) fail(ACC_SPMM_ERR_INVALID_ARG, "slabs_per_wave must be 0, 1 or 2");
     if (opt.value_type != ACC_SPMM_FP16 && opt.value_type != ACC_SPMM_BF16)
         fail(ACC_SPMM_ERR_INVALID_ARG, "value_type must be ACC_SPMM_FP16 or ACC_SPMM_BF16");
 

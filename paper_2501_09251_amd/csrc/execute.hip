@@ -301,10 +301,13 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     const int slab_width = 16 * p.fpl;
     const int slabs = (N + slab_width - 1) / slab_width;
     // Two slabs per wave halve the reads of A and of the index words; one slab per wave with twice the waves
-    // keeps more rows of B in flight.  Measured at N = 256 and 512: one slab is 6-15 % faster on the sparse
-    // tiles of power-law inputs (B dominates the traffic), two slabs 8-10 % faster on dense tiles (stencil).
+    // keeps more rows of B in flight and needs fewer registers.  Measured at N = 256 and 512: one slab is 6-15 %
+    // faster on sparse tiles with the two-matrix addressing of a column order (balanced power-law inputs; that
+    // addressing costs registers), two slabs are 3-11 % faster on sparse tiles read in place and 8-15 % on dense tiles.
     const bool dense_tiles = plan.stats.mean_nnz_per_tile * 16.0 / f.TW >= 24.0;   // per 16 x 16 positions
-    p.ns = (dense_tiles && (slabs % 2 == 0 || slabs > 3)) ? 2 : 1;
+    p.ns = ((dense_tiles || p.addr != kAddrHot) && (slabs % 2 == 0 || slabs > 3)) ? 2 : 1;
+    if (plan.opt.slabs_per_wave == 1) p.ns = 1;
+    if (plan.opt.slabs_per_wave == 2 && slabs >= 2) p.ns = 2;
     p.grid_y = (slabs + p.ns - 1) / p.ns;
     p.tail = (int64_t)p.grid_y * p.ns * slab_width != N;
     if (!p.tail && p.ns == 2 && p.fpl != 8) p.tail = true;  // shape compiled only in its general form

@@ -170,3 +170,39 @@ def test_default_value_fetch_is_near_the_best_way_on_held_out_inputs():
             for plan in plans.values():
                 acc.acc_spmm_destroy(plan)
     assert not failures, "the default value fetch is more than 15 % slower than the best way:\n" + "\n".join(failures)
+
+
+def test_default_slabs_per_wave_is_near_the_better_shape_on_held_out_inputs():
+    """One or two feature slabs per wavefront at N = 256 and 512: both shapes are forced on inputs outside
+    the benchmark set.  (A first rule, two slabs for dense tiles only, failed here on the rectangular input;
+    the present one also takes two where B is read in place.)"""
+    failures = []
+    picked = {"rmat 2^21, quadrants .45/.22/.22/.11, labels as generated", "rmat 2^21, benchmark quadrants, scrambled labels",
+              "block model, communities of 16, p_in .6", "banded, 33 diagonals", "rectangular 2^19 x 2^21, heavy-tailed column use"}
+    for name, (M, K), (rowptr, colidx, vals) in _inputs():
+        if name not in picked:
+            continue
+        nnz = len(colidx)
+        plans = {f: acc.acc_spmm_plan_ex(M, K, nnz, rowptr, colidx, vals, acc.make_options(slabs_per_wave=f)) for f in (0, 1, 2)}
+        try:
+            for n in (256, 512):
+                print(f"[slabs] {name}: N={n}", flush=True)
+                B = torch.from_numpy(wl.dense(K, n, 31, "normal", 0.0, 1.0).view(np.int16)).cuda()
+                C = torch.empty((M, n), dtype=torch.float32, device="cuda")
+                stream = torch.cuda.current_stream().cuda_stream
+                ms = {}
+                for f, plan in plans.items():
+                    for _ in range(2):
+                        acc.acc_spmm_execute(plan, B, n, C, stream)
+                    torch.cuda.synchronize()
+                    ms[f] = float(np.median([sum(acc.acc_spmm_execute_timed(plan, B, n, C, stream)) for _ in range(7)]))
+                line = f"[slabs] {name}: N={n} ms one slab {ms[1]:.4f} two slabs {ms[2]:.4f} default {ms[0]:.4f}"
+                print(line, flush=True)
+                if ms[0] > 1.10 * min(ms[1], ms[2]) + SLACK_MS:
+                    failures.append(line)
+                del B, C
+                torch.cuda.empty_cache()
+        finally:
+            for plan in plans.values():
+                acc.acc_spmm_destroy(plan)
+    assert not failures, "the default slab count is more than 10 % slower than the better one:\n" + "\n".join(failures)

@@ -96,8 +96,9 @@ typedef struct {
      * (non-temporal) stores, the counterpart of the paper's write-through policy. */
     int32_t streaming_stores;
     /* Tiles of B rows kept in flight per wavefront while one tile is multiplied (1..3).
-     * 0 = default (3 for N = 128, 2 for N >= 256, 1 for N <= 64).  Ignored when no_prefetch
-     * is set. */
+     * 0 = default: 1 for N <= 64 and for plans with fewer than 64 tiles per work item; else 3
+     * where a wavefront takes one 128-feature slab and 2 where it takes two.  Ignored when
+     * no_prefetch is set. */
     int32_t pipeline_depth;
     /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its
      * own up-to-four values one by one; 2 = the wavefront loads the tile's values once and the

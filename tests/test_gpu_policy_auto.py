@@ -206,3 +206,39 @@ def test_default_slabs_per_wave_is_near_the_better_shape_on_held_out_inputs():
             for plan in plans.values():
                 acc.acc_spmm_destroy(plan)
     assert not failures, "the default slab count is more than 10 % slower than the better one:\n" + "\n".join(failures)
+
+
+def test_default_pipeline_depth_is_near_the_best_on_held_out_inputs():
+    """Tiles in flight per wavefront (ring depth 1, 2 or 3) at N = 64, 128 and 256: every depth is forced on
+    inputs outside the benchmark set, on which the defaults (3 for one 128-feature slab, 2 for two, 1 for
+    narrower lanes) were swept."""
+    failures = []
+    picked = {"rmat 2^21, quadrants .45/.22/.22/.11, labels as generated", "rmat 2^21, benchmark quadrants, scrambled labels",
+              "block model, communities of 256, p_in .08", "banded, 33 diagonals", "rectangular 2^19 x 2^21, heavy-tailed column use"}
+    for name, (M, K), (rowptr, colidx, vals) in _inputs():
+        if name not in picked:
+            continue
+        nnz = len(colidx)
+        plans = {f: acc.acc_spmm_plan_ex(M, K, nnz, rowptr, colidx, vals, acc.make_options(pipeline_depth=f)) for f in (0, 1, 2, 3)}
+        try:
+            for n in (64, 128, 256):
+                print(f"[depth] {name}: N={n}", flush=True)
+                B = torch.from_numpy(wl.dense(K, n, 31, "normal", 0.0, 1.0).view(np.int16)).cuda()
+                C = torch.empty((M, n), dtype=torch.float32, device="cuda")
+                stream = torch.cuda.current_stream().cuda_stream
+                ms = {}
+                for f, plan in plans.items():
+                    for _ in range(2):
+                        acc.acc_spmm_execute(plan, B, n, C, stream)
+                    torch.cuda.synchronize()
+                    ms[f] = float(np.median([sum(acc.acc_spmm_execute_timed(plan, B, n, C, stream)) for _ in range(7)]))
+                line = f"[depth] {name}: N={n} ms depth 1 {ms[1]:.4f} depth 2 {ms[2]:.4f} depth 3 {ms[3]:.4f} default {ms[0]:.4f}"
+                print(line, flush=True)
+                if ms[0] > 1.10 * min(ms[1], ms[2], ms[3]) + SLACK_MS:
+                    failures.append(line)
+                del B, C
+                torch.cuda.empty_cache()
+        finally:
+            for plan in plans.values():
+                acc.acc_spmm_destroy(plan)
+    assert not failures, "the default ring depth is more than 10 % slower than the best one:\n" + "\n".join(failures)

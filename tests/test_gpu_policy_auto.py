@@ -242,3 +242,32 @@ def test_default_pipeline_depth_is_near_the_best_on_held_out_inputs():
             for plan in plans.values():
                 acc.acc_spmm_destroy(plan)
     assert not failures, "the default ring depth is more than 10 % slower than the best one:\n" + "\n".join(failures)
+
+
+def test_auto_load_balancing_is_near_the_better_choice_on_held_out_inputs():
+    """Load balancing (Section 3.5) forced on and off against AUTO (on iff the imbalance measure of Eq. 3
+    exceeds the threshold) at N = 128 on all held-out inputs."""
+    failures = []
+    for name, (M, K), (rowptr, colidx, vals) in _inputs():
+        nnz = len(colidx)
+        print(f"[balance] {name}", flush=True)
+        B = torch.from_numpy(wl.dense(K, N, 31, "normal", 0.0, 1.0).view(np.int16)).cuda()
+        C = torch.empty((M, N), dtype=torch.float32, device="cuda")
+        ms, ibd, applied = {}, 0.0, 0
+        for lb in (acc.ACC_SPMM_OFF, acc.ACC_SPMM_ON, acc.ACC_SPMM_AUTO):
+            plan = acc.acc_spmm_plan_ex(M, K, nnz, rowptr, colidx, vals, acc.make_options(load_balance=lb))
+            try:
+                ms[lb] = _time_plan(plan, B, C, M)
+                if lb == acc.ACC_SPMM_AUTO:
+                    st = acc.acc_spmm_plan_stats(plan)
+                    ibd, applied = st["ibd"], st["load_balance_applied"]
+            finally:
+                acc.acc_spmm_destroy(plan)
+        line = (f"[balance] {name}: ms off {ms[acc.ACC_SPMM_OFF]:.4f} on {ms[acc.ACC_SPMM_ON]:.4f} auto {ms[acc.ACC_SPMM_AUTO]:.4f} "
+                f"(imbalance {ibd:.1f}, applied {applied})")
+        print(line, flush=True)
+        if ms[acc.ACC_SPMM_AUTO] > TOLERANCE * min(ms[acc.ACC_SPMM_OFF], ms[acc.ACC_SPMM_ON]) + SLACK_MS:
+            failures.append(line)
+        del B, C
+        torch.cuda.empty_cache()
+    assert not failures, "AUTO load balancing is more than 5 % slower than the better choice:\n" + "\n".join(failures)

@@ -1114,7 +1114,7 @@ def test_plans_release_their_device_memory():
 
 
 # -------------------------------------------------- random shapes x random options
-@pytest.mark.parametrize("block", range(6))
+@pytest.mark.parametrize("block", range(8))
 def test_randomised_shapes_and_options(block):
     """Seeded sweep over shapes (empty matrices, M != K, K below one tile, one heavy row, empty
     windows) and over every option, SpMM and SDDMM, each case against the oracle."""
@@ -1144,7 +1144,9 @@ def test_randomised_shapes_and_options(block):
                    operand_order=operand_order, value_fetch=int(rng.integers(0, 4)),
                    pipeline_depth=int(rng.integers(0, 4)), streaming_stores=int(rng.integers(0, 2)),
                    segment_length=int(rng.choice([0, 2, 37, 4096])), keep_csr=1, keep_entry_map=1,
-                   value_type=acc.ACC_SPMM_BF16 if use_bf16 else acc.ACC_SPMM_FP16)
+                   value_type=acc.ACC_SPMM_BF16 if use_bf16 else acc.ACC_SPMM_FP16,
+                   slabs_per_wave=int(rng.integers(0, 3)), tile_width=int(rng.choice([0, 0, 16, 32])))
+        wide_tiles = opt["tile_width"] == 32
         label = f"block {block} case {case}: M={M} K={K} nnz={nnz} N={N} {opt}"
         print(label, flush=True)
         plan = acc.acc_spmm_plan_ex(M, K, nnz, rowptr, colidx, vals, acc.make_options(**opt))
@@ -1162,6 +1164,8 @@ def test_randomised_shapes_and_options(block):
             Ns = int(rng.choice([32, 96, 128, 256]))
             X, Y = to_bits(rng.standard_normal((M, Ns))), to_bits(rng.standard_normal((K, Ns)))
             Y_given = _permuted(plan, Y) if in_plan_order and K > 0 else Y
+            if wide_tiles:                      # the sampled product runs plans with 16 x 16 tiles only
+                continue
             got = run_sddmm(plan, X, Y_given, nnz, Ns, 1)
             if nnz > 0:
                 check_sddmm(rowptr, colidx, vals, X, Y, got, 1, value_type=vt)

@@ -216,20 +216,53 @@ def acc_spmm_plan_ex(M, K, nnz, csr_rowptr, csr_colidx, csr_vals, options):
     return h
 
 
+_plan_shape = {}     # plan handle -> (M, K, nnz), for the size checks below
+
+
+def _shape_of(plan):
+    shape = _plan_shape.get(plan)
+    if shape is None:
+        st = acc_spmm_stats()
+        if load().acc_spmm_plan_stats(plan, ctypes.byref(st)) != 0:
+            return None
+        shape = _plan_shape[plan] = (int(st.M), int(st.K), int(st.nnz))
+    return shape
+
+
+def _check_operands(plan, B, N, C, c_bytes_per_value):
+    """The C ABI takes bare addresses and cannot know how large the caller's buffers are.  When they come as
+    tensors the binding can: a B or C smaller than the call's N needs is refused here instead of being read or
+    written past its end by the kernels."""
+    if not (hasattr(B, "numel") or hasattr(C, "numel")) or not isinstance(N, int) or N <= 0 or N > 65536:
+        return                            # widths out of range are the library's to refuse
+    shape = _shape_of(plan)
+    if shape is None:
+        return                            # not a plan: the library reports it
+    M, K, _ = shape
+    if hasattr(B, "numel") and B.numel() * B.element_size() < K * N * 2:
+        raise ValueError(f"B holds {B.numel() * B.element_size()} bytes, the call reads K x N x 2 = {K * N * 2}")
+    if hasattr(C, "numel") and C.numel() * C.element_size() < M * N * c_bytes_per_value:
+        raise ValueError(f"C holds {C.numel() * C.element_size()} bytes, the call writes M x N x {c_bytes_per_value} = "
+                         f"{M * N * c_bytes_per_value}")
+
+
 def acc_spmm_execute(plan, B, N, C, stream=None):
     """Enqueue C = A.B.  B, C: torch CUDA tensors or device addresses; stream: hipStream_t as int."""
+    _check_operands(plan, B, N, C, 4)
     if load().acc_spmm_execute(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
         _raise()
 
 
 def acc_spmm_execute_c16(plan, B, N, C, stream=None):
     """Enqueue C = A.B with C in the plan's 16-bit value type (fp32 accumulation, one rounding)."""
+    _check_operands(plan, B, N, C, 2)
     if load().acc_spmm_execute_c16(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
         _raise()
 
 
 def acc_spmm_execute_static(plan, B, N, C, stream=None):
     """acc_spmm_execute that allocates nothing: its temporary buffers live in the library's static device array."""
+    _check_operands(plan, B, N, C, 4)
     if load().acc_spmm_execute_static(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
         _raise()
 
@@ -239,6 +272,7 @@ STATIC_SCRATCH_BYTES = 64 << 20
 
 def acc_spmm_execute_timed(plan, B, N, C, stream=None):
     """Blocking execute; returns (tile kernel ms, combine kernel ms, B gather ms) from HIP events on `stream`."""
+    _check_operands(plan, B, N, C, 4)
     t, c, g = ctypes.c_float(), ctypes.c_float(), ctypes.c_float()
     if load().acc_spmm_execute_timed(plan, _dev_ptr(B), N, _dev_ptr(C), stream, ctypes.byref(t), ctypes.byref(c),
                                      ctypes.byref(g)) != 0:
@@ -284,6 +318,11 @@ def acc_spmm_update_values(plan, csr_vals, stream=None):
 
 
 def acc_spmm_sddmm(plan, X, Y, N, out, use_values=0, stream=None):
+    shape = _shape_of(plan) if isinstance(N, int) and 0 < N <= 65536 else None
+    if shape is not None:                 # tensors too small for the call are refused here (see _check_operands)
+        for name, t, need in (("X", X, shape[0] * N * 2), ("Y", Y, shape[1] * N * 2), ("out", out, shape[2] * 4)):
+            if hasattr(t, "numel") and t.numel() * t.element_size() < need:
+                raise ValueError(f"{name} holds {t.numel() * t.element_size()} bytes, the call needs {need}")
     if load().acc_spmm_sddmm(plan, _dev_ptr(X), _dev_ptr(Y), N, _dev_ptr(out), use_values, stream) != 0:
         _raise()
 
@@ -306,12 +345,14 @@ def acc_spmm_calibration_gather(table, rows, row_bytes, index, n_index, sink, si
 
 
 def acc_spmm_execute_csr_naive(plan, B, N, C, stream=None):
+    _check_operands(plan, B, N, C, 4)
     if load().acc_spmm_execute_csr_naive(plan, _dev_ptr(B), N, _dev_ptr(C), stream) != 0:
         _raise()
 
 
 def acc_spmm_destroy(plan):
     if plan:
+        _plan_shape.pop(plan, None)      # the address may be handed out again
         load().acc_spmm_destroy(plan)
 
 

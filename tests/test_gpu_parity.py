@@ -522,7 +522,7 @@ def test_update_values_keeps_the_plan(reorder):
 
 def test_sddmm_argument_errors():
     rowptr, colidx, vals = csr_from_rows([[0]])
-    X = torch.zeros(1, 48, dtype=torch.float16, device="cuda")
+    X = torch.zeros(1, 8192, dtype=torch.float16, device="cuda")        # large enough for every width tried
     out = torch.zeros(1, device="cuda")
     plan = acc.acc_spmm_plan(1, 1, 1, rowptr, colidx, vals)
     try:
@@ -1281,5 +1281,26 @@ def test_full_size_sddmm_sampled_rows(cfg):
         ok, ratio = oracle.within_bound(got[pick], ref, bound)
         print(f"[full-size sddmm] worst error/limit = {ratio:.3g}", flush=True)
         assert ok
+    finally:
+        acc.acc_spmm_destroy(plan)
+
+
+def test_binding_refuses_tensors_smaller_than_the_call_needs():
+    """The C ABI takes bare addresses; the Python binding, which sees tensors, refuses a B or C too small for
+    the N of the call before any kernel could read or write past their end."""
+    rowptr, colidx, vals = csr_from_rows([[0, 3], [1], [2, 3]])
+    plan = acc.acc_spmm_plan(3, 4, 5, rowptr, colidx, vals)
+    try:
+        B = torch.zeros(4, 32, dtype=torch.float16, device="cuda")
+        C = torch.zeros(3, 32, device="cuda")
+        acc.acc_spmm_execute(plan, B, 32, C, None)
+        for call in (acc.acc_spmm_execute, acc.acc_spmm_execute_static, acc.acc_spmm_execute_timed):
+            with pytest.raises(ValueError):
+                call(plan, B, 128, C, None)                              # both too small for N = 128
+            with pytest.raises(ValueError):
+                call(plan, torch.zeros(4, 128, dtype=torch.float16, device="cuda"), 128, C, None)
+        with pytest.raises(ValueError):
+            acc.acc_spmm_execute_c16(plan, B, 32, torch.zeros(3, 16, dtype=torch.float16, device="cuda"), None)
+        torch.cuda.synchronize()
     finally:
         acc.acc_spmm_destroy(plan)

@@ -95,6 +95,14 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2501_09251_amd.build` "
                           "(there is no CPU fallback)")
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 under the same soname as the system's.
+    # Whichever is loaded first serves both; if this library pulled in the system copy before torch is
+    # imported, torch would run its bundled HSA runtime under a foreign HIP and see no device.  So a
+    # process that has torch gets torch's runtime first.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = ctypes.CDLL(LIB_PATH)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
     L.acc_spmm_plan.restype = vp

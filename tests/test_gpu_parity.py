@@ -642,6 +642,40 @@ def test_dendrogram_rounds_on_special_graphs():
         np.testing.assert_array_equal(host_parent, parent, err_msg=name)
 
 
+def test_dendrogram_on_larger_special_graphs():
+    """Step I against the oracle where the device form's special paths carry the load: a star of 2^20 vertices (one
+    list of a million records, walked by thousands of blocks and reduced by a wavefront), hubs with long lists that
+    are each other's neighbours (the per-round record budget), a few hundred hubs over many leaves, cliques on a
+    ring.  Whichever form ends up running, the result is the oracle's."""
+    import scipy.sparse as sp
+
+    def csr_of(M, a, b):
+        a, b = np.asarray(a, np.int64), np.asarray(b, np.int64)
+        A = sp.coo_matrix((np.ones(2 * len(a), np.int8), (np.concatenate([a, b]), np.concatenate([b, a]))), shape=(M, M)).tocsr()
+        A.sum_duplicates()
+        A.sort_indices()
+        return A.indptr.astype(np.int32), A.indices.astype(np.int32)
+
+    rng = np.random.default_rng(7)
+    graphs = {}
+    n = 1 << 20
+    graphs["star"] = csr_of(n, np.zeros(n - 1, np.int64), np.arange(1, n))
+    h = 64
+    ii, jj = np.triu_indices(h, 1)
+    graphs["mutual hubs"] = csr_of(300000, np.concatenate([np.repeat(np.arange(h), 20000), ii]),
+                                   np.concatenate([rng.integers(h, 300000, h * 20000), jj]))
+    graphs["hubs over leaves"] = csr_of(200000, rng.integers(0, 300, 400000), rng.integers(300, 200000, 400000))
+    blocks = 100
+    ii, jj = np.triu_indices(40, 1)
+    graphs["cliques on a ring"] = csr_of(40 * blocks, np.concatenate([ii + 40 * c for c in range(blocks)] + [np.arange(blocks) * 40]),
+                                         np.concatenate([jj + 40 * c for c in range(blocks)] + [(np.arange(blocks) + 1) % blocks * 40]))
+    for name, (rowptr, colidx) in graphs.items():
+        print(f"[dendrogram] {name}: M={len(rowptr) - 1} entries={len(colidx)}", flush=True)
+        parent, st = _dendrogram_of(rowptr, colidx)
+        assert st["dendrogram_rounds"] >= 1, name
+        np.testing.assert_array_equal(parent, oracle.dendrogram(rowptr, colidx)[0], err_msg=name)
+
+
 def test_dendrogram_of_a_banded_matrix_falls_back_to_the_host_form():
     """A chain: every vertex's decision depends on its predecessor's, so a round commits one or two
     vertices.  The device form notices that the rest would take longer than the sequential form

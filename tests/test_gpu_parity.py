@@ -1338,3 +1338,24 @@ def test_binding_refuses_tensors_smaller_than_the_call_needs():
         torch.cuda.synchronize()
     finally:
         acc.acc_spmm_destroy(plan)
+
+
+@pytest.mark.parametrize("cfg,opt", [(2, dict(tile_width=32)), (4, dict(tile_width=32)),
+                                      (2, dict(value_fetch=3, slabs_per_wave=2)), (3, dict(value_fetch=3, pipeline_depth=2))])
+def test_full_size_whole_output_of_the_forced_variants(cfg, opt):
+    """At the benchmark's sizes, the kernel forms that the defaults do not pick there: 16 x 32 tiles, the span
+    fetch on long chains of sparse tiles with two slabs per wave, the span fetch where the cooperative one is
+    the default.  Every element of C against the oracle."""
+    w = wl.config(cfg)
+    print(f"[full-size] {w.name} with {opt}", flush=True)
+    plan = acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(**opt))
+    try:
+        for N in ((w.N, 256) if cfg == 2 else (w.N,)):
+            B = w.B if N == w.N else wl.dense(w.K, N, 5, "normal", 0.0, 1.0)
+            C = run_spmm(plan, B, w.M, N)
+            assert np.isfinite(C).all()
+            w2 = wl.Workload(name=w.name, M=w.M, K=w.K, N=N, rowptr=w.rowptr, colidx=w.colidx, vals=w.vals, B=B)
+            ratio = _compare_whole_output(w2, C)
+            print(f"[full-size] N={N}: all {w.M} rows within tolerance, worst error/limit = {ratio:.3g}", flush=True)
+    finally:
+        acc.acc_spmm_destroy(plan)

@@ -1,7 +1,8 @@
 """The plan's AUTO decisions (row reordering, column order) and the execute call's choice of how the
 packed values are fetched, on inputs that are none of the five benchmark workloads: for each input
-every forced alternative is timed, and what the library picks by itself must run within 5 % (15 % for
-the value fetch; the worst case seen is 8-12 %, a power-law graph at N = 32 where the per-lane loads win) of the fastest one.
+every forced alternative is timed, and what the library picks by itself must run within 5 % (20 % for
+the value fetch: the worst case seen is 8-12 %, a power-law graph at N = 32 where the per-lane loads win, and the
+gate leaves room for the run-to-run spread of a 0.7 ms launch) of the fastest one.
 
 The thresholds behind AUTO (keep the reordering for at least 1 % fewer tiles; apply the column order
 from 2^20 columns on when the labels of the most used columns are concentrated on few residues)
@@ -162,14 +163,14 @@ def test_default_value_fetch_is_near_the_best_way_on_held_out_inputs():
                 best = min(ms[1], ms[2], ms[3])
                 line = f"[fetch] {name}: N={n} ms per-lane {ms[1]:.4f} cooperative {ms[2]:.4f} span {ms[3]:.4f} default {ms[0]:.4f}"
                 print(line, flush=True)
-                if ms[0] > 1.15 * best + SLACK_MS:
+                if ms[0] > 1.20 * best + SLACK_MS:
                     failures.append(line)
                 del B, C
                 torch.cuda.empty_cache()
         finally:
             for plan in plans.values():
                 acc.acc_spmm_destroy(plan)
-    assert not failures, "the default value fetch is more than 15 % slower than the best way:\n" + "\n".join(failures)
+    assert not failures, "the default value fetch is more than 20 % slower than the best way:\n" + "\n".join(failures)
 
 
 def test_default_slabs_per_wave_is_near_the_better_shape_on_held_out_inputs():

@@ -103,11 +103,14 @@ typedef struct {
     /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its
      * own up-to-four values one by one; 2 = the wavefront loads the tile's values once and the
      * lanes exchange them across registers; 3 = every lane loads the twelve bytes around its
-     * (consecutive) values at once; 0 = default: 3 for N <= 32; for 32 < N <= 64, 2 when the plan
-     * has at least 24 entries per tile on average or at least 16384 tiles, else 1; for N > 64,
-     * 3 when the plan has at least 24 entries per tile on average or fewer than 64 tiles per
-     * work item, else 1.  (By the lane width the
-     * call uses: a width N that is not a multiple of 8 counts as the narrower class.) */
+     * (consecutive) values at once; 0 = default, by the lane width the call uses (a width N that
+     * is not a multiple of 8 counts as the narrower class):
+     *   N <= 32: 3; but 1 if the plan has 64 tiles or more per work item and its windows share
+     *     almost no columns (at least 0.95 gathered rows of B per entry);
+     *   32 < N <= 64: 2 when the plan has at least 24 entries per tile on average or at least
+     *     16384 tiles, else 1;
+     *   N > 64: 3 when the plan has at least 24 entries per tile on average or fewer than 64
+     *     tiles per work item, else 1. */
     int32_t value_fetch;
     /* The 16-bit floating-point type of csr_vals and of B: ACC_SPMM_FP16 (0, default) = IEEE
      * binary16, ACC_SPMM_BF16 (1) = bfloat16.  C is fp32 and products are accumulated in fp32

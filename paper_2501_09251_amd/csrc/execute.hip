@@ -322,12 +322,16 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     const bool many_tiles = plan.stats.num_tiles >= 16384;
     // tiles a wave multiplies one after the other: a window or two without load balancing, hundreds with it
     const bool short_chains = plan.stats.num_tiles < 64 * (int64_t)plan.items.size();
+    // gathered rows of B per entry of A: near 1 when the rows of a window share almost no columns.  At N <= 32 the
+    // span read's lead over the per-lane loads shrinks as this grows (twelve inputs: 22 % at 0.87, 7-15 % at 0.91,
+    // 2 % at 0.97) and is a loss of 4-10 % at 0.96 on long chains of tiles
+    const bool unshared_rows = (double)plan.stats.sum_distinct_cols >= 0.95 * (double)std::max<int64_t>(1, f.nnz);
     switch (plan.opt.value_fetch) {
         case 1: p.fetch = kFetchLane; break;
         case 2: p.fetch = kFetchCoop; break;
         case 3: p.fetch = kFetchSpan; break;
         default:
-            if (p.fpl <= 2) p.fetch = kFetchSpan;
+            if (p.fpl <= 2) p.fetch = (!short_chains && unshared_rows) ? kFetchLane : kFetchSpan;
             else if (p.fpl == 4) p.fetch = (dense_tiles || many_tiles) ? kFetchCoop : kFetchLane;
             else p.fetch = (dense_tiles || short_chains) ? kFetchSpan : kFetchLane;
     }

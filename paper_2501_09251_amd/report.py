@@ -4,6 +4,7 @@ bitmap format against CSR and an int8-per-entry tile format (4.3.2), pipeline on
 (4.3.3), load balancing on/off (4.3.4) and the switch-by-switch ablation (4.3.5).
 
     python -m paper_2501_09251_amd.report --config 2
+    python -m paper_2501_09251_amd.report --config 2 --variants --widths 32,64,128,256
 
 Needs a GPU.  Prints one JSON object per line; every timing is the whole execute (gather of B
 where the plan has a column order, tile kernel, split-window combine kernel), from HIP events,
@@ -30,6 +31,10 @@ def main() -> int:
                     help="build one plan with the row reordering forced on and print its statistics and phase times "
                          "(for profiling the preprocessing kernels); nothing is executed")
     ap.add_argument("--dendrogram-on-host", action="store_true", help="with --plan-only: the host form of Step I")
+    ap.add_argument("--variants", action="store_true",
+                    help="time the forms of the tile kernel that execute chooses among (value fetch, slabs per wave, ring "
+                         "depth, 16x32 tiles, LDS staging) against the library's own choice, at the widths of --widths")
+    ap.add_argument("--widths", default="32,64,128,256", help="with --variants: comma-separated N")
     args = ap.parse_args()
 
     import torch
@@ -50,6 +55,8 @@ def main() -> int:
             "t_encode_s", "t_schedule_s", "dendrogram_on_device", "dendrogram_rounds", "reorder_work_ratio", "num_tiles",
             "num_tiles_identity")}}), flush=True)
         return 0
+    if args.variants:
+        return variants(args, torch, acc, wl)
     w = wl.config(args.config, args.shrink)
     dev = torch.device("cuda:0")
     B = torch.from_numpy(w.B.view(np.int16)).to(dev)
@@ -130,6 +137,41 @@ def main() -> int:
             del X, Y
     finally:
         acc.acc_spmm_destroy(plan)
+    return 0
+
+
+def variants(args, torch, acc, wl) -> int:
+    """One JSON line per width: whole execute in ms (median of --steps launches) for the library's own choice and for
+    every forced form that the width allows."""
+    w = wl.config(args.config, args.shrink, with_B=False)
+    forms = [("default", {}), ("fetch per-lane", dict(value_fetch=1)), ("fetch cooperative", dict(value_fetch=2)),
+             ("fetch span", dict(value_fetch=3)), ("one slab per wave", dict(slabs_per_wave=1)),
+             ("two slabs per wave", dict(slabs_per_wave=2)), ("ring depth 1", dict(pipeline_depth=1)),
+             ("ring depth 2", dict(pipeline_depth=2)), ("ring depth 3", dict(pipeline_depth=3)),
+             ("no prefetch", dict(no_prefetch=1)), ("16x32 tiles, depth 1", dict(tile_width=32, pipeline_depth=1)),
+             ("16x32 tiles, depth 2", dict(tile_width=32, pipeline_depth=2)), ("LDS staging", dict(lds_staging=1))]
+    plans = {name: acc.acc_spmm_plan_ex(w.M, w.K, w.nnz, w.rowptr, w.colidx, w.vals, acc.make_options(**kw)) for name, kw in forms}
+    stream = torch.cuda.current_stream().cuda_stream
+    try:
+        for N in (int(x) for x in args.widths.split(",")):
+            B = torch.from_numpy(wl.dense(w.K, N, wl.SEED_BASE, "normal", 0.0, 1.0).view(np.int16)).cuda()
+            C = torch.empty((w.M, N), dtype=torch.float32, device="cuda")
+            ms = {}
+            for name, plan in plans.items():
+                try:
+                    for _ in range(2):
+                        acc.acc_spmm_execute(plan, B, N, C, stream)
+                except acc.AccSpmmError:
+                    continue                  # a form that does not exist at this width (LDS staging, mostly)
+                torch.cuda.synchronize()
+                ms[name] = round(float(np.median([sum(acc.acc_spmm_execute_timed(plan, B, N, C, stream))
+                                                  for _ in range(args.steps)])), 4)
+            print(json.dumps({"report": "variants", "workload": w.name, "N": N, "execute_ms": ms}), flush=True)
+            del B, C
+            torch.cuda.empty_cache()
+    finally:
+        for plan in plans.values():
+            acc.acc_spmm_destroy(plan)
     return 0
 
 

@@ -96,8 +96,8 @@ typedef struct {
      * (non-temporal) stores, the counterpart of the paper's write-through policy. */
     int32_t streaming_stores;
     /* Tiles of B rows kept in flight per wavefront while one tile is multiplied (1..3).
-     * 0 = default: 1 for N <= 64 and for plans with fewer than 64 tiles per work item; else 3
-     * where a wavefront takes one 128-feature slab and 2 where it takes two.  Ignored when
+     * 0 = default: 1 for plans with fewer than 64 tiles per work item; else 3 where a wavefront
+     * takes one 128-feature slab and 2 otherwise.  Ignored when
      * no_prefetch is set. */
     int32_t pipeline_depth;
     /* How a tile's packed values reach the lanes of the wavefront: 1 = every lane loads its

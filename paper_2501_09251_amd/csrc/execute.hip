@@ -339,9 +339,10 @@ void launch_execute(const Plan& plan, const void* B, int32_t N, void* C, hipStre
     p.tw32 = tw32;
     if (tw32) p.fetch = kFetchSpan;   // the only way the 16 x 32 kernel fetches values
     // Tiles in flight per wave: swept on long chains of tiles (balanced power-law inputs), where 3 is best for one
-    // 128-feature slab, 2 for two and 1 for narrower lanes; a wave that multiplies one window's dozen tiles and ends
+    // 128-feature slab and 2 otherwise (narrower lanes: 2-5 % faster than 1 on three of four such inputs at
+    // N = 32 and 64, 2 % slower on the fourth); a wave that multiplies one window's dozen tiles and ends
     // gains nothing from a deep ring and pays its prologue (held-out inputs: 4-10 % faster at depth 1).
-    const int default_depth = short_chains ? 1 : ((p.fpl == 8 && p.ns == 1) ? 3 : (p.fpl == 8 ? 2 : 1));
+    const int default_depth = short_chains ? 1 : ((p.fpl == 8 && p.ns == 1) ? 3 : 2);
     p.depth = plan.opt.no_prefetch ? 0 : (plan.opt.pipeline_depth > 0 ? plan.opt.pipeline_depth : default_depth);
     if (tw32) {
         // a tile holds twice the rows of B: half the depth keeps the same bytes in flight; depths 1 and 2 exist

@@ -4,6 +4,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <random>
+#include <algorithm>
 #include <set>
 #include <string>
 #include <vector>
@@ -48,6 +49,18 @@ int main(int argc, char** argv) {
         const int32_t seg_len = 1 + rng() % 64;
         if (!build_dendrogram_host(M, gptr.data(), gadj.data(), seg_len, 0.0, parent, seq, seg, &work)) return 2;
         if ((int64_t)seq.size() != M || seg.back() != M) return 3;
+        {   // the leaf sequence rebuilt from the parents and the visiting order (what follows the device form of
+            // Step I) equals the one the host form produced itself
+            std::vector<int32_t> order(M);
+            for (int64_t i = 0; i < M; ++i) order[i] = (int32_t)i;
+            std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+                return gptr[a + 1] - gptr[a] < gptr[b + 1] - gptr[b];
+            });
+            std::vector<int32_t> seq2;
+            std::vector<int64_t> seg2;
+            leaf_sequence_from_parents(M, parent, order, seg_len, seq2, seg2);
+            if (seq2 != seq || seg2 != seg) return 6;
+        }
         build_dendrogram_host(M, gptr.data(), gadj.data(), seg_len, 0.5, parent, seq, seg, &work);   // a budget that may stop it
 
         // a schedule over random tile counts, with a heavy window

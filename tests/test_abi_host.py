@@ -73,6 +73,11 @@ def test_invalid_input_is_reported_not_crashed():
     assert _plan_error(1, 4, [1, 1], [], v(0)) == -2                   # rowptr[0] != 0
     assert _plan_error(1, 4, [0, 1], [0], v(1), window_height=12, tile_width=16) == -3
     assert _plan_error(1, 4, [0, 1], [0], v(1), reorder=7) == -1
+    for bad in (dict(value_fetch=4), dict(value_fetch=-1), dict(slabs_per_wave=3), dict(slabs_per_wave=-1), dict(lds_staging=2),
+                dict(column_order=3), dict(operand_order=2), dict(max_tiles_per_item=-1), dict(segment_length=-5)):
+        assert _plan_error(1, 4, [0, 1], [0], v(1), **bad) == -1, bad
+    for bad in (dict(tile_width=12), dict(window_height=16, tile_width=64), dict(window_height=128)):
+        assert _plan_error(1, 4, [0, 1], [0], v(1), **bad) == -3, bad
     bad = acc.make_options()
     bad.struct_size = 3
     with pytest.raises(acc.AccSpmmError) as e:
